@@ -1,0 +1,152 @@
+/*
+ * C ABI of the MI355X CKKS ciphertext x plaintext matmul library (libckks_hip.so).
+ *
+ * Scope: the server side of the projection kernel Y = XW of the paper's
+ * Sec. 3.2 / App. A.2 (segment-column packing, baby-step/giant-step diagonal
+ * method) and the CKKS machinery it stands on: RNS arithmetic over
+ * R_Q = Z_Q[X]/(X^N+1) (Sec. 2.2), the primitives add / ptmul / rot / conj of
+ * Table 1, and rescale (Sec. 2.2).  The server holds evaluation keys and the
+ * model, never the secret key (Sec. 2.3, "Key Distribution"); the ckks_client_*
+ * calls at the end are the key holder's side and exist so that callers can
+ * produce keys and ciphertexts without any other library.
+ *
+ * Conventions
+ *  - Every call returns 0 (CKKS_OK) or a negative CKKS_E_* code; the message of
+ *    the last failure on the calling thread is ckks_last_error().  No call
+ *    aborts or throws across this boundary.
+ *  - "d_" pointers are DEVICE pointers (HIP, current device); all others are
+ *    HOST pointers.  The caller owns every buffer it passes.  Handles returned
+ *    by *_create / *_load are owned by the library until the matching *_destroy.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Compute calls enqueue work on it and return without synchronising; the
+ *    library's scratch memory is private to a params handle, so calls on one
+ *    handle must be issued on one stream at a time.
+ *  - Residues are uint64 in [0, q_i), little endian.  A ciphertext at level l is
+ *    [component 2][limb l][N], component 0 = c0, 1 = c1, in the NTT domain:
+ *    entry k of a limb is the polynomial evaluated at psi^(2*bitrev(k)+1), psi the
+ *    smallest positive 2N-th primitive root of that limb's prime.  Size
+ *    2*N*l*8 bytes, the ct_bytes(N, L) of the paper's Eq. in Sec. 5.2.
+ *  - Limb ids: 0..L-1 are the ciphertext primes q_i, L..L+K-1 the special primes.
+ */
+#ifndef CKKS_H
+#define CKKS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CKKS_OK 0
+#define CKKS_E_INVAL (-1) /* bad argument: null pointer, size, non-prime, ... */
+#define CKKS_E_LEVEL (-2) /* level out of range for the operation */
+#define CKKS_E_NOKEY (-3) /* a non-identity Galois element without a key */
+#define CKKS_E_NOMEM (-4) /* device or host allocation failed */
+#define CKKS_E_HIP (-5)   /* a HIP runtime call failed */
+
+#define CKKS_STEP_CONJ INT32_MIN /* "step" meaning complex conjugation (Table 1, conj) */
+
+typedef struct ckks_params ckks_params_t;
+typedef struct ckks_gkey ckks_gkey_t;
+typedef struct ckks_weights ckks_weights_t;
+
+/* Operation counts of one ckks_ctpt_matmul call (App. A.2.2 counts key switches). */
+typedef struct {
+    uint64_t key_switches; /* rotations that needed a key */
+    uint64_t ptmuls;       /* ciphertext x plaintext products */
+    uint64_t limb_ntts;    /* forward + inverse limb transforms */
+} ckks_counters_t;
+
+const char *ckks_last_error(void);
+
+/* Prime search used by the benchmark configurations: the first `count` primes
+ * among 2^bits - k*2N + 1, k = 1, 2, ... (all are 1 mod 2N).  out: host, count
+ * entries.  CKKS_E_INVAL if bits > 61 or the range is exhausted. */
+int ckks_find_primes(uint32_t bits, uint32_t logN, uint32_t count, uint64_t *out);
+
+/* Parameter set (Sec. 2.2): ring degree N = 2^logN (10 <= logN <= 17), ciphertext
+ * primes q[0..L-1] (q[0] = base), special primes p[0..K-1] (K = 0 allowed: no key
+ * switching), dnum digits of alpha = L/dnum limbs for hybrid key switching.
+ * Validates: primes distinct, prime, < 2^62, 1 mod 2N; L % dnum == 0; L+K <= 64;
+ * alpha, K <= 16.  Builds twiddle and base-conversion tables on the current
+ * device. */
+int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint64_t *p, uint32_t K,
+                       uint32_t dnum, ckks_params_t **out);
+void ckks_params_destroy(ckks_params_t *params);
+
+/* psi of limb `limb` (host out): the root that fixes the NTT-domain bits. */
+int ckks_params_root(const ckks_params_t *params, uint32_t limb, uint64_t *psi);
+
+/* Negacyclic NTT / inverse NTT in place on d_data [batch][n_limbs][N]; row
+ * (b, i) is a polynomial modulo limb limb_ids[i] (host array, n_limbs <= 64).
+ * Forward: natural coefficient order in, bit-reversed evaluation order out
+ * (out[k] = a(psi^(2*bitrev(k)+1))).  Inverse undoes it, including 1/N. */
+int ckks_ntt(const ckks_params_t *params, uint64_t *d_data, const uint32_t *limb_ids, uint32_t n_limbs,
+             uint32_t batch, void *stream);
+int ckks_intt(const ckks_params_t *params, uint64_t *d_data, const uint32_t *limb_ids, uint32_t n_limbs,
+              uint32_t batch, void *stream);
+
+/* Galois element of a slot rotation: rot by `step` is the cyclic LEFT shift of
+ * the n = N/2 slots (Sec. 3.1): 5^(step mod n) mod 2N; CKKS_STEP_CONJ -> 2N-1. */
+int ckks_galois_elt(const ckks_params_t *params, int32_t step, uint64_t *galois_elt);
+
+/* Evaluation key for one Galois element (the "Galois keys" of Sec. 2.1).
+ * d_key: [dnum][2][L+K][N], NTT domain, canonical residues; component 0 = b_j,
+ * 1 = a_j with b_j = -a_j*s + e_j + P*T_j*sigma_g(s).  The library keeps its own
+ * copy (Montgomery form); d_key may be freed once `stream` has drained. */
+int ckks_galois_key_load(const ckks_params_t *params, uint64_t galois_elt, const uint64_t *d_key,
+                         void *stream, ckks_gkey_t **out);
+void ckks_galois_key_destroy(ckks_gkey_t *key);
+
+/* rot / conj of Table 1 for many steps of ONE ciphertext (the rotation banks
+ * of Sec. 3.2/3.3 share their input): INTT(c1), digit decomposition and ModUp
+ * are done once, then per step: automorphism, inner product with the key,
+ * ModDown, + sigma(c0).  d_ct_in [2][level][N]; steps (host) as in
+ * ckks_galois_elt; keys (host array of n_steps handles, in step order; an entry
+ * may be NULL only if its step is the identity, which is copied); d_ct_out
+ * [n_steps][2][level][N].  Errors: CKKS_E_LEVEL (level 0 or > L), CKKS_E_NOKEY,
+ * CKKS_E_INVAL (key of another element, K = 0). */
+int ckks_rotate_hoisted(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level, const int32_t *steps,
+                        uint32_t n_steps, const ckks_gkey_t *const *keys, uint64_t *d_ct_out, void *stream);
+
+/* Plaintext weights of one projection Y = XW (Sec. 3.2, App. A.2.1) at `level`:
+ * segment length m, C columns per ciphertext (C divides N/2/m; the C columns
+ * repeat over all segments), G input groups, B_out output blocks, N1 baby steps
+ * (N1 divides C, N2 = C/N1).  Diagonals are handed over as encoded integer
+ * coefficient polynomials and expanded here to `level` limbs in the NTT domain
+ * (offline step, not part of the matmul latency).  Diagonal (b, p, g, q) has
+ * index ((b*N2 + p)*G + g)*N1 + q; its slot vector holds
+ * W[g*C + (c+q) mod C, b*C + (c - p*N1) mod C] in every slot of segment c. */
+int ckks_weights_create(const ckks_params_t *params, uint32_t level, uint32_t m, uint32_t C, uint32_t G,
+                        uint32_t B_out, uint32_t N1, ckks_weights_t **out);
+/* d_coeffs: int64 [count][N] for diagonals first .. first+count-1. */
+int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count, const int64_t *d_coeffs,
+                               void *stream);
+/* d_bias_coeffs: int64 [B_out][N]; the plaintext added to c0 of block b is
+ * bias_coeffs[b] * bias_mul (an integer factor that lifts the bias encoding to
+ * the product scale). */
+int ckks_weights_set_bias(ckks_weights_t *w, const int64_t *d_bias_coeffs, uint64_t bias_mul, void *stream);
+void ckks_weights_destroy(ckks_weights_t *w);
+
+/* Y = XW + bias on ciphertexts (Sec. 3.2 with real packing):
+ *   bank x_q^(g) = rot(x^(g); q*m), q < N1 (hoisted, one call per input);
+ *   acc_{b,p} = sum_g sum_q x_q^(g) (.) w_{b,p,g,q};
+ *   y_b = acc_{b,0} + sum_{p>=1} rot(acc_{b,p}; p*N1*m) + bias_b.
+ * d_ct_x [G][2][level][N]; baby_keys: N1-1 handles for steps q*m (q = 1..);
+ * giant_keys: N2-1 handles for steps p*N1*m; d_ct_y [B_out][2][level][N] at the
+ * input level and scale(x)*scale(w) -- follow with ckks_rescale.  counters
+ * (host, may be NULL) receives the operation counts. */
+int ckks_ctpt_matmul(ckks_params_t *params, const ckks_weights_t *w, const uint64_t *d_ct_x,
+                     const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys,
+                     uint64_t *d_ct_y, ckks_counters_t *counters, void *stream);
+
+/* rescale (Sec. 2.2): drops limb level_in-1 and divides by its prime with
+ * centred rounding.  d_ct_in [n_ct][2][level_in][N] -> d_ct_out
+ * [n_ct][2][level_in-1][N].  CKKS_E_LEVEL if level_in < 2 or > L. */
+int ckks_rescale(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct,
+                 uint64_t *d_ct_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKKS_H */

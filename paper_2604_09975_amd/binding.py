@@ -1,0 +1,224 @@
+"""ctypes binding of libckks_hip.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see include/ckks.h).
+Device buffers are torch tensors on the current HIP device (dtype int64 used as
+raw 64-bit storage for uint64 residues); the stream is torch's current stream.
+The library is loaded at import and the import fails loudly if it is missing:
+there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libckks_hip.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2604_09975_amd.build` (hipcc, gfx950)")
+lib = C.CDLL(LIB_PATH)
+
+STEP_CONJ = -(2 ** 31)
+_u64p, _u32p, _i32p, _vp = C.POINTER(C.c_uint64), C.POINTER(C.c_uint32), C.POINTER(C.c_int32), C.c_void_p
+
+
+class Counters(C.Structure):
+    _fields_ = [("key_switches", C.c_uint64), ("ptmuls", C.c_uint64), ("limb_ntts", C.c_uint64)]
+
+
+class CkksError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"ckks error {code}: {msg}")
+        self.code = code
+
+
+lib.ckks_last_error.restype = C.c_char_p
+_SIGS = {
+    "ckks_find_primes": [C.c_uint32, C.c_uint32, C.c_uint32, _u64p],
+    "ckks_params_create": [C.c_uint32, _u64p, C.c_uint32, _u64p, C.c_uint32, C.c_uint32, C.POINTER(_vp)],
+    "ckks_params_root": [_vp, C.c_uint32, _u64p],
+    "ckks_ntt": [_vp, _vp, _u32p, C.c_uint32, C.c_uint32, _vp],
+    "ckks_intt": [_vp, _vp, _u32p, C.c_uint32, C.c_uint32, _vp],
+    "ckks_galois_elt": [_vp, C.c_int32, _u64p],
+    "ckks_galois_key_load": [_vp, C.c_uint64, _vp, _vp, C.POINTER(_vp)],
+    "ckks_rotate_hoisted": [_vp, _vp, C.c_uint32, _i32p, C.c_uint32, C.POINTER(_vp), _vp, _vp],
+    "ckks_weights_create": [_vp] + [C.c_uint32] * 6 + [C.POINTER(_vp)],
+    "ckks_weights_set_diagonals": [_vp, C.c_uint32, C.c_uint32, _vp, _vp],
+    "ckks_weights_set_bias": [_vp, _vp, C.c_uint64, _vp],
+    "ckks_ctpt_matmul": [_vp, _vp, _vp, C.POINTER(_vp), C.POINTER(_vp), _vp, C.POINTER(Counters), _vp],
+    "ckks_rescale": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
+}
+for _n, _a in _SIGS.items():
+    getattr(lib, _n).argtypes = _a
+    getattr(lib, _n).restype = C.c_int
+for _n in ("ckks_params_destroy", "ckks_galois_key_destroy", "ckks_weights_destroy"):
+    getattr(lib, _n).argtypes = [_vp]
+    getattr(lib, _n).restype = None
+
+
+def _check(rc):
+    if rc != 0:
+        raise CkksError(rc, lib.ckks_last_error().decode())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.element_size() == 8):
+        raise TypeError("expected a contiguous 64-bit device tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def _u64arr(v):
+    return (C.c_uint64 * max(len(v), 1))(*[int(x) for x in v])
+
+
+def ckks_find_primes(bits, logN, count):
+    out = (C.c_uint64 * count)()
+    _check(lib.ckks_find_primes(bits, logN, count, out))
+    return [int(x) for x in out]
+
+
+class Handle:
+    """Owns one library handle and destroys it once."""
+    _destroy = None
+
+    def __init__(self, h):
+        self.h = h
+
+    def close(self):
+        if self.h:
+            getattr(lib, self._destroy)(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Params(Handle):
+    _destroy = "ckks_params_destroy"
+
+
+class GaloisKey(Handle):
+    _destroy = "ckks_galois_key_destroy"
+
+
+class Weights(Handle):
+    _destroy = "ckks_weights_destroy"
+
+
+def ckks_params_create(logN, q, p, dnum):
+    h = _vp()
+    _check(lib.ckks_params_create(logN, _u64arr(q), len(q), _u64arr(p), len(p), dnum, C.byref(h)))
+    P = Params(h)
+    P.logN, P.N, P.L, P.K, P.dnum = logN, 1 << logN, len(q), len(p), dnum
+    P.q, P.p = [int(x) for x in q], [int(x) for x in p]
+    return P
+
+
+def ckks_params_root(P, limb):
+    out = C.c_uint64()
+    _check(lib.ckks_params_root(P.h, limb, C.byref(out)))
+    return int(out.value)
+
+
+def _ntt(fn, P, d_data, limb_ids, batch):
+    ids = (C.c_uint32 * max(len(limb_ids), 1))(*[int(x) for x in limb_ids])
+    if d_data.numel() != batch * len(limb_ids) * P.N:
+        raise ValueError("tensor size does not match batch * n_limbs * N")
+    _check(fn(P.h, _dev(d_data), ids, len(limb_ids), batch, _stream()))
+    return d_data
+
+
+def ckks_ntt(P, d_data, limb_ids, batch):
+    return _ntt(lib.ckks_ntt, P, d_data, limb_ids, batch)
+
+
+def ckks_intt(P, d_data, limb_ids, batch):
+    return _ntt(lib.ckks_intt, P, d_data, limb_ids, batch)
+
+
+def ckks_galois_elt(P, step):
+    out = C.c_uint64()
+    _check(lib.ckks_galois_elt(P.h, STEP_CONJ if step == "conj" else int(step), C.byref(out)))
+    return int(out.value)
+
+
+def ckks_galois_key_load(P, galois_elt, d_key):
+    if d_key.numel() != P.dnum * 2 * (P.L + P.K) * P.N:
+        raise ValueError("key tensor must be [dnum][2][L+K][N]")
+    h = _vp()
+    _check(lib.ckks_galois_key_load(P.h, galois_elt, _dev(d_key), _stream(), C.byref(h)))
+    k = GaloisKey(h)
+    k.galois_elt = galois_elt
+    return k
+
+
+def _keyarr(keys):
+    arr = (_vp * max(len(keys), 1))()
+    for i, k in enumerate(keys):
+        arr[i] = k.h if k is not None else None
+    return arr
+
+
+def ckks_rotate_hoisted(P, d_ct_in, level, steps, keys, d_ct_out=None):
+    n = len(steps)
+    if d_ct_in.numel() != 2 * level * P.N:
+        raise ValueError("ciphertext must be [2][level][N]")
+    if d_ct_out is None:
+        d_ct_out = torch.empty((n, 2, level, P.N), dtype=torch.int64, device=d_ct_in.device)
+    elif d_ct_out.numel() != n * 2 * level * P.N:
+        raise ValueError("output must be [n_steps][2][level][N]")
+    st = (C.c_int32 * max(n, 1))(*[STEP_CONJ if s == "conj" else int(s) for s in steps])
+    _check(lib.ckks_rotate_hoisted(P.h, _dev(d_ct_in), level, st, n, _keyarr(keys), _dev(d_ct_out), _stream()))
+    return d_ct_out
+
+
+def ckks_weights_create(P, level, m, Cc, G, B_out, N1):
+    h = _vp()
+    _check(lib.ckks_weights_create(P.h, level, m, Cc, G, B_out, N1, C.byref(h)))
+    w = Weights(h)
+    w.level, w.m, w.C, w.G, w.B_out, w.N1, w.N2 = level, m, Cc, G, B_out, N1, Cc // N1
+    w.N = P.N
+    return w
+
+
+def ckks_weights_set_diagonals(w, first, d_coeffs):
+    count = d_coeffs.numel() // w.N
+    if d_coeffs.numel() != count * w.N:
+        raise ValueError("coefficients must be [count][N]")
+    _check(lib.ckks_weights_set_diagonals(w.h, first, count, _dev(d_coeffs), _stream()))
+
+
+def ckks_weights_set_bias(w, d_bias_coeffs, bias_mul):
+    if d_bias_coeffs.numel() != w.B_out * w.N:
+        raise ValueError("bias coefficients must be [B_out][N]")
+    _check(lib.ckks_weights_set_bias(w.h, _dev(d_bias_coeffs), int(bias_mul), _stream()))
+
+
+def ckks_ctpt_matmul(P, w, d_ct_x, baby_keys, giant_keys, d_ct_y=None):
+    if d_ct_x.numel() != w.G * 2 * w.level * P.N:
+        raise ValueError("input must be [G][2][level][N]")
+    if len(baby_keys) != w.N1 - 1 or len(giant_keys) != w.N2 - 1:
+        raise ValueError("need N1-1 baby keys and N2-1 giant keys")
+    if d_ct_y is None:
+        d_ct_y = torch.empty((w.B_out, 2, w.level, P.N), dtype=torch.int64, device=d_ct_x.device)
+    elif d_ct_y.numel() != w.B_out * 2 * w.level * P.N:
+        raise ValueError("output must be [B_out][2][level][N]")
+    cnt = Counters()
+    _check(lib.ckks_ctpt_matmul(P.h, w.h, _dev(d_ct_x), _keyarr(baby_keys), _keyarr(giant_keys), _dev(d_ct_y),
+                                C.byref(cnt), _stream()))
+    return d_ct_y, cnt
+
+
+def ckks_rescale(P, d_ct_in, level_in, n_ct, d_ct_out=None):
+    if d_ct_in.numel() != n_ct * 2 * level_in * P.N:
+        raise ValueError("input must be [n_ct][2][level][N]")
+    if d_ct_out is None:
+        d_ct_out = torch.empty((n_ct, 2, max(level_in - 1, 1), P.N), dtype=torch.int64, device=d_ct_in.device)
+    _check(lib.ckks_rescale(P.h, _dev(d_ct_in), level_in, n_ct, _dev(d_ct_out), _stream()))
+    return d_ct_out

@@ -1,0 +1,109 @@
+// Internal declarations shared by the library's translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/ckks.h"
+#include "modarith.h"
+
+namespace ckks {
+
+constexpr u32 MAX_LIMBS = 64;     // L + K
+constexpr u32 MAX_DIGIT = 16;     // alpha and K
+constexpr u32 ROT_BATCH = 16;     // key switches in flight per kernel wave
+constexpr u32 SKIP_ROW = 255;     // limb id meaning "leave this row alone"
+
+constexpr u32 MAX_ROW_IDS = 128;  // rows described by one LimbIds pattern
+
+// limb id of each row of a [batch][n][N] array, row index taken modulo n
+struct LimbIds {
+    uint8_t id[MAX_ROW_IDS];
+};
+
+void set_error(const char *fmt, ...);
+int hip_fail(hipError_t e, const char *what);
+
+#define CKKS_HIP(call)                                        \
+    do {                                                      \
+        hipError_t e_ = (call);                               \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);     \
+    } while (0)
+
+#define CKKS_LAUNCH_CHECK(name)                               \
+    do {                                                      \
+        hipError_t e_ = hipGetLastError();                    \
+        if (e_ != hipSuccess) return hip_fail(e_, name);      \
+    } while (0)
+
+// Base-conversion tables of one level (digits depend on the level only through
+// the last, possibly partial, digit).
+struct LevelTables {
+    u32 level = 0, beta = 0;
+    u64 *d_up_inv = nullptr;   // [level]: ((Q_D/q_i)^-1 mod q_i), Montgomery form, D = digit of i
+    u64 *d_up_mat = nullptr;   // [level][level+K]: (Q_D/q_i mod t), Montgomery form w.r.t. t; 0 for t in D
+};
+
+}  // namespace ckks
+
+struct ckks_params {
+    ckks::u32 logN = 0, N = 0, L = 0, K = 0, dnum = 0, alpha = 0, W = 0;
+    int device = 0;
+    std::vector<ckks::u64> mod, psi;
+    std::vector<ckks::ModConst> hmod;
+    ckks::ModConst *d_mod = nullptr;   // [W]
+    ckks::u64 *d_tw_fwd = nullptr;     // [W][N]: psi^bitrev(idx), Montgomery form, idx in [1, N)
+    ckks::u64 *d_tw_inv = nullptr;     // [W][N]: psi^-bitrev(idx), Montgomery form
+    ckks::u64 *d_ninv = nullptr;       // [W][2]: N^-1 and N^-1 * psi^-(N/2), Montgomery form
+    // ModDown tables (independent of the level)
+    ckks::u64 *d_dn_inv = nullptr;     // [K]: (P/p_k)^-1 mod p_k
+    ckks::u64 *d_dn_mat = nullptr;     // [K][L]: P/p_k mod q_i
+    ckks::u64 *d_pinv = nullptr;       // [L]: P^-1 mod q_i
+    ckks::u64 *d_qlinv = nullptr;      // [L][L]: q_l^-1 mod q_i (rescale), row l
+    std::map<ckks::u32, ckks::LevelTables> levels;
+    // private scratch arena
+    void *d_scratch = nullptr;
+    size_t scratch_bytes = 0;
+
+    mutable uint64_t limb_ntts = 0;    // limb transforms launched so far (for the operation counters)
+
+    int ensure_scratch(size_t bytes, hipStream_t stream);
+    int level_tables(ckks::u32 level, const ckks::LevelTables **out);
+};
+
+struct ckks_gkey {
+    const ckks_params *params = nullptr;
+    ckks::u64 galois_elt = 0;
+    ckks::u64 *d_key = nullptr;        // [dnum][2][L+K][N], Montgomery form
+};
+
+struct ckks_weights {
+    const ckks_params *params = nullptr;
+    ckks::u32 level = 0, m = 0, C = 0, G = 0, B_out = 0, N1 = 0, N2 = 0;
+    ckks::u64 *d_w = nullptr;          // [B_out][N2][G][N1][level][N], NTT domain, Montgomery form
+    ckks::u64 *d_bias = nullptr;       // [B_out][level][N], NTT domain, canonical, times bias_mul; or null
+};
+
+namespace ckks {
+
+// ntt.hip
+int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, bool inverse,
+               hipStream_t stream);
+
+// keyswitch.hip
+struct SwitchItem {
+    const u64 *digits;   // [beta][level+K][N] extended digits of the source c1, NTT domain
+    const u64 *c0;       // [level][N] source c0
+    const u64 *key;      // Montgomery-form key
+    u64 *dst;            // [2][level][N]
+    u64 galois_elt;
+    u32 accumulate;      // add into dst instead of overwriting
+};
+size_t digits_words(const ckks_params *p, u32 level);
+size_t switch_scratch_words(const ckks_params *p, u32 level, u32 n_items);
+int decompose(ckks_params *p, const u64 *d_c1, u32 level, u64 *d_digits, u64 *d_tmp, hipStream_t stream);
+int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream);
+
+}  // namespace ckks

@@ -1,0 +1,330 @@
+// Hybrid key switching for rot / conj (Table 1) with the input-side work hoisted.
+//
+// The paper treats rot and conj as primitives and says nothing about how they
+// are evaluated; this is the standard RNS hybrid method with dnum digits:
+//   decompose:  INTT(c1) -> per digit D_j approximate base conversion of
+//               [c1]_{Q_Dj} to every other active limb and to the special
+//               primes (ModUp) -> NTT.  Done ONCE per ciphertext.
+//   switch:     per Galois element g: u = sum_j sigma_g(d_j) (.) key_j over the
+//               level+K limbs (the automorphism is an index gather in the NTT
+//               domain, fused into the loads) -> INTT of the K special limbs ->
+//               base conversion P -> Q, subtract, times P^-1 (ModDown) ->
+//               + sigma_g(c0).
+// Base conversions use no floating-point correction term; sums of products are
+// accumulated in 128 bits and reduced once.
+#include <algorithm>
+
+#include "ckks_internal.h"
+#include "common_kernels.h"
+
+namespace ckks {
+
+constexpr u32 KS_THREADS = EW_THREADS;
+constexpr u32 UP_CHUNK = 8;    // target limbs per workgroup in ModUp
+constexpr u32 DN_CHUNK = 12;   // target limbs per workgroup in ModDown
+
+__device__ __forceinline__ u32 galois_index(u32 k, u64 g, u32 logN) {
+    // entry k holds the value at psi^(2*bitrev(k)+1); sigma_g reads the value at that exponent times g
+    u32 e = 2u * (__brev(k) >> (32 - logN)) + 1u;
+    u32 e2 = (u32)(((u64)e * g) & ((2ull << logN) - 1));
+    return __brev((e2 - 1u) >> 1) >> (32 - logN);
+}
+
+// y_i = c_i * (Q_D/q_i)^-1 mod q_i for the limbs of digit j, then for every target t outside the digit
+// out_t = sum_i y_i * (Q_D/q_i mod t) mod t.
+__global__ __launch_bounds__(KS_THREADS) void modup_kernel(const u64 *__restrict__ c1_coeff, u64 *__restrict__ digits,
+                                                           const ModConst *__restrict__ mods,
+                                                           const u64 *__restrict__ up_inv,
+                                                           const u64 *__restrict__ up_mat, u32 level, u32 K, u32 L,
+                                                           u32 alpha, u32 N) {
+    const u32 n = blockIdx.x * KS_THREADS + threadIdx.x;
+    const u32 j = blockIdx.y;
+    const u32 Wl = level + K;
+    const u32 lo = j * alpha, hi = min(lo + alpha, level);
+    u64 y[MAX_DIGIT];
+#pragma unroll
+    for (u32 a = 0; a < MAX_DIGIT; ++a) {
+        y[a] = 0;
+        if (lo + a < hi) y[a] = mont_mul(c1_coeff[(size_t)(lo + a) * N + n], up_inv[lo + a], mods[lo + a]);
+    }
+    const u32 t0 = blockIdx.z * UP_CHUNK, t1 = min(t0 + UP_CHUNK, Wl);
+    for (u32 t = t0; t < t1; ++t) {
+        if (t >= lo && t < hi) continue;
+        const u32 gl = t < level ? t : L + (t - level);
+        u128 acc = {0, 0};
+#pragma unroll
+        for (u32 a = 0; a < MAX_DIGIT; ++a)
+            if (lo + a < hi) mac(acc, y[a], up_mat[(size_t)(lo + a) * Wl + t]);
+        digits[((size_t)j * Wl + t) * N + n] = redc(acc, mods[gl]);
+    }
+}
+
+struct ItemPack {
+    SwitchItem it[ROT_BATCH];
+};
+
+// u[r][comp][t][k] = sum_j digits_r[j][t][sigma_g(k)] * key_r[j][comp][limb(t)][k]
+__global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack, u64 *__restrict__ u,
+                                                                   const ModConst *__restrict__ mods, u32 level,
+                                                                   u32 K, u32 L, u32 beta, u32 logN) {
+    const u32 N = 1u << logN;
+    const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
+    const u32 t = blockIdx.y, r = blockIdx.z;
+    const u32 Wl = level + K, Wt = L + K;
+    const u32 gl = t < level ? t : L + (t - level);
+    const SwitchItem &it = pack.it[r];
+    const u32 kp = galois_index(k, it.galois_elt, logN);
+    u128 a0 = {0, 0}, a1 = {0, 0};
+    for (u32 j = 0; j < beta; ++j) {
+        const u64 d = it.digits[((size_t)j * Wl + t) * N + kp];
+        mac(a0, d, it.key[(((size_t)j * 2 + 0) * Wt + gl) * N + k]);
+        mac(a1, d, it.key[(((size_t)j * 2 + 1) * Wt + gl) * N + k]);
+    }
+    const ModConst m = mods[gl];
+    u[(((size_t)r * 2 + 0) * Wl + t) * N + k] = redc_wide(a0, m);
+    u[(((size_t)r * 2 + 1) * Wl + t) * N + k] = redc_wide(a1, m);
+}
+
+// Special-prime rows of u are in the coefficient domain here.
+// y_k = u_{p_k} * (P/p_k)^-1 mod p_k;  w_i = sum_k y_k * (P/p_k mod q_i) mod q_i.
+__global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__restrict__ u, u64 *__restrict__ w,
+                                                                  const ModConst *__restrict__ mods,
+                                                                  const u64 *__restrict__ dn_inv,
+                                                                  const u64 *__restrict__ dn_mat, u32 level, u32 K,
+                                                                  u32 L, u32 N) {
+    const u32 n = blockIdx.x * KS_THREADS + threadIdx.x;
+    const u32 pc = blockIdx.y;   // (item, component)
+    const u32 Wl = level + K;
+    u64 y[MAX_DIGIT];
+#pragma unroll
+    for (u32 k = 0; k < MAX_DIGIT; ++k) {
+        y[k] = 0;
+        if (k < K) y[k] = mont_mul(u[((size_t)pc * Wl + level + k) * N + n], dn_inv[k], mods[L + k]);
+    }
+    const u32 i0 = blockIdx.z * DN_CHUNK, i1 = min(i0 + DN_CHUNK, level);
+    for (u32 i = i0; i < i1; ++i) {
+        u128 acc = {0, 0};
+#pragma unroll
+        for (u32 k = 0; k < MAX_DIGIT; ++k)
+            if (k < K) mac(acc, y[k], dn_mat[(size_t)k * L + i]);
+        w[((size_t)pc * level + i) * N + n] = redc(acc, mods[i]);
+    }
+}
+
+// dst[comp][i][k] (+)= (u_{q_i} - NTT(w_i)) * P^-1  (+ sigma_g(c0)[i][k] for comp 0)
+__global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(ItemPack pack, const u64 *__restrict__ u,
+                                                                   const u64 *__restrict__ w,
+                                                                   const ModConst *__restrict__ mods,
+                                                                   const u64 *__restrict__ pinv, u32 level, u32 K,
+                                                                   u32 logN) {
+    const u32 N = 1u << logN;
+    const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
+    const u32 i = blockIdx.y, r = blockIdx.z >> 1, comp = blockIdx.z & 1;
+    const u32 Wl = level + K;
+    const SwitchItem &it = pack.it[r];
+    const ModConst m = mods[i];
+    const u64 uq = u[(((size_t)r * 2 + comp) * Wl + i) * N + k];
+    const u64 wq = w[(((size_t)r * 2 + comp) * level + i) * N + k];
+    u64 v = mont_mul(sub_mod(uq, wq, m.q), pinv[i], m);
+    if (comp == 0) v = add_mod(v, it.c0[(size_t)i * N + galois_index(k, it.galois_elt, logN)], m.q);
+    u64 *dst = it.dst + ((size_t)comp * level + i) * N + k;
+    if (it.accumulate) v = add_mod(v, *dst, m.q);
+    *dst = v;
+}
+
+size_t digits_words(const ckks_params *p, u32 level) {
+    u32 beta = (level + p->alpha - 1) / p->alpha;
+    return (size_t)beta * (level + p->K) * p->N;
+}
+
+size_t switch_scratch_words(const ckks_params *p, u32 level, u32 n_items) {
+    return (size_t)n_items * 2 * ((size_t)(level + p->K) + level) * p->N;
+}
+
+// d_c1 [level][N] NTT domain -> d_digits [beta][level+K][N] NTT domain; d_tmp [level][N] scratch.
+int decompose(ckks_params *p, const u64 *d_c1, u32 level, u64 *d_digits, u64 *d_tmp, hipStream_t stream) {
+    const u32 N = p->N, K = p->K, L = p->L, Wl = level + K, alpha = p->alpha;
+    const LevelTables *lt = nullptr;
+    int rc = p->level_tables(level, &lt);
+    if (rc) return rc;
+    const u32 beta = lt->beta;
+    CKKS_HIP(hipMemcpyAsync(d_tmp, d_c1, sizeof(u64) * level * N, hipMemcpyDeviceToDevice, stream));
+    LimbIds ids;
+    for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
+    rc = launch_ntt(p, d_tmp, ids, level, level, true, stream);
+    if (rc) return rc;
+    dim3 grid(N / KS_THREADS, beta, (Wl + UP_CHUNK - 1) / UP_CHUNK);
+    hipLaunchKernelGGL(modup_kernel, grid, dim3(KS_THREADS), 0, stream, d_tmp, d_digits, p->d_mod, lt->d_up_inv,
+                       lt->d_up_mat, level, K, L, alpha, N);
+    CKKS_LAUNCH_CHECK("modup_kernel");
+    // forward NTT of the converted rows; the digit's own limbs are copied from the input instead
+    auto row_id = [&](u32 j, u32 t) -> uint8_t {
+        u32 lo = j * alpha, hi = std::min(lo + alpha, level);
+        if (t >= lo && t < hi) return (uint8_t)SKIP_ROW;
+        return (uint8_t)(t < level ? t : L + (t - level));
+    };
+    if (beta * Wl <= MAX_ROW_IDS) {
+        for (u32 j = 0; j < beta; ++j)
+            for (u32 t = 0; t < Wl; ++t) ids.id[j * Wl + t] = row_id(j, t);
+        rc = launch_ntt(p, d_digits, ids, beta * Wl, beta * Wl, false, stream);
+        if (rc) return rc;
+    } else {
+        for (u32 j = 0; j < beta; ++j) {
+            for (u32 t = 0; t < Wl; ++t) ids.id[t] = row_id(j, t);
+            rc = launch_ntt(p, d_digits + (size_t)j * Wl * N, ids, Wl, Wl, false, stream);
+            if (rc) return rc;
+        }
+    }
+    for (u32 j = 0; j < beta; ++j) {
+        u32 lo = j * alpha, hi = std::min(lo + alpha, level);
+        CKKS_HIP(hipMemcpyAsync(d_digits + ((size_t)j * Wl + lo) * N, d_c1 + (size_t)lo * N,
+                                sizeof(u64) * (hi - lo) * N, hipMemcpyDeviceToDevice, stream));
+    }
+    return CKKS_OK;
+}
+
+// n <= ROT_BATCH key switches from ready digits.  d_work: switch_scratch_words(level, n).
+int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream) {
+    if (n == 0) return CKKS_OK;
+    const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
+    const u32 beta = (level + p->alpha - 1) / p->alpha;
+    ItemPack pack;
+    for (u32 r = 0; r < ROT_BATCH; ++r) pack.it[r] = items[r < n ? r : 0];
+    u64 *u = d_work;
+    u64 *w = d_work + (size_t)n * 2 * Wl * N;
+    hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n), dim3(KS_THREADS), 0, stream, pack, u,
+                       p->d_mod, level, K, L, beta, p->logN);
+    CKKS_LAUNCH_CHECK("inner_product_kernel");
+    LimbIds ids;
+    for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
+    int rc = launch_ntt(p, u, ids, Wl, n * 2 * Wl, true, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(moddown_conv_kernel, dim3(N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK),
+                       dim3(KS_THREADS), 0, stream, u, w, p->d_mod, p->d_dn_inv, p->d_dn_mat, level, K, L, N);
+    CKKS_LAUNCH_CHECK("moddown_conv_kernel");
+    for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
+    rc = launch_ntt(p, w, ids, level, n * 2 * level, false, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(moddown_final_kernel, dim3(N / KS_THREADS, level, n * 2), dim3(KS_THREADS), 0, stream, pack,
+                       u, w, p->d_mod, p->d_pinv, level, K, p->logN);
+    CKKS_LAUNCH_CHECK("moddown_final_kernel");
+    return CKKS_OK;
+}
+
+}  // namespace ckks
+
+using namespace ckks;
+
+extern "C" {
+
+int ckks_galois_key_load(const ckks_params_t *P, uint64_t galois_elt, const uint64_t *d_key, void *stream,
+                         ckks_gkey_t **out) {
+    if (!out) {
+        set_error("ckks_galois_key_load: out is null");
+        return CKKS_E_INVAL;
+    }
+    *out = nullptr;
+    if (!P || !d_key) {
+        set_error("ckks_galois_key_load: null argument");
+        return CKKS_E_INVAL;
+    }
+    if (P->K == 0) {
+        set_error("ckks_galois_key_load: parameter set has no special primes");
+        return CKKS_E_INVAL;
+    }
+    if (!(galois_elt & 1) || galois_elt >= 2ull * P->N || galois_elt == 1) {
+        set_error("ckks_galois_key_load: %llu is not a non-trivial Galois element", (unsigned long long)galois_elt);
+        return CKKS_E_INVAL;
+    }
+    ckks_gkey *k = new ckks_gkey();
+    k->params = P;
+    k->galois_elt = galois_elt;
+    size_t rows = (size_t)P->dnum * 2 * P->W;
+    hipError_t e = hipMalloc((void **)&k->d_key, rows * P->N * sizeof(u64));
+    if (e != hipSuccess) {
+        delete k;
+        return hip_fail(e, "hipMalloc(key)");
+    }
+    hipLaunchKernelGGL(to_mont_kernel, dim3(P->N / KS_THREADS, (u32)rows), dim3(KS_THREADS), 0, (hipStream_t)stream,
+                       d_key, k->d_key, P->d_mod, P->W, P->N);
+    e = hipGetLastError();
+    if (e != hipSuccess) {
+        hipFree(k->d_key);
+        delete k;
+        return hip_fail(e, "to_mont_kernel");
+    }
+    *out = k;
+    return CKKS_OK;
+}
+
+void ckks_galois_key_destroy(ckks_gkey_t *key) {
+    if (!key) return;
+    hipFree(key->d_key);
+    delete key;
+}
+
+int ckks_rotate_hoisted(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level, const int32_t *steps,
+                        uint32_t n_steps, const ckks_gkey_t *const *keys, uint64_t *d_ct_out, void *stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!P || !d_ct_in || (n_steps && (!steps || !d_ct_out))) {
+        set_error("ckks_rotate_hoisted: null argument");
+        return CKKS_E_INVAL;
+    }
+    if (level == 0 || level > P->L) {
+        set_error("ckks_rotate_hoisted: level %u outside [1,%u]", level, P->L);
+        return CKKS_E_LEVEL;
+    }
+    const u32 N = P->N;
+    const size_t ctw = (size_t)2 * level * N;
+    std::vector<SwitchItem> items;
+    std::vector<u32> copies;
+    for (u32 r = 0; r < n_steps; ++r) {
+        u64 g;
+        ckks_galois_elt(P, steps[r], &g);
+        if (g == 1) {
+            copies.push_back(r);
+            continue;
+        }
+        if (P->K == 0) {
+            set_error("ckks_rotate_hoisted: parameter set has no special primes");
+            return CKKS_E_INVAL;
+        }
+        if (!keys || !keys[r]) {
+            set_error("ckks_rotate_hoisted: step %d (index %u) has no key", steps[r], r);
+            return CKKS_E_NOKEY;
+        }
+        if (keys[r]->params != P || keys[r]->galois_elt != g) {
+            set_error("ckks_rotate_hoisted: key %u is for Galois element %llu, step %d needs %llu", r,
+                      (unsigned long long)keys[r]->galois_elt, steps[r], (unsigned long long)g);
+            return CKKS_E_INVAL;
+        }
+        SwitchItem it;
+        it.digits = nullptr;
+        it.c0 = d_ct_in;
+        it.key = keys[r]->d_key;
+        it.dst = d_ct_out + (size_t)r * ctw;
+        it.galois_elt = g;
+        it.accumulate = 0;
+        items.push_back(it);
+    }
+    for (u32 r : copies)
+        CKKS_HIP(hipMemcpyAsync(d_ct_out + (size_t)r * ctw, d_ct_in, ctw * sizeof(u64), hipMemcpyDeviceToDevice,
+                                stream));
+    if (items.empty()) return CKKS_OK;
+    const u32 batch = std::min<u32>(ROT_BATCH, (u32)items.size());
+    const size_t dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
+    int rc = P->ensure_scratch((dig_w + tmp_w + switch_scratch_words(P, level, batch)) * sizeof(u64), stream);
+    if (rc) return rc;
+    u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + dig_w, *d_work = d_tmp + tmp_w;
+    rc = decompose(P, d_ct_in + (size_t)level * N, level, d_digits, d_tmp, stream);
+    if (rc) return rc;
+    for (auto &it : items) it.digits = d_digits;
+    for (size_t done = 0; done < items.size(); done += batch) {
+        u32 n = (u32)std::min<size_t>(batch, items.size() - done);
+        rc = switch_batch(P, level, items.data() + done, n, d_work, stream);
+        if (rc) return rc;
+    }
+    return CKKS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,395 @@
+// The projection kernel Y = XW on ciphertexts (Sec. 3.2, App. A.2) and rescale (Sec. 2.2).
+//
+//   bank     x_q^(g) = rot(x^(g); q*m), q < N1            one hoisted call per input group
+//   diagonal acc_{b,p} = sum_g sum_q x_q^(g) (.) w_{b,p,g,q}  the byte mover: every weight limb is read once
+//   giant    y_b = acc_{b,0} + sum_{p>=1} rot(acc_{b,p}; p*N1*m)
+//   bias     y_b.c0 += bias_b
+// Real packing: the imaginary half of the complex weights of App. A.2.1 is not used.
+#include <algorithm>
+
+#include "ckks_internal.h"
+#include "common_kernels.h"
+
+namespace ckks {
+
+constexpr u32 MM_THREADS = 256;
+constexpr u32 MM_TB = 8;   // (b,p) accumulators kept in registers per thread
+
+// int64 coefficients [count][N] -> canonical residues [count][level][N]
+__global__ __launch_bounds__(EW_THREADS) void expand_coeffs_kernel(const int64_t *__restrict__ coef,
+                                                                   u64 *__restrict__ out,
+                                                                   const ModConst *__restrict__ mods, u32 level,
+                                                                   u32 N) {
+    const u32 n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const u32 d = blockIdx.y;
+    const int64_t v = coef[(size_t)d * N + n];
+    for (u32 i = 0; i < level; ++i) out[((size_t)d * level + i) * N + n] = reduce_signed(v, mods[i]);
+}
+
+// rows [rows][N], row r modulo limb r % level: x <- x * c mod q (c canonical, any size)
+__global__ __launch_bounds__(EW_THREADS) void scale_rows_kernel(u64 *data, const ModConst *__restrict__ mods,
+                                                                u32 level, u32 N, u64 c) {
+    const u32 n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const u32 row = blockIdx.y;
+    const ModConst m = mods[row % level];
+    const u64 cm = mont_mul(reduce_any(c, m), m.r2, m);
+    const size_t idx = (size_t)row * N + n;
+    data[idx] = mont_mul(data[idx], cm, m);
+}
+
+// acc[bp][comp][i][k] = sum_{gq} bank[gq][comp][i][k] * w[bp][gq][i][k]   (w in Montgomery form)
+// grid: x = tile of MM_TB (b,p) pairs (fastest, so neighbouring workgroups share their bank lines in L2),
+//       y = run of 256 coefficients, z = limb (slowest: one limb's bank slice stays cache-resident).
+// flush: number of products that fit a 128-bit lazy sum for the largest modulus.
+__global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restrict__ bank,
+                                                              const u64 *__restrict__ w, u64 *__restrict__ acc,
+                                                              const ModConst *__restrict__ mods, u32 level, u32 N,
+                                                              u32 GQ, u32 BP, u32 flush) {
+    const u32 bp0 = blockIdx.x * MM_TB;
+    const u32 k = blockIdx.y * MM_THREADS + threadIdx.x;
+    const u32 i = blockIdx.z;
+    const ModConst m = mods[i];
+    const size_t limb_off = (size_t)i * N + k;
+    const size_t w_stride = (size_t)level * N;         // between consecutive gq of one (b,p)
+    u128 a0[MM_TB], a1[MM_TB];
+    u64 s0[MM_TB], s1[MM_TB];
+#pragma unroll
+    for (u32 t = 0; t < MM_TB; ++t) {
+        a0[t] = {0, 0};
+        a1[t] = {0, 0};
+        s0[t] = 0;
+        s1[t] = 0;
+    }
+    u32 pending = 0;
+    for (u32 gq = 0; gq < GQ; ++gq) {
+        const u64 x0 = bank[((size_t)gq * 2 + 0) * w_stride + limb_off];
+        const u64 x1 = bank[((size_t)gq * 2 + 1) * w_stride + limb_off];
+#pragma unroll
+        for (u32 t = 0; t < MM_TB; ++t) {
+            if (bp0 + t < BP) {
+                const u64 wv = w[((size_t)(bp0 + t) * GQ + gq) * w_stride + limb_off];
+                mac(a0[t], x0, wv);
+                mac(a1[t], x1, wv);
+            }
+        }
+        if (++pending == flush) {
+#pragma unroll
+            for (u32 t = 0; t < MM_TB; ++t) {
+                s0[t] = add_mod(s0[t], redc(a0[t], m), m.q);
+                s1[t] = add_mod(s1[t], redc(a1[t], m), m.q);
+                a0[t] = {0, 0};
+                a1[t] = {0, 0};
+            }
+            pending = 0;
+        }
+    }
+#pragma unroll
+    for (u32 t = 0; t < MM_TB; ++t) {
+        if (bp0 + t < BP) {
+            acc[((size_t)(bp0 + t) * 2 + 0) * w_stride + limb_off] = add_mod(s0[t], redc(a0[t], m), m.q);
+            acc[((size_t)(bp0 + t) * 2 + 1) * w_stride + limb_off] = add_mod(s1[t], redc(a1[t], m), m.q);
+        }
+    }
+}
+
+// delta[pc][i][n] = ((r + h) mod q_l) mod q_i - h mod q_i, r = coefficient-domain last limb, h = floor(q_l/2)
+__global__ __launch_bounds__(EW_THREADS) void rescale_delta_kernel(const u64 *__restrict__ r, u64 *__restrict__ out,
+                                                                   const ModConst *__restrict__ mods, u32 level,
+                                                                   u32 N) {
+    const u32 n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const u32 pc = blockIdx.y;
+    const u64 ql = mods[level - 1].q, h = ql >> 1;
+    const u64 rp = add_mod(r[(size_t)pc * N + n], h, ql);
+    for (u32 i = 0; i + 1 < level; ++i) {
+        const ModConst m = mods[i];
+        out[((size_t)pc * (level - 1) + i) * N + n] = sub_mod(reduce_any(rp, m), reduce_any(h, m), m.q);
+    }
+}
+
+// out[pc][i][k] = (in[pc][i][k] - out[pc][i][k]) * q_l^-1 mod q_i   (out holds NTT(delta) on entry)
+__global__ __launch_bounds__(EW_THREADS) void rescale_final_kernel(const u64 *__restrict__ in, u64 *out,
+                                                                   const ModConst *__restrict__ mods,
+                                                                   const u64 *__restrict__ qlinv, u32 level, u32 N) {
+    const u32 k = blockIdx.x * EW_THREADS + threadIdx.x;
+    const u32 i = blockIdx.y, pc = blockIdx.z;
+    const ModConst m = mods[i];
+    const size_t o = ((size_t)pc * (level - 1) + i) * N + k;
+    out[o] = mont_mul(sub_mod(in[((size_t)pc * level + i) * N + k], out[o], m.q), qlinv[i], m);
+}
+
+// gather rows: dst[pc][n] = src[pc][level-1][n]
+__global__ __launch_bounds__(EW_THREADS) void take_last_limb_kernel(const u64 *__restrict__ in, u64 *__restrict__ r,
+                                                                    u32 level, u32 N) {
+    const u32 n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const u32 pc = blockIdx.y;
+    r[(size_t)pc * N + n] = in[((size_t)pc * level + level - 1) * N + n];
+}
+
+static int expand_plain(const ckks_params *P, u32 level, const int64_t *d_coeffs, u32 count, u64 *d_out, bool mont,
+                        hipStream_t stream) {
+    const u32 N = P->N;
+    LimbIds ids;
+    for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
+    const u32 per = std::max<u32>(1, 16384 / level);
+    for (u32 done = 0; done < count; done += per) {
+        const u32 c = std::min(per, count - done);
+        u64 *o = d_out + (size_t)done * level * N;
+        hipLaunchKernelGGL(expand_coeffs_kernel, dim3(N / EW_THREADS, c), dim3(EW_THREADS), 0, stream,
+                           d_coeffs + (size_t)done * N, o, P->d_mod, level, N);
+        CKKS_LAUNCH_CHECK("expand_coeffs_kernel");
+        int rc = launch_ntt(P, o, ids, level, c * level, false, stream);
+        if (rc) return rc;
+        if (mont) {
+            hipLaunchKernelGGL(to_mont_kernel, dim3(N / EW_THREADS, c * level), dim3(EW_THREADS), 0, stream, o, o,
+                               P->d_mod, level, N);
+            CKKS_LAUNCH_CHECK("to_mont_kernel");
+        }
+    }
+    return CKKS_OK;
+}
+
+}  // namespace ckks
+
+using namespace ckks;
+
+extern "C" {
+
+int ckks_weights_create(const ckks_params_t *P, uint32_t level, uint32_t m, uint32_t C, uint32_t G, uint32_t B_out,
+                        uint32_t N1, ckks_weights_t **out) {
+    if (!out) {
+        set_error("ckks_weights_create: out is null");
+        return CKKS_E_INVAL;
+    }
+    *out = nullptr;
+    if (!P) {
+        set_error("ckks_weights_create: params is null");
+        return CKKS_E_INVAL;
+    }
+    if (level == 0 || level > P->L) {
+        set_error("ckks_weights_create: level %u outside [1,%u]", level, P->L);
+        return CKKS_E_LEVEL;
+    }
+    const u32 n = P->N / 2;
+    if (!m || !C || !G || !B_out || !N1 || n % m || (n / m) % C || C % N1) {
+        set_error("ckks_weights_create: plan m=%u C=%u G=%u B_out=%u N1=%u does not tile %u slots", m, C, G, B_out, N1,
+                  n);
+        return CKKS_E_INVAL;
+    }
+    ckks_weights *w = new ckks_weights();
+    w->params = P;
+    w->level = level;
+    w->m = m;
+    w->C = C;
+    w->G = G;
+    w->B_out = B_out;
+    w->N1 = N1;
+    w->N2 = C / N1;
+    size_t words = (size_t)B_out * w->N2 * G * N1 * level * P->N;
+    hipError_t e = hipMalloc((void **)&w->d_w, words * sizeof(u64));
+    if (e != hipSuccess) {
+        delete w;
+        return hip_fail(e, "hipMalloc(weights)");
+    }
+    *out = w;
+    return CKKS_OK;
+}
+
+int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count, const int64_t *d_coeffs,
+                               void *stream) {
+    if (!w || !d_coeffs) {
+        set_error("ckks_weights_set_diagonals: null argument");
+        return CKKS_E_INVAL;
+    }
+    const u64 total = (u64)w->B_out * w->N2 * w->G * w->N1;
+    if ((u64)first + count > total) {
+        set_error("ckks_weights_set_diagonals: [%u,%u) exceeds %llu diagonals", first, first + count,
+                  (unsigned long long)total);
+        return CKKS_E_INVAL;
+    }
+    return expand_plain(w->params, w->level, d_coeffs, count, w->d_w + (size_t)first * w->level * w->params->N, true,
+                        (hipStream_t)stream);
+}
+
+int ckks_weights_set_bias(ckks_weights_t *w, const int64_t *d_bias_coeffs, uint64_t bias_mul, void *stream) {
+    if (!w || !d_bias_coeffs) {
+        set_error("ckks_weights_set_bias: null argument");
+        return CKKS_E_INVAL;
+    }
+    const ckks_params *P = w->params;
+    if (!w->d_bias) CKKS_HIP(hipMalloc((void **)&w->d_bias, (size_t)w->B_out * w->level * P->N * sizeof(u64)));
+    int rc = expand_plain(P, w->level, d_bias_coeffs, w->B_out, w->d_bias, false, (hipStream_t)stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(scale_rows_kernel, dim3(P->N / EW_THREADS, w->B_out * w->level), dim3(EW_THREADS), 0,
+                       (hipStream_t)stream, w->d_bias, P->d_mod, w->level, P->N, bias_mul);
+    CKKS_LAUNCH_CHECK("scale_rows_kernel");
+    return CKKS_OK;
+}
+
+void ckks_weights_destroy(ckks_weights_t *w) {
+    if (!w) return;
+    hipFree(w->d_w);
+    hipFree(w->d_bias);
+    delete w;
+}
+
+int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *d_ct_x,
+                     const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys, uint64_t *d_ct_y,
+                     ckks_counters_t *counters, void *stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!P || !w || !d_ct_x || !d_ct_y) {
+        set_error("ckks_ctpt_matmul: null argument");
+        return CKKS_E_INVAL;
+    }
+    if (w->params != P) {
+        set_error("ckks_ctpt_matmul: weights belong to another parameter set");
+        return CKKS_E_INVAL;
+    }
+    const u32 N = P->N, level = w->level, G = w->G, B = w->B_out, N1 = w->N1, N2 = w->N2, m = w->m;
+    if ((N1 > 1 && !baby_keys) || (N2 > 1 && !giant_keys)) {
+        set_error("ckks_ctpt_matmul: key list missing (N1=%u, N2=%u)", N1, N2);
+        return CKKS_E_NOKEY;
+    }
+    // every key is checked before any work is enqueued
+    std::vector<int32_t> baby_steps(N1), giant_steps(N2);
+    for (u32 q = 0; q < N1; ++q) baby_steps[q] = (int32_t)(q * m);
+    for (u32 p = 0; p < N2; ++p) giant_steps[p] = (int32_t)(p * N1 * m);
+    std::vector<const ckks_gkey_t *> bk(N1, nullptr);
+    for (u32 q = 1; q < N1; ++q) {
+        u64 g;
+        ckks_galois_elt(P, baby_steps[q], &g);
+        bk[q] = baby_keys[q - 1];
+        if (g != 1 && (!bk[q] || bk[q]->params != P || bk[q]->galois_elt != g)) {
+            set_error("ckks_ctpt_matmul: baby key %u missing or for the wrong Galois element", q);
+            return bk[q] ? CKKS_E_INVAL : CKKS_E_NOKEY;
+        }
+    }
+    std::vector<u64> giant_g(N2, 1);
+    for (u32 p = 1; p < N2; ++p) {
+        ckks_galois_elt(P, giant_steps[p], &giant_g[p]);
+        const ckks_gkey_t *k = giant_keys[p - 1];
+        if (giant_g[p] != 1 && (!k || k->params != P || k->galois_elt != giant_g[p])) {
+            set_error("ckks_ctpt_matmul: giant key %u missing or for the wrong Galois element", p);
+            return k ? CKKS_E_INVAL : CKKS_E_NOKEY;
+        }
+    }
+    const uint64_t ntt0 = P->limb_ntts;
+    const size_t ctw = (size_t)2 * level * N;
+    const u32 BP = B * N2, GQ = G * N1;
+    // persistent buffers of this call live behind the key-switch scratch
+    const u32 batch = std::min<u32>(ROT_BATCH, std::max(N1, B));
+    const size_t dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
+    const size_t ks_w = batch * dig_w + tmp_w + switch_scratch_words(P, level, batch);
+    const size_t bank_w = (size_t)GQ * ctw, acc_w = (size_t)BP * ctw;
+    int rc = P->ensure_scratch((ks_w + bank_w + acc_w) * sizeof(u64), stream);
+    if (rc) return rc;
+    u64 *d_bank = (u64 *)P->d_scratch + ks_w, *d_acc = d_bank + bank_w;
+
+    // 1. baby-step bank (ckks_rotate_hoisted uses the front of the same scratch; it cannot grow it now)
+    for (u32 g = 0; g < G; ++g) {
+        rc = ckks_rotate_hoisted(P, d_ct_x + (size_t)g * ctw, level, baby_steps.data(), N1, bk.data(),
+                                 d_bank + (size_t)g * N1 * ctw, stream);
+        if (rc) return rc;
+    }
+    // 2. diagonal multiply-accumulate
+    u64 maxq = 0;
+    for (u32 i = 0; i < level; ++i) maxq = std::max(maxq, P->mod[i]);
+    const u32 flush = (u32)std::min<u64>(1u << 30, (~0ull) / maxq);
+    hipLaunchKernelGGL(diag_mac_kernel, dim3((BP + MM_TB - 1) / MM_TB, N / MM_THREADS, level), dim3(MM_THREADS), 0,
+                       stream, d_bank, w->d_w, d_acc, P->d_mod, level, N, GQ, BP, flush);
+    CKKS_LAUNCH_CHECK("diag_mac_kernel");
+    // 3. giant steps: y_b = acc_{b,0} + sum_p rot(acc_{b,p})
+    for (u32 b = 0; b < B; ++b)
+        CKKS_HIP(hipMemcpyAsync(d_ct_y + (size_t)b * ctw, d_acc + (size_t)b * N2 * ctw, ctw * sizeof(u64),
+                                hipMemcpyDeviceToDevice, stream));
+    u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + tmp_w;
+    for (u32 p = 1; p < N2; ++p) {
+        for (u32 b0 = 0; b0 < B; b0 += batch) {
+            const u32 nb = std::min(batch, B - b0);
+            if (giant_g[p] == 1) {   // a full turn: plain addition
+                for (u32 r = 0; r < nb; ++r) {
+                    hipLaunchKernelGGL(add_rows_kernel, dim3(N / EW_THREADS, 2 * level), dim3(EW_THREADS), 0, stream,
+                                       d_ct_y + (size_t)(b0 + r) * ctw, d_acc + ((size_t)(b0 + r) * N2 + p) * ctw,
+                                       P->d_mod, level, N);
+                    CKKS_LAUNCH_CHECK("add_rows_kernel");
+                }
+                continue;
+            }
+            SwitchItem items[ROT_BATCH];
+            for (u32 r = 0; r < nb; ++r) {
+                const u64 *src = d_acc + ((size_t)(b0 + r) * N2 + p) * ctw;
+                rc = decompose(P, src + (size_t)level * N, level, d_digits + (size_t)r * dig_w, d_tmp, stream);
+                if (rc) return rc;
+                items[r].digits = d_digits + (size_t)r * dig_w;
+                items[r].c0 = src;
+                items[r].key = giant_keys[p - 1]->d_key;
+                items[r].dst = d_ct_y + (size_t)(b0 + r) * ctw;   // distinct b within a batch: no two items share dst
+                items[r].galois_elt = giant_g[p];
+                items[r].accumulate = 1;
+            }
+            rc = switch_batch(P, level, items, nb, d_work, stream);
+            if (rc) return rc;
+        }
+    }
+    // 4. bias into c0
+    if (w->d_bias) {
+        for (u32 b = 0; b < B; ++b) {
+            hipLaunchKernelGGL(add_rows_kernel, dim3(N / EW_THREADS, level), dim3(EW_THREADS), 0, stream,
+                               d_ct_y + (size_t)b * ctw, w->d_bias + (size_t)b * level * N, P->d_mod, level, N);
+            CKKS_LAUNCH_CHECK("add_rows_kernel");
+        }
+    }
+    if (counters) {
+        u64 ks = 0;
+        for (u32 q = 1; q < N1; ++q) {
+            u64 g;
+            ckks_galois_elt(P, baby_steps[q], &g);
+            ks += (g != 1) ? G : 0;
+        }
+        for (u32 p = 1; p < N2; ++p) ks += (giant_g[p] != 1) ? B : 0;
+        counters->key_switches = ks;
+        counters->ptmuls = (u64)GQ * BP;
+        counters->limb_ntts = P->limb_ntts - ntt0;
+    }
+    return CKKS_OK;
+}
+
+int ckks_rescale(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct, uint64_t *d_ct_out,
+                 void *stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!P || !d_ct_in || !d_ct_out) {
+        set_error("ckks_rescale: null argument");
+        return CKKS_E_INVAL;
+    }
+    if (level_in < 2 || level_in > P->L) {
+        set_error("ckks_rescale: level %u outside [2,%u]", level_in, P->L);
+        return CKKS_E_LEVEL;
+    }
+    if (n_ct == 0) return CKKS_OK;
+    const u32 N = P->N, level = level_in, rows = 2 * n_ct;
+    if (rows * (level - 1) > 65535) {
+        set_error("ckks_rescale: %u ciphertexts exceed one launch", n_ct);
+        return CKKS_E_INVAL;
+    }
+    int rc = P->ensure_scratch((size_t)rows * N * sizeof(u64), stream);
+    if (rc) return rc;
+    u64 *d_r = (u64 *)P->d_scratch;
+    hipLaunchKernelGGL(take_last_limb_kernel, dim3(N / EW_THREADS, rows), dim3(EW_THREADS), 0, stream, d_ct_in, d_r,
+                       level, N);
+    CKKS_LAUNCH_CHECK("take_last_limb_kernel");
+    LimbIds ids;
+    ids.id[0] = (uint8_t)(level - 1);
+    rc = launch_ntt(P, d_r, ids, 1, rows, true, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(rescale_delta_kernel, dim3(N / EW_THREADS, rows), dim3(EW_THREADS), 0, stream, d_r, d_ct_out,
+                       P->d_mod, level, N);
+    CKKS_LAUNCH_CHECK("rescale_delta_kernel");
+    for (u32 i = 0; i + 1 < level; ++i) ids.id[i] = (uint8_t)i;
+    rc = launch_ntt(P, d_ct_out, ids, level - 1, rows * (level - 1), false, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(rescale_final_kernel, dim3(N / EW_THREADS, level - 1, rows), dim3(EW_THREADS), 0, stream,
+                       d_ct_in, d_ct_out, P->d_mod, P->d_qlinv + (size_t)(level - 1) * P->L, level, N);
+    CKKS_LAUNCH_CHECK("rescale_final_kernel");
+    return CKKS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,155 @@
+// Negacyclic NTT / INTT over the RNS limbs.
+//
+// out[k] = a(psi^(2*bitrev(k)+1)): the transform splits X^(2t) - psi^(2e) into
+// (X^t - psi^e)(X^t + psi^e) stage by stage; stage s has 2^s nodes and node i
+// uses the twiddle psi^bitrev(2^s + i).  A polynomial of N = 2^16 residues
+// (512 KiB) does not fit LDS, so the stages are cut into two passes over HBM:
+//   pass A: the first a = logN - 8 stages.  Elements that interact there share
+//           their index modulo N/2^a; a workgroup owns 2^a rows of a run of
+//           consecutive residues, so global accesses stay contiguous.
+//   pass B: the last 8 stages act inside aligned runs of 256 residues; a
+//           workgroup owns 4096 consecutive residues.
+// The inverse runs pass B then pass A with Gentleman-Sande butterflies and folds
+// N^-1 into the last stage.  Rings with N <= 4096 fit one tile and use pass B alone.
+#include <algorithm>
+
+#include "ckks_internal.h"
+
+namespace ckks {
+
+constexpr u32 NTT_THREADS = 256;
+constexpr u32 NTT_TILE_LOG = 12;
+
+// strided != 0: pass A layout, local element (x, lo) = (e / LT, e % LT) sits at
+//   x * (N >> a) + blockIdx.x * LT + lo   with LT = T >> a.
+// strided == 0: pass B layout, local element e sits at blockIdx.x * T + e.
+template <bool INV>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_pass_kernel(u64 *__restrict__ data,
+                                                               const ModConst *__restrict__ mods,
+                                                               const u64 *__restrict__ tw,
+                                                               const u64 *__restrict__ ninv, LimbIds ids,
+                                                               u32 n_limbs, u32 logN, u32 s_lo, u32 s_hi,
+                                                               u32 tile_log, u32 strided) {
+    extern __shared__ u64 lds[];
+    const u32 row = blockIdx.y;
+    const u32 limb = ids.id[row % n_limbs];
+    if (limb == SKIP_ROW) return;
+    const ModConst m = mods[limb];
+    const u32 N = 1u << logN, T = 1u << tile_log;
+    u64 *poly = data + (size_t)row * N;
+    const u64 *twl = tw + (size_t)limb * N;
+    const u32 a = s_hi;                       // pass A always covers stages [0, a)
+    const u32 lt_log = tile_log - a;          // only meaningful when strided
+    const u32 base = blockIdx.x << (strided ? lt_log : tile_log);
+
+    for (u32 e = threadIdx.x; e < T; e += NTT_THREADS) {
+        size_t gi = strided ? ((size_t)(e >> lt_log) << (logN - a)) + base + (e & ((1u << lt_log) - 1)) : base + e;
+        lds[e] = poly[gi];
+    }
+    __syncthreads();
+
+    const u32 n_st = s_hi - s_lo;
+    for (u32 st = 0; st < n_st; ++st) {
+        const u32 s = INV ? s_hi - 1 - st : s_lo + st;
+        // local gap between the two legs of a butterfly
+        const u32 gap_log = strided ? tile_log - 1 - s : logN - 1 - s;
+        const u32 node0 = strided ? 0 : base >> (logN - s);
+        for (u32 bf = threadIdx.x; bf < T / 2; bf += NTT_THREADS) {
+            const u32 grp = bf >> gap_log, j = bf & ((1u << gap_log) - 1);
+            const u32 i0 = (grp << (gap_log + 1)) + j, i1 = i0 + (1u << gap_log);
+            const u64 w = twl[(1u << s) + node0 + grp];
+            u64 x = lds[i0], y = lds[i1];
+            if (!INV) {
+                u64 v = mont_mul(y, w, m);
+                lds[i0] = add_mod(x, v, m.q);
+                lds[i1] = sub_mod(x, v, m.q);
+            } else if (s != 0) {
+                lds[i0] = add_mod(x, y, m.q);
+                lds[i1] = mont_mul(sub_mod(x, y, m.q), w, m);
+            } else {
+                lds[i0] = mont_mul(add_mod(x, y, m.q), ninv[2 * limb], m);
+                lds[i1] = mont_mul(sub_mod(x, y, m.q), ninv[2 * limb + 1], m);
+            }
+        }
+        __syncthreads();
+    }
+
+    for (u32 e = threadIdx.x; e < T; e += NTT_THREADS) {
+        size_t gi = strided ? ((size_t)(e >> lt_log) << (logN - a)) + base + (e & ((1u << lt_log) - 1)) : base + e;
+        poly[gi] = lds[e];
+    }
+}
+
+int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, bool inverse,
+               hipStream_t stream) {
+    if (rows == 0) return CKKS_OK;
+    const u32 logN = p->logN;
+    const u32 tile_log = logN < NTT_TILE_LOG ? logN : NTT_TILE_LOG;
+    const u32 a = logN > NTT_TILE_LOG ? logN - 8 : 0;
+    const size_t lds_bytes = sizeof(u64) << tile_log;
+    dim3 grid(p->N >> tile_log, rows), block(NTT_THREADS);
+    for (u32 r = 0; r < rows; ++r)
+        if (ids.id[r % n_limbs] != SKIP_ROW) ++p->limb_ntts;
+    if (rows > 65535) {
+        set_error("launch_ntt: %u rows exceed one launch", rows);
+        return CKKS_E_INVAL;
+    }
+    if (!inverse) {
+        if (a)
+            hipLaunchKernelGGL(ntt_pass_kernel<false>, grid, block, lds_bytes, stream, d_data, p->d_mod, p->d_tw_fwd,
+                               p->d_ninv, ids, n_limbs, logN, 0u, a, tile_log, 1u);
+        hipLaunchKernelGGL(ntt_pass_kernel<false>, grid, block, lds_bytes, stream, d_data, p->d_mod, p->d_tw_fwd,
+                           p->d_ninv, ids, n_limbs, logN, a, logN, tile_log, 0u);
+    } else {
+        hipLaunchKernelGGL(ntt_pass_kernel<true>, grid, block, lds_bytes, stream, d_data, p->d_mod, p->d_tw_inv,
+                           p->d_ninv, ids, n_limbs, logN, a, logN, tile_log, 0u);
+        if (a)
+            hipLaunchKernelGGL(ntt_pass_kernel<true>, grid, block, lds_bytes, stream, d_data, p->d_mod, p->d_tw_inv,
+                               p->d_ninv, ids, n_limbs, logN, 0u, a, tile_log, 1u);
+    }
+    CKKS_LAUNCH_CHECK("ntt_pass_kernel");
+    return CKKS_OK;
+}
+
+}  // namespace ckks
+
+using namespace ckks;
+
+static int ntt_api(const ckks_params_t *P, uint64_t *d_data, const uint32_t *limb_ids, uint32_t n_limbs,
+                   uint32_t batch, void *stream, bool inverse) {
+    if (P && batch == 0) return CKKS_OK;
+    if (!P || !d_data || !limb_ids || n_limbs == 0 || n_limbs > MAX_LIMBS) {
+        set_error("ckks_ntt: null argument or n_limbs outside [1,%u]", MAX_LIMBS);
+        return CKKS_E_INVAL;
+    }
+    LimbIds ids;
+    for (u32 i = 0; i < n_limbs; ++i) {
+        if (limb_ids[i] >= P->W) {
+            set_error("ckks_ntt: limb id %u out of range", limb_ids[i]);
+            return CKKS_E_INVAL;
+        }
+        ids.id[i] = (uint8_t)limb_ids[i];
+    }
+    // long batches go out in slices of at most 32768 rows
+    u32 per = (32768 / n_limbs) * n_limbs;
+    for (u64 done = 0; done < (u64)batch * n_limbs; done += per) {
+        u32 rows = (u32)std::min<u64>(per, (u64)batch * n_limbs - done);
+        int rc = launch_ntt(P, d_data + done * P->N, ids, n_limbs, rows, inverse, (hipStream_t)stream);
+        if (rc) return rc;
+    }
+    return CKKS_OK;
+}
+
+extern "C" {
+
+int ckks_ntt(const ckks_params_t *P, uint64_t *d_data, const uint32_t *limb_ids, uint32_t n_limbs, uint32_t batch,
+             void *stream) {
+    return ntt_api(P, d_data, limb_ids, n_limbs, batch, stream, false);
+}
+
+int ckks_intt(const ckks_params_t *P, uint64_t *d_data, const uint32_t *limb_ids, uint32_t n_limbs, uint32_t batch,
+              void *stream) {
+    return ntt_api(P, d_data, limb_ids, n_limbs, batch, stream, true);
+}
+
+}  // extern "C"

@@ -1,0 +1,347 @@
+// Host side of a parameter set: validation of the modulus chain, roots of
+// unity, twiddle tables and base-conversion tables (all uploaded in Montgomery
+// form), and the private scratch arena.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <algorithm>
+
+#include "ckks_internal.h"
+
+namespace ckks {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char *what) {
+    set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+    return e == hipErrorOutOfMemory ? CKKS_E_NOMEM : CKKS_E_HIP;
+}
+
+typedef unsigned __int128 wide;
+
+static u64 hmul(u64 a, u64 b, u64 q) { return (u64)((wide)a * b % q); }
+static u64 hpow(u64 a, u64 e, u64 q) {
+    u64 r = 1;
+    a %= q;
+    for (; e; e >>= 1) {
+        if (e & 1) r = hmul(r, a, q);
+        a = hmul(a, a, q);
+    }
+    return r;
+}
+static u64 hinv(u64 a, u64 q) { return hpow(a % q, q - 2, q); }
+
+// Miller-Rabin with the witness set {2,3,5,7,11,13,17,19,23,29,31,37}, which is
+// known to be exact below 3.3e24.
+static bool is_prime(u64 n) {
+    if (n < 2) return false;
+    const u64 wit[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    for (u64 w : wit) {
+        if (n == w) return true;
+        if (n % w == 0) return false;
+    }
+    u64 odd = n - 1;
+    int twos = 0;
+    while (!(odd & 1)) {
+        odd >>= 1;
+        ++twos;
+    }
+    for (u64 w : wit) {
+        u64 x = hpow(w, odd, n);
+        if (x == 1 || x == n - 1) continue;
+        bool witness = true;
+        for (int i = 1; i < twos && witness; ++i) {
+            x = hmul(x, x, n);
+            if (x == n - 1) witness = false;
+        }
+        if (witness) return false;
+    }
+    return true;
+}
+
+// Smallest psi with psi^N = -1 mod q: take any element of order exactly 2N and
+// walk its odd powers.
+static u64 smallest_root(u64 q, u32 logN) {
+    u64 N = (u64)1 << logN, cof = (q - 1) >> (logN + 1);
+    u64 base = 0;
+    for (u64 cand = 2; cand < q; ++cand) {
+        u64 r = hpow(cand, cof, q);
+        if (hpow(r, N, q) == q - 1) {
+            base = r;
+            break;
+        }
+    }
+    u64 sq = hmul(base, base, q), cur = base, best = base;
+    for (u64 i = 1; i < N; ++i) {
+        cur = hmul(cur, sq, q);
+        best = std::min(best, cur);
+    }
+    return best;
+}
+
+static u32 bitrev(u32 x, u32 bits) {
+    u32 r = 0;
+    for (u32 i = 0; i < bits; ++i) r |= ((x >> i) & 1u) << (bits - 1 - i);
+    return r;
+}
+
+static ModConst make_mod(u64 q) {
+    ModConst m;
+    m.q = q;
+    u64 inv = q;  // Newton: correct to 3 bits, doubles each step
+    for (int i = 0; i < 6; ++i) inv *= 2 - q * inv;
+    m.qinv = inv;
+    m.one = (u64)((((wide)1) << 64) % q);
+    m.r2 = hmul(m.one, m.one, q);
+    return m;
+}
+
+static u64 to_mont(u64 x, const ModConst &m) { return hmul(x % m.q, m.one, m.q); }
+
+template <typename T>
+static int upload(T **dst, const std::vector<T> &src) {
+    *dst = nullptr;
+    if (src.empty()) return CKKS_OK;
+    CKKS_HIP(hipMalloc((void **)dst, src.size() * sizeof(T)));
+    CKKS_HIP(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+    return CKKS_OK;
+}
+
+}  // namespace ckks
+
+using namespace ckks;
+
+int ckks_params::ensure_scratch(size_t bytes, hipStream_t stream) {
+    if (bytes <= scratch_bytes) return CKKS_OK;
+    if (d_scratch) {
+        CKKS_HIP(hipStreamSynchronize(stream));
+        CKKS_HIP(hipFree(d_scratch));
+        d_scratch = nullptr;
+        scratch_bytes = 0;
+    }
+    CKKS_HIP(hipMalloc(&d_scratch, bytes));
+    scratch_bytes = bytes;
+    return CKKS_OK;
+}
+
+int ckks_params::level_tables(u32 level, const LevelTables **out) {
+    auto it = levels.find(level);
+    if (it != levels.end()) {
+        *out = &it->second;
+        return CKKS_OK;
+    }
+    LevelTables t;
+    t.level = level;
+    t.beta = (level + alpha - 1) / alpha;
+    u32 Wl = level + K;
+    std::vector<u64> inv(level), mat((size_t)level * Wl, 0);
+    for (u32 i = 0; i < level; ++i) {
+        u32 lo = (i / alpha) * alpha, hi = std::min(lo + alpha, level);
+        u64 qi = mod[i], prod = 1;
+        for (u32 b = lo; b < hi; ++b)
+            if (b != i) prod = hmul(prod, mod[b] % qi, qi);
+        inv[i] = to_mont(hinv(prod, qi), hmod[i]);
+        for (u32 t2 = 0; t2 < Wl; ++t2) {
+            if (t2 >= lo && t2 < hi) continue;
+            u32 gl = t2 < level ? t2 : L + (t2 - level);
+            u64 mt = mod[gl], f = 1;
+            for (u32 b = lo; b < hi; ++b)
+                if (b != i) f = hmul(f, mod[b] % mt, mt);
+            mat[(size_t)i * Wl + t2] = to_mont(f, hmod[gl]);
+        }
+    }
+    int rc = upload(&t.d_up_inv, inv);
+    if (rc) return rc;
+    rc = upload(&t.d_up_mat, mat);
+    if (rc) return rc;
+    auto ins = levels.emplace(level, t);
+    *out = &ins.first->second;
+    return CKKS_OK;
+}
+
+extern "C" {
+
+const char *ckks_last_error(void) { return ckks::g_err; }
+
+int ckks_find_primes(uint32_t bits, uint32_t logN, uint32_t count, uint64_t *out) {
+    if (!out || bits > 61 || bits < logN + 2 || logN < 1 || logN > 30) {
+        set_error("ckks_find_primes: bad arguments (bits=%u logN=%u)", bits, logN);
+        return CKKS_E_INVAL;
+    }
+    u64 step = (u64)2 << logN, top = (u64)1 << bits;
+    u32 found = 0;
+    for (u64 k = 1; found < count; ++k) {
+        if (k * step >= top / 2) {
+            set_error("ckks_find_primes: only %u primes of %u bits", found, bits);
+            return CKKS_E_INVAL;
+        }
+        u64 c = top - k * step + 1;
+        if (is_prime(c)) out[found++] = c;
+    }
+    return CKKS_OK;
+}
+
+int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint64_t *p, uint32_t K,
+                       uint32_t dnum, ckks_params_t **out) {
+    if (!out) {
+        set_error("ckks_params_create: out is null");
+        return CKKS_E_INVAL;
+    }
+    *out = nullptr;
+    if (!q || (K && !p) || L == 0 || dnum == 0) {
+        set_error("ckks_params_create: null prime list or empty chain");
+        return CKKS_E_INVAL;
+    }
+    if (logN < 10 || logN > 17) {
+        set_error("ckks_params_create: logN=%u outside [10,17]", logN);
+        return CKKS_E_INVAL;
+    }
+    if (L % dnum) {
+        set_error("ckks_params_create: L=%u not divisible by dnum=%u", L, dnum);
+        return CKKS_E_INVAL;
+    }
+    if (L + K > MAX_LIMBS || L / dnum > MAX_DIGIT || K > MAX_DIGIT) {
+        set_error("ckks_params_create: L+K=%u > %u, or digit/special count > %u", L + K, MAX_LIMBS, MAX_DIGIT);
+        return CKKS_E_INVAL;
+    }
+    u64 twoN = (u64)2 << logN;
+    std::vector<u64> mod;
+    for (u32 i = 0; i < L; ++i) mod.push_back(q[i]);
+    for (u32 k = 0; k < K; ++k) mod.push_back(p[k]);
+    for (size_t i = 0; i < mod.size(); ++i) {
+        u64 v = mod[i];
+        if (v >> 62 || v < twoN || v % twoN != 1 || !is_prime(v)) {
+            set_error("ckks_params_create: modulus %zu (%llu) is not a prime < 2^62 that is 1 mod 2N", i,
+                      (unsigned long long)v);
+            return CKKS_E_INVAL;
+        }
+        for (size_t j = 0; j < i; ++j)
+            if (mod[j] == v) {
+                set_error("ckks_params_create: modulus %llu listed twice", (unsigned long long)v);
+                return CKKS_E_INVAL;
+            }
+    }
+    // lazy sums of alpha (or K) products must stay below 2^64 * target modulus
+    u64 maxq = *std::max_element(mod.begin(), mod.end());
+    u32 terms = std::max(L / dnum, K);
+    if ((wide)terms * maxq >= ((wide)1 << 64)) {
+        set_error("ckks_params_create: digit size %u too large for %llu-sized primes", terms, (unsigned long long)maxq);
+        return CKKS_E_INVAL;
+    }
+
+    ckks_params *P = new ckks_params();
+    P->logN = logN;
+    P->N = 1u << logN;
+    P->L = L;
+    P->K = K;
+    P->dnum = dnum;
+    P->alpha = L / dnum;
+    P->W = L + K;
+    P->mod = mod;
+    hipGetDevice(&P->device);
+    u32 N = P->N, W = P->W;
+    for (u64 v : mod) {
+        P->hmod.push_back(make_mod(v));
+        P->psi.push_back(smallest_root(v, logN));
+    }
+    std::vector<u64> fwd((size_t)W * N, 0), inv((size_t)W * N, 0), ninv((size_t)W * 2);
+    std::vector<u64> pw(2 * (size_t)N);
+    for (u32 i = 0; i < W; ++i) {
+        const ModConst &m = P->hmod[i];
+        pw[0] = 1;
+        for (u32 e = 1; e < 2 * N; ++e) pw[e] = hmul(pw[e - 1], P->psi[i], m.q);
+        for (u32 idx = 1; idx < N; ++idx) {
+            u32 e = bitrev(idx, logN);
+            fwd[(size_t)i * N + idx] = to_mont(pw[e], m);
+            inv[(size_t)i * N + idx] = to_mont(pw[2 * N - e], m);
+        }
+        u64 ni = hinv(N % m.q, m.q);
+        ninv[2 * i] = to_mont(ni, m);
+        ninv[2 * i + 1] = to_mont(hmul(ni, pw[2 * N - N / 2], m.q), m);
+    }
+    std::vector<u64> dn_inv(K), dn_mat((size_t)K * L), pinv(L), qlinv((size_t)L * L, 0);
+    for (u32 k = 0; k < K; ++k) {
+        u64 pk = mod[L + k], prod = 1;
+        for (u32 b = 0; b < K; ++b)
+            if (b != k) prod = hmul(prod, mod[L + b] % pk, pk);
+        dn_inv[k] = to_mont(hinv(prod, pk), P->hmod[L + k]);
+        for (u32 i = 0; i < L; ++i) {
+            u64 f = 1;
+            for (u32 b = 0; b < K; ++b)
+                if (b != k) f = hmul(f, mod[L + b] % mod[i], mod[i]);
+            dn_mat[(size_t)k * L + i] = to_mont(f, P->hmod[i]);
+        }
+    }
+    for (u32 i = 0; i < L; ++i) {
+        u64 pm = 1;
+        for (u32 k = 0; k < K; ++k) pm = hmul(pm, mod[L + k] % mod[i], mod[i]);
+        pinv[i] = to_mont(hinv(pm, mod[i]), P->hmod[i]);
+        for (u32 l = 0; l < L; ++l)
+            if (l != i) qlinv[(size_t)l * L + i] = to_mont(hinv(mod[l] % mod[i], mod[i]), P->hmod[i]);
+    }
+    int rc = upload(&P->d_mod, P->hmod);
+    if (!rc) rc = upload(&P->d_tw_fwd, fwd);
+    if (!rc) rc = upload(&P->d_tw_inv, inv);
+    if (!rc) rc = upload(&P->d_ninv, ninv);
+    if (!rc) rc = upload(&P->d_dn_inv, dn_inv);
+    if (!rc) rc = upload(&P->d_dn_mat, dn_mat);
+    if (!rc) rc = upload(&P->d_pinv, pinv);
+    if (!rc) rc = upload(&P->d_qlinv, qlinv);
+    if (rc) {
+        ckks_params_destroy(P);
+        return rc;
+    }
+    *out = P;
+    return CKKS_OK;
+}
+
+void ckks_params_destroy(ckks_params_t *P) {
+    if (!P) return;
+    hipFree(P->d_mod);
+    hipFree(P->d_tw_fwd);
+    hipFree(P->d_tw_inv);
+    hipFree(P->d_ninv);
+    hipFree(P->d_dn_inv);
+    hipFree(P->d_dn_mat);
+    hipFree(P->d_pinv);
+    hipFree(P->d_qlinv);
+    for (auto &kv : P->levels) {
+        hipFree(kv.second.d_up_inv);
+        hipFree(kv.second.d_up_mat);
+    }
+    hipFree(P->d_scratch);
+    delete P;
+}
+
+int ckks_params_root(const ckks_params_t *P, uint32_t limb, uint64_t *psi) {
+    if (!P || !psi || limb >= P->W) {
+        set_error("ckks_params_root: bad arguments");
+        return CKKS_E_INVAL;
+    }
+    *psi = P->psi[limb];
+    return CKKS_OK;
+}
+
+int ckks_galois_elt(const ckks_params_t *P, int32_t step, uint64_t *g) {
+    if (!P || !g) {
+        set_error("ckks_galois_elt: null argument");
+        return CKKS_E_INVAL;
+    }
+    u64 twoN = 2ull * P->N;
+    if (step == CKKS_STEP_CONJ) {
+        *g = twoN - 1;
+        return CKKS_OK;
+    }
+    int64_t n = P->N / 2, r = ((int64_t)step % n + n) % n;
+    *g = hpow(5, (u64)r, twoN);   // 2N is not prime, but square-and-multiply needs no inverse
+    return CKKS_OK;
+}
+
+}  // extern "C"

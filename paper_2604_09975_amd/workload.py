@@ -44,7 +44,7 @@ class MatmulSpec:
 
 TOY_RING = RingSpec(logN=12, q_bits=(40, 30, 30), p_bits=(40,), dnum=3, log_scale=30, name="toy")
 BIG_RING = RingSpec(logN=16, q_bits=(50,) * 24, p_bits=(60,) * 8, dnum=3, log_scale=40, name="n16_l24_k8")
-NTT_RING = RingSpec(logN=16, q_bits=(50,) * 24, p_bits=(), dnum=1, log_scale=40, name="ntt_n16_l24")
+NTT_RING = RingSpec(logN=16, q_bits=(50,) * 24, p_bits=(), dnum=3, log_scale=40, name="ntt_n16_l24")
 
 TOY_MATMUL = MatmulSpec(ring=TOY_RING, m=16, d_in=64, d_out=64, C=64, N1=64, x_dist="uniform1", w_std=0.0,
                         bias=False, seed=SEED_BASE + 0, name="toy_16x64x64")

@@ -1,0 +1,133 @@
+"""GPU parity: the ct-pt projection Y = XW (+ bias) and rescale against the oracle, bit for bit,
+and the decrypted result against the fp64 product."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import encoding as E
+from tests import helpers
+from tests.gpu_util import load_keys, make_pair, to_dev, to_host
+from paper_2604_09975_amd import workload as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _B():
+    from paper_2604_09975_amd import binding as B
+    return B
+
+
+def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_blocks=None):
+    """Runs the projection on both sides from identical integer inputs; returns everything."""
+    B = _B()
+    N, n = O.N, O.n
+    sx = sw = 2.0**log_scale
+    d_in, d_out = Wm.shape
+    G, B_out, N2 = -(-d_in // C), -(-d_out // C), C // N1
+    cl = helpers.Client(O, seed, hamming_weight=hw)
+    mx = E.encode(E.pack_columns(X, n, C) + 0j, sx, N)
+    ct_x = np.stack([cl.encrypt_coeffs(mx[g], level) for g in range(G)])
+    diag = E.encode_diagonals(Wm, m, N, C, N1, sw)
+    bias_c = None
+    if bias is not None:
+        bias_c = np.stack([E.encode(E.bias_slots(bias, m, n, C, b) + 0j, sx, N) for b in range(B_out)])
+    baby_np, baby_h = load_keys(P, O, cl, [q * m for q in range(1, N1)])
+    giant_np, giant_h = load_keys(P, O, cl, [p * N1 * m for p in range(1, N2)])
+
+    w = B.ckks_weights_create(P, level, m, C, G, B_out, N1)
+    flat = diag.reshape(-1, N)
+    half = max(1, flat.shape[0] // 2)                 # two uploads: exercises the `first` offset
+    B.ckks_weights_set_diagonals(w, 0, to_dev(flat[:half]))
+    if flat.shape[0] > half:
+        B.ckks_weights_set_diagonals(w, half, to_dev(flat[half:]))
+    if bias_c is not None:
+        B.ckks_weights_set_bias(w, to_dev(bias_c), int(sw))
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h)
+    y_res = B.ckks_rescale(P, y_dev, level, B_out)
+    torch.cuda.synchronize()
+    got, got_res = to_host(y_dev), to_host(y_res)
+
+    blocks = list(range(B_out)) if oracle_blocks is None else oracle_blocks
+    for b in blocks:
+        want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(sw), ct_x, baby_np, giant_np,
+                             b_first=b, b_count=1)
+        assert (got[b] == want[b]).all(), f"block {b}"
+        assert (got_res[b] == O.rescale(want[b:b + 1], level)[0]).all(), f"rescaled block {b}"
+    assert cnt.key_switches == sum(1 for k in baby_np if k is not None) * G + sum(1 for k in giant_np if k is not None) * B_out
+    assert cnt.ptmuls == G * N1 * B_out * N2
+    scale = sx * sw / O.q[level - 1]
+    slots = np.stack([cl.decrypt_slots(got_res[b], level - 1, scale, nlimbs=min(level - 1, 2)) for b in range(B_out)])
+    Y = E.unpack_columns(slots.real, m, C, d_out)
+    ref = X @ Wm + (bias if bias is not None else 0.0)
+    return Y, ref, cnt, slots
+
+
+def test_toy_config():
+    """N = 2^12, scale 2^30, 16x64 times 64x64, the 64 rotations of the plain diagonal method, one rescale."""
+    O, P = make_pair(W.TOY_RING)
+    spec = W.TOY_MATMUL
+    X, Wm, _ = W.matmul_inputs(spec)
+    Y, ref, cnt, _ = run_case(O, P, X, Wm, None, spec.m, spec.C, spec.N1, 30, 3, spec.seed)
+    assert np.abs(Y - ref).max() <= 1e-3
+    assert cnt.key_switches == 63
+
+
+@pytest.mark.parametrize("N1", [1, 4, 16])
+def test_bsgs_bias_ragged_shapes(N1):
+    """n = 512 slots, m = 4, C = 16 (eight periods of the active columns), d_in = 40 (ragged last group),
+    d_out = 20 (ragged last block), bias, every split of the 16 diagonals."""
+    O = helpers.small_oracle(10, L=3, K=1, dnum=3, qbits=40, pbits=42)
+    _, P = make_pair(O)
+    r = W.rng(9)
+    X = r.uniform(-1, 1, (4, 40))
+    Wm = r.uniform(-0.5, 0.5, (40, 20))
+    bias = r.uniform(-0.5, 0.5, 20)
+    Y, ref, cnt, slots = run_case(O, P, X, Wm, bias, 4, 16, N1, 30, 3, 19, hw=16)
+    assert np.abs(Y - ref).max() <= 1e-3
+    assert np.abs(slots.imag).max() <= 1e-3
+    assert cnt.key_switches == 3 * (N1 - 1) + 2 * (16 // N1 - 1)
+
+
+def test_more_blocks_than_one_switch_batch():
+    """B_out = 20 output blocks: the giant step runs in more than one batch of key switches."""
+    O = helpers.small_oracle(10, L=2, K=1, dnum=2, qbits=40, pbits=42)
+    _, P = make_pair(O)
+    r = W.rng(10)
+    X = r.uniform(-1, 1, (64, 8))
+    Wm = r.uniform(-0.5, 0.5, (8, 160))
+    Y, ref, cnt, _ = run_case(O, P, X, Wm, None, 64, 8, 4, 30, 2, 29, hw=16)
+    assert np.abs(Y - ref).max() <= 1e-3
+
+
+def test_rescale_alone_bit_exact_and_errors():
+    B = _B()
+    O, P = make_pair(W.BIG_RING)
+    r = W.rng(4)
+    for level, n_ct in ((24, 2), (2, 1), (7, 3)):
+        ct = W.uniform_residues(r, O.q[:level], O.N, lead=(n_ct, 2))
+        got = to_host(B.ckks_rescale(P, to_dev(ct), level, n_ct))
+        assert (got == O.rescale(ct, level)).all()
+    d = torch.zeros((1, 2, 1, O.N), dtype=torch.int64, device="cuda")
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_rescale(P, d, 1, 1)
+    assert e.value.code == -2
+    assert B.lib.ckks_rescale(P.h, d.data_ptr(), 25, 1, d.data_ptr(), None) == -2
+
+
+def test_matmul_errors():
+    B = _B()
+    O, P = make_pair(W.TOY_RING)
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_weights_create(P, 3, 16, 48, 1, 1, 16)          # C does not divide the 128 segments
+    assert e.value.code == -1
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_weights_create(P, 4, 16, 64, 1, 1, 64)          # level > L
+    assert e.value.code == -2
+    w = B.ckks_weights_create(P, 3, 16, 64, 1, 1, 32)
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_weights_set_diagonals(w, 60, torch.zeros((8, O.N), dtype=torch.int64, device="cuda"))
+    assert e.value.code == -1
+    x = torch.zeros((1, 2, 3, O.N), dtype=torch.int64, device="cuda")
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_ctpt_matmul(P, w, x, [None] * 31, [None])
+    assert e.value.code == -3
