@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the CKKS ct x pt matmul hot path on one MI355X.
+
+One step = one pass of the whole path on the BERT-base QKV projection under CKKS
+(N = 2^16, 24 + 8 primes, scale 2^40, X 128x768 encrypted, W 768x2304 + bias in plaintext):
+ckks_ctpt_matmul (hoisted baby-step bank, diagonal multiply-accumulate over the pre-expanded
+weights, giant-step key switches, bias) followed by ckks_rescale, with keys, weights and input
+ciphertexts resident in HBM.  Prints ONE JSON line; the second headline figure, key switches per
+second on a hoisted batch (N = 2^16, L = 24), rides in the same line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def setup_matmul(B, CL, W, P, cl, spec, n1):
+    import torch
+    N, n = P.N, P.N // 2
+    level = P.L
+    X, Wm, bias = W.matmul_inputs(spec)
+    G, B_out = -(-spec.d_in // spec.C), -(-spec.d_out // spec.C)
+    N2 = spec.C // n1
+    scale = 2.0 ** spec.ring.log_scale
+    t0 = time.time()
+    baby = [cl.galois_key(q * spec.m) for q in range(1, n1)]
+    giant = [cl.galois_key(p * n1 * spec.m) for p in range(1, N2)]
+    log(f"[bench] {len(baby) + len(giant)} Galois keys in {time.time() - t0:.1f}s")
+    xs = CL.pack_columns(X, n, spec.C)
+    ct_x = torch.stack([cl.encrypt_slots(xs[g], scale, level) for g in range(G)])
+    w = B.ckks_weights_create(P, level, spec.m, spec.C, G, B_out, n1)
+    t0 = time.time()
+    for b in range(B_out):
+        for p in range(N2):
+            z = CL.diagonal_slots(Wm, spec.m, n, spec.C, n1, b, p).reshape(G * n1, n)
+            coeffs = cl.enc.encode(z, scale)
+            B.ckks_weights_set_diagonals(w, (b * N2 + p) * G * n1, torch.from_numpy(coeffs).cuda())
+    if bias is not None:
+        nseg = n // spec.m
+        bz = np.zeros((B_out, n))
+        for b in range(B_out):
+            col = b * spec.C + np.arange(nseg) % spec.C
+            v = np.where(col < spec.d_out, bias[np.minimum(col, spec.d_out - 1)], 0.0)
+            bz[b] = np.repeat(v, spec.m)
+        B.ckks_weights_set_bias(w, torch.from_numpy(cl.enc.encode(bz, scale)).cuda(), int(scale))
+    torch.cuda.synchronize()
+    log(f"[bench] {G * n1 * B_out * N2} weight diagonals encoded and expanded in {time.time() - t0:.1f}s")
+    ref = X @ Wm + (bias if bias is not None else 0.0)
+    return dict(ct_x=ct_x, w=w, baby=baby, giant=giant, ref=ref, G=G, B_out=B_out, N2=N2, scale=scale, level=level)
+
+
+def cpu_baseline(W, spec, n1):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    import oracle
+    from oracle import encoding as E
+    ring = spec.ring
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    q = oracle.find_primes(50, ring.logN, 24)
+    p = oracle.find_primes(60, ring.logN, 8)
+    O = oracle.Oracle(ring.logN, q, p, ring.dnum)
+    r = W.rng(spec.seed + 1000)
+    s = W.ternary_secret(r, O.N)
+
+    def key(step):
+        a = W.uniform_residues(r, O.moduli, O.N, lead=(O.dnum,))
+        e = W.gaussian_error(r, (O.dnum, O.N))
+        return O.galois_keygen(s, O.galois_elt(step), a, e)
+
+    # sample: the 128 x 256 x 256 corner of the projection (one input group, one output block):
+    # 256 of the 6912 diagonals, 15 of the 45 hoisted and 15 of the 135 single key switches
+    C, m = spec.C, spec.m
+    N2 = C // n1
+    X, Wm, _ = W.matmul_inputs(spec)
+    X, Wm = X[:, :C], Wm[:C, :C]
+    scale = 2.0 ** ring.log_scale
+    mx = E.encode(E.pack_columns(X, O.n, C) + 0j, scale, O.N)
+    a = W.uniform_residues(r, O.q, O.N)
+    ct = O.encrypt(O.L, mx[0], s, a, W.gaussian_error(r, (O.N,)))[None]
+    diag = E.encode_diagonals(Wm, m, O.N, C, n1, scale)
+    baby = [key(qq * m) for qq in range(1, n1)]
+    giant = [key(pp * n1 * m) for pp in range(1, N2)]
+    t0 = time.time()
+    O.rotate_hoisted(ct[0], O.L, [O.galois_elt(qq * m) for qq in range(n1)], [None] + baby)
+    t_bank = time.time() - t0
+    t0 = time.time()
+    O.rotate_hoisted(ct[0], O.L, [O.galois_elt(n1 * m)], giant[:1])
+    t_single = time.time() - t0
+    t0 = time.time()
+    y = O.ctpt_matmul(O.L, m, 1, 1, n1, N2, diag, None, 0, ct, baby, giant)
+    O.rescale(y, O.L)
+    t_sub = time.time() - t0
+    G, B_out = -(-spec.d_in // C), -(-spec.d_out // C)
+    t_diag = max(t_sub - t_bank - (N2 - 1) * t_single, 0.0)        # 256 diagonals + one rescale
+    full = G * t_bank + G * B_out * t_diag + B_out * (N2 - 1) * t_single
+    ks_per_s = (n1 - 1) / t_bank
+    return dict(value=full * 1e3, unit="ms", cores=cores, kind="oracle",
+                sample=f"128x{C}x{C} corner of the projection run by the oracle in {t_sub + t_bank + t_single:.1f}s "
+                       f"(256/6912 diagonals, {n1 - 1} hoisted + {N2 - 1} single key switches, 1 rescale); "
+                       f"value = {G}*bank + {G * B_out}*diagonals + {B_out * (N2 - 1)}*single switch, extrapolated",
+                key_switches_per_s_hoisted=ks_per_s)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--n1", type=int, default=0, help="baby steps (0 = the configuration's default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are part of "
+              "the path). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2604_09975_amd import binding as B, client as CL, workload as W
+    torch.cuda.set_device(0)
+    spec = W.BERT_QKV
+    n1 = args.n1 or spec.N1
+    ring = spec.ring
+    q = B.ckks_find_primes(50, ring.logN, 24)
+    p = B.ckks_find_primes(60, ring.logN, 8)
+    P = B.ckks_params_create(ring.logN, q, p, ring.dnum)
+    cl = CL.Client(P, spec.seed)
+    S = setup_matmul(B, CL, W, P, cl, spec, n1)
+    N, level, B_out, G, N2 = P.N, S["level"], S["B_out"], S["G"], S["N2"]
+    y = torch.empty((B_out, 2, level, N), dtype=torch.int64, device="cuda")
+    yr = torch.empty((B_out, 2, level - 1, N), dtype=torch.int64, device="cuda")
+
+    def step():
+        _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y)
+        B.ckks_rescale(P, y, level, B_out, yr)
+        return cnt
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    B.ckks_profile_begin(P)
+    t0 = time.time()
+    e0.record()
+    for _ in range(args.steps):
+        cnt = step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.time() - t0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    mac_ms, mac_launches = B.ckks_profile_end(P)
+    mac_ms /= max(mac_launches, 1)
+
+    # correctness of what was timed: decrypt, decode, compare with the fp64 product
+    max_err = None
+    if not args.no_check:
+        out_scale = S["scale"] * S["scale"] / P.q[level - 1]
+        slots = np.stack([cl.decrypt_slots(yr[b], level - 1, out_scale) for b in range(B_out)])
+        Y = CL.unpack_columns(slots.real, spec.m, spec.C, spec.d_out)
+        max_err = float(np.abs(Y - S["ref"]).max())
+        log(f"[bench] decrypted max abs error vs fp64 X@W+b: {max_err:.3e}")
+        if not max_err <= 1e-3:
+            log("[bench] ERROR: decrypted result is outside the 1e-3 bound")
+            sys.exit(1)
+
+    # hoisted rotation batch (N = 2^16, L = 24): 26 rotations + conjugation from one ciphertext
+    steps = [s for s in W.HOISTED_STEPS if s != (1 << 15)]
+    keys = [cl.galois_key(s) for s in steps]
+    ct = cl.encrypt_slots(W.unit_disk_slots(W.rng(W.HOISTED_SEED), P.N // 2), S["scale"], level)
+    rot_out = torch.empty((len(steps), 2, level, N), dtype=torch.int64, device="cuda")
+    B.ckks_rotate_hoisted(P, ct, level, steps, keys, rot_out)
+    torch.cuda.synchronize()
+    reps = 10
+    e0.record()
+    for _ in range(reps):
+        B.ckks_rotate_hoisted(P, ct, level, steps, keys, rot_out)
+    e1.record()
+    torch.cuda.synchronize()
+    rot_ms = e0.elapsed_time(e1) / reps
+    ks_per_s = len(steps) / rot_ms * 1e3
+
+    # algorithmic bytes of one diagonal multiply-accumulate launch: every weight limb once, the bank once,
+    # the accumulators once (8 bytes per residue)
+    limb_poly = 8 * N
+    mac_bytes = (G * n1 * B_out * N2 * level + G * n1 * 2 * level + B_out * N2 * 2 * level) * limb_poly
+    achieved = mac_bytes / (mac_ms * 1e-3) / 1e9
+    ks_bytes = 188.7e6
+    out = {
+        "metric": "ct-pt matmul latency ms (128x768x2304)",
+        "value": ms_per_step,
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {"workload": spec.name, "N": N, "q_limbs": P.L, "special_limbs": P.K, "dnum": P.dnum,
+                   "log_scale": ring.log_scale, "m": spec.m, "d_in": spec.d_in, "d_out": spec.d_out,
+                   "C": spec.C, "G": G, "B_out": B_out, "N1": n1, "N2": N2,
+                   "key_switches_per_step": int(cnt.key_switches), "ptmuls_per_step": int(cnt.ptmuls),
+                   "limb_ntts_per_step": int(cnt.limb_ntts)},
+        "key_switches_per_s": ks_per_s,
+        "hoisted_batch": {"key_switches": len(steps), "ms": rot_ms,
+                          "hbm_roofline_frac": ks_bytes * ks_per_s / (HBM_PEAK_GBS * 1e9)},
+        "matmul_hbm_roofline_frac": (90.0e9 / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
+        "max_abs_err": max_err,
+        "wall_s_timed_region": wall,
+        "roofline": {"bound": "hbm", "kernel": "diag_mac_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": mac_bytes, "ms_per_launch": mac_ms},
+    }
+    if not args.no_cpu_baseline:
+        t0 = time.time()
+        out["cpu_baseline"] = cpu_baseline(W, spec, n1)
+        log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -146,6 +146,39 @@ int ckks_ctpt_matmul(ckks_params_t *params, const ckks_weights_t *w, const uint6
 int ckks_rescale(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct,
                  uint64_t *d_ct_out, void *stream);
 
+/* Timing of the diagonal multiply-accumulate kernel inside ckks_ctpt_matmul (the kernel that streams
+ * the weights, i.e. the path's byte mover): between begin and end every launch is bracketed by HIP
+ * events on the call's stream.  end synchronises `stream` and returns the summed kernel time in ms
+ * and the number of launches. */
+int ckks_profile_begin(ckks_params_t *params);
+int ckks_profile_end(ckks_params_t *params, void *stream, double *total_ms, uint32_t *launches);
+
+/* ---- key holder's side (the client of Sec. 2.3: KeyGen, Enc, Dec) ----------
+ * Randomness is drawn by the caller and passed in, so results are reproducible
+ * and comparable bit for bit.  None of these calls is on the server's path. */
+typedef struct ckks_secret ckks_secret_t;
+
+/* Secret key s in {-1,0,1}^N (host, int8): keeps NTT(s) on every limb on the device. */
+int ckks_client_secret_load(const ckks_params_t *params, const int8_t *s, void *stream, ckks_secret_t **out);
+void ckks_client_secret_destroy(ckks_secret_t *secret);
+
+/* Galois key for `galois_elt`: b_j = -a_j*s + e_j + [P*T_j]*sigma_g(s), key[j] = (b_j, a_j), where
+ * [P*T_j] is P mod q_i on the limbs of digit j and 0 elsewhere.  d_a [dnum][L+K][N] uniform
+ * residues (taken as NTT-domain values), d_e int64 [dnum][N] small errors (coefficients),
+ * d_key out [dnum][2][L+K][N] canonical, NTT domain (the layout ckks_galois_key_load takes). */
+int ckks_client_galois_keygen(ckks_params_t *params, const ckks_secret_t *secret, uint64_t galois_elt,
+                              const uint64_t *d_a, const int64_t *d_e, uint64_t *d_key, void *stream);
+
+/* Symmetric encryption at `level`: c1 = a, c0 = -a*s + e + m.  d_m int64 [N] encoded plaintext
+ * coefficients, d_a [level][N] uniform residues (NTT domain), d_e int64 [N]; d_ct out [2][level][N]. */
+int ckks_client_encrypt(ckks_params_t *params, const ckks_secret_t *secret, uint32_t level, const int64_t *d_m,
+                        const uint64_t *d_a, const int64_t *d_e, uint64_t *d_ct, void *stream);
+
+/* c0 + c1*s on the first nlimbs limbs, coefficient domain: d_out [nlimbs][N] canonical residues
+ * (the caller lifts them by CRT and decodes). */
+int ckks_client_decrypt(ckks_params_t *params, const ckks_secret_t *secret, const uint64_t *d_ct, uint32_t level,
+                        uint32_t nlimbs, uint64_t *d_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

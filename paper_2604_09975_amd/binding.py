@@ -222,3 +222,76 @@ def ckks_rescale(P, d_ct_in, level_in, n_ct, d_ct_out=None):
         d_ct_out = torch.empty((n_ct, 2, max(level_in - 1, 1), P.N), dtype=torch.int64, device=d_ct_in.device)
     _check(lib.ckks_rescale(P.h, _dev(d_ct_in), level_in, n_ct, _dev(d_ct_out), _stream()))
     return d_ct_out
+
+
+lib.ckks_profile_begin.argtypes = [_vp]
+lib.ckks_profile_begin.restype = C.c_int
+lib.ckks_profile_end.argtypes = [_vp, _vp, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]
+lib.ckks_profile_end.restype = C.c_int
+
+
+def ckks_profile_begin(P):
+    _check(lib.ckks_profile_begin(P.h))
+
+
+def ckks_profile_end(P):
+    """-> (total ms of the diagonal multiply-accumulate kernel, launches) since ckks_profile_begin."""
+    ms, n = C.c_double(), C.c_uint32()
+    _check(lib.ckks_profile_end(P.h, _stream(), C.byref(ms), C.byref(n)))
+    return ms.value, n.value
+
+
+# ---- key holder's side -------------------------------------------------------
+class Secret(Handle):
+    _destroy = "ckks_client_secret_destroy"
+
+
+_i8p = C.POINTER(C.c_int8)
+for _n, _a in {
+    "ckks_client_secret_load": [_vp, _i8p, _vp, C.POINTER(_vp)],
+    "ckks_client_galois_keygen": [_vp, _vp, C.c_uint64, _vp, _vp, _vp, _vp],
+    "ckks_client_encrypt": [_vp, _vp, C.c_uint32, _vp, _vp, _vp, _vp, _vp],
+    "ckks_client_decrypt": [_vp, _vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
+}.items():
+    getattr(lib, _n).argtypes = _a
+    getattr(lib, _n).restype = C.c_int
+lib.ckks_client_secret_destroy.argtypes = [_vp]
+lib.ckks_client_secret_destroy.restype = None
+
+
+def ckks_client_secret_load(P, s):
+    """s: numpy int8 [N] ternary."""
+    import numpy as np
+    s = np.ascontiguousarray(s, dtype=np.int8)
+    if s.shape != (P.N,):
+        raise ValueError("secret must be int8 [N]")
+    h = _vp()
+    _check(lib.ckks_client_secret_load(P.h, s.ctypes.data_as(_i8p), _stream(), C.byref(h)))
+    return Secret(h)
+
+
+def ckks_client_galois_keygen(P, S, galois_elt, d_a, d_e, d_key=None):
+    W = P.L + P.K
+    if d_a.numel() != P.dnum * W * P.N or d_e.numel() != P.dnum * P.N:
+        raise ValueError("a must be [dnum][L+K][N], e [dnum][N]")
+    if d_key is None:
+        d_key = torch.empty((P.dnum, 2, W, P.N), dtype=torch.int64, device=d_a.device)
+    _check(lib.ckks_client_galois_keygen(P.h, S.h, galois_elt, _dev(d_a), _dev(d_e), _dev(d_key), _stream()))
+    return d_key
+
+
+def ckks_client_encrypt(P, S, level, d_m, d_a, d_e, d_ct=None):
+    if d_m.numel() != P.N or d_e.numel() != P.N or d_a.numel() != level * P.N:
+        raise ValueError("m, e must be [N], a [level][N]")
+    if d_ct is None:
+        d_ct = torch.empty((2, level, P.N), dtype=torch.int64, device=d_a.device)
+    _check(lib.ckks_client_encrypt(P.h, S.h, level, _dev(d_m), _dev(d_a), _dev(d_e), _dev(d_ct), _stream()))
+    return d_ct
+
+
+def ckks_client_decrypt(P, S, d_ct, level, nlimbs):
+    if d_ct.numel() != 2 * level * P.N:
+        raise ValueError("ciphertext must be [2][level][N]")
+    out = torch.empty((nlimbs, P.N), dtype=torch.int64, device=d_ct.device)
+    _check(lib.ckks_client_decrypt(P.h, S.h, _dev(d_ct), level, nlimbs, _dev(out), _stream()))
+    return out

@@ -67,6 +67,10 @@ struct ckks_params {
     void *d_scratch = nullptr;
     size_t scratch_bytes = 0;
 
+    // optional timing of the diagonal multiply-accumulate kernel (ckks_profile_*)
+    bool prof_on = false;
+    std::vector<hipEvent_t> prof_ev;   // start/stop pairs
+    size_t prof_used = 0;
     mutable uint64_t limb_ntts = 0;    // limb transforms launched so far (for the operation counters)
 
     int ensure_scratch(size_t bytes, hipStream_t stream);

@@ -294,9 +294,21 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     u64 maxq = 0;
     for (u32 i = 0; i < level; ++i) maxq = std::max(maxq, P->mod[i]);
     const u32 flush = (u32)std::min<u64>(1u << 30, (~0ull) / maxq);
+    if (P->prof_on) {
+        while (P->prof_ev.size() < P->prof_used + 2) {
+            hipEvent_t ev;
+            CKKS_HIP(hipEventCreate(&ev));
+            P->prof_ev.push_back(ev);
+        }
+        CKKS_HIP(hipEventRecord(P->prof_ev[P->prof_used], stream));
+    }
     hipLaunchKernelGGL(diag_mac_kernel, dim3((BP + MM_TB - 1) / MM_TB, N / MM_THREADS, level), dim3(MM_THREADS), 0,
                        stream, d_bank, w->d_w, d_acc, P->d_mod, level, N, GQ, BP, flush);
     CKKS_LAUNCH_CHECK("diag_mac_kernel");
+    if (P->prof_on) {
+        CKKS_HIP(hipEventRecord(P->prof_ev[P->prof_used + 1], stream));
+        P->prof_used += 2;
+    }
     // 3. giant steps: y_b = acc_{b,0} + sum_p rot(acc_{b,p})
     for (u32 b = 0; b < B; ++b)
         CKKS_HIP(hipMemcpyAsync(d_ct_y + (size_t)b * ctw, d_acc + (size_t)b * N2 * ctw, ctw * sizeof(u64),
@@ -350,6 +362,35 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         counters->ptmuls = (u64)GQ * BP;
         counters->limb_ntts = P->limb_ntts - ntt0;
     }
+    return CKKS_OK;
+}
+
+int ckks_profile_begin(ckks_params_t *P) {
+    if (!P) {
+        set_error("ckks_profile_begin: params is null");
+        return CKKS_E_INVAL;
+    }
+    P->prof_on = true;
+    P->prof_used = 0;
+    return CKKS_OK;
+}
+
+int ckks_profile_end(ckks_params_t *P, void *stream, double *total_ms, uint32_t *launches) {
+    if (!P || !total_ms || !launches) {
+        set_error("ckks_profile_end: null argument");
+        return CKKS_E_INVAL;
+    }
+    CKKS_HIP(hipStreamSynchronize((hipStream_t)stream));
+    double sum = 0;
+    for (size_t i = 0; i + 1 < P->prof_used; i += 2) {
+        float ms = 0;
+        CKKS_HIP(hipEventElapsedTime(&ms, P->prof_ev[i], P->prof_ev[i + 1]));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (uint32_t)(P->prof_used / 2);
+    P->prof_on = false;
+    P->prof_used = 0;
     return CKKS_OK;
 }
 

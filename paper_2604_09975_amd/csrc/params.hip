@@ -207,6 +207,10 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
         set_error("ckks_params_create: L=%u not divisible by dnum=%u", L, dnum);
         return CKKS_E_INVAL;
     }
+    if (dnum > 16) {   // the key inner product sums dnum 124-bit products in 128 bits
+        set_error("ckks_params_create: dnum=%u > 16", dnum);
+        return CKKS_E_INVAL;
+    }
     if (L + K > MAX_LIMBS || L / dnum > MAX_DIGIT || K > MAX_DIGIT) {
         set_error("ckks_params_create: L+K=%u > %u, or digit/special count > %u", L + K, MAX_LIMBS, MAX_DIGIT);
         return CKKS_E_INVAL;
@@ -317,6 +321,7 @@ void ckks_params_destroy(ckks_params_t *P) {
         hipFree(kv.second.d_up_mat);
     }
     hipFree(P->d_scratch);
+    for (hipEvent_t ev : P->prof_ev) hipEventDestroy(ev);
     delete P;
 }
 

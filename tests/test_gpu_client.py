@@ -1,0 +1,63 @@
+"""GPU parity: the key holder's calls (keygen, encrypt, decrypt) against the oracle, bit for bit,
+and the host encoder against the oracle's within rounding."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import encoding as E
+from tests import helpers
+from tests.gpu_util import make_pair, to_dev, to_host
+from paper_2604_09975_amd import workload as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("spec", [W.TOY_RING, W.BIG_RING], ids=["toy", "big"])
+def test_keygen_encrypt_decrypt_bit_exact(spec):
+    from paper_2604_09975_amd import binding as B
+    O, P = make_pair(spec)
+    r = W.rng(77)
+    s = W.ternary_secret(r, O.N)
+    S = B.ckks_client_secret_load(P, s)
+    level = O.L
+    for step in (1, "conj"):
+        g = O.galois_elt(step)
+        a = W.uniform_residues(r, O.moduli, O.N, lead=(O.dnum,))
+        e = W.gaussian_error(r, (O.dnum, O.N))
+        got = to_host(B.ckks_client_galois_keygen(P, S, g, to_dev(a), to_dev(e)))
+        assert (got == O.galois_keygen(s, g, a, e)).all()
+    m = E.encode(W.unit_disk_slots(r, O.n), 2.0**spec.log_scale, O.N)
+    m[:4] = (0, -1, 1, -(1 << 42))
+    for lvl in (level, 1):
+        a = W.uniform_residues(r, O.q[:lvl], O.N)
+        e = W.gaussian_error(r, (O.N,))
+        ct = B.ckks_client_encrypt(P, S, lvl, to_dev(m), to_dev(a), to_dev(e))
+        want = O.encrypt(lvl, m, s, a, e)
+        assert (to_host(ct) == want).all()
+        nl = min(lvl, 2)
+        dec = to_host(B.ckks_client_decrypt(P, S, ct, lvl, nl))
+        assert (dec == O.decrypt(want, lvl, s, nl)).all()
+
+
+def test_host_encoder_matches_oracle_encoder():
+    from paper_2604_09975_amd import client as CL
+    r = W.rng(3)
+    for N in (1 << 5, 1 << 12, 1 << 16):
+        enc = CL.Encoder(N)
+        z = W.unit_disk_slots(r, N // 2)
+        a, b = enc.encode(z, 2.0**40), E.encode(z, 2.0**40, N)
+        assert np.abs(a - b).max() <= 1                      # two fp64 evaluations may round a near-tie apart
+        assert np.abs(enc.decode(a, 2.0**40) - z).max() < 1e-7
+    X = r.standard_normal((4, 40))
+    assert (CL.pack_columns(X, 128, 16) == E.pack_columns(X, 128, 16)).all()
+    Wm = r.standard_normal((40, 20))
+    for b in range(2):
+        for p in range(4):
+            d = CL.diagonal_slots(Wm, 4, 128, 16, 4, b, p)
+            for g in range(3):
+                for q in range(4):
+                    assert (d[g, q] == E.weight_diagonal(Wm, 4, 128, 16, 4, b, p, g, q)).all()
+    sl = r.standard_normal((2, 128))
+    assert (CL.unpack_columns(sl, 4, 16, 20) == E.unpack_columns(sl, 4, 16, 20)).all()
+    res = np.array([[5, 0, 7], [1, 3, 2]], dtype=np.uint64)
+    assert CL.centred_crt(res, [11, 13]) == E.crt_centre(res, [11, 13])

@@ -67,7 +67,9 @@ def test_full_size_hoisted_batch():
     for s in (1, 1 << 14, "conj"):
         zz = cl.decrypt_slots(got[steps.index(s)], 24, 2.0**40)
         want = np.conj(z) if s == "conj" else np.roll(z, -s)
-        assert np.abs(zz - want).max() < 1e-6
+        # worst-case coefficient error of one switch here is (K+1)(1+h) = 585 (the P-part is negligible);
+        # a slot sums N coefficients
+        assert np.abs(zz - want).max() < 585 * O.N / 2.0**40
 
 
 def test_rotate_errors():
