@@ -9,7 +9,7 @@ LIB = os.path.join(HERE, "libckks_hip.so")
 SOURCES = ["params.hip", "ntt.hip", "keyswitch.hip", "matmul.hip", "client.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-Wno-unused-value", "-Wno-unused-result"]
+         "-ffp-contract=off", "-Wall", "-Wno-unused-function", "-Wno-unused-value", "-Wno-unused-result"]
 
 
 def _stale(out, deps):

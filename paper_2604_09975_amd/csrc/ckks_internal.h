@@ -23,6 +23,13 @@ struct LimbIds {
     uint8_t id[MAX_ROW_IDS];
 };
 
+// fp64 view of a modulus below 2^50: residues, twiddles and products are exact integers in doubles
+struct ModFp {
+    double q, u;           // q and its rounded reciprocal
+    double ninv, ninv_w;   // N^-1 and N^-1 * psi^-(N/2) as plain integers
+    u32 ok, pad;           // 1 if q < 2^50 (the FMA butterflies apply)
+};
+
 void set_error(const char *fmt, ...);
 int hip_fail(hipError_t e, const char *what);
 
@@ -57,6 +64,9 @@ struct ckks_params {
     ckks::u64 *d_tw_fwd = nullptr;     // [W][N]: psi^bitrev(idx), Montgomery form, idx in [1, N)
     ckks::u64 *d_tw_inv = nullptr;     // [W][N]: psi^-bitrev(idx), Montgomery form
     ckks::u64 *d_ninv = nullptr;       // [W][2]: N^-1 and N^-1 * psi^-(N/2), Montgomery form
+    ckks::ModFp *d_modf = nullptr;     // [W]
+    double *d_twf_fwd = nullptr;       // [W][N]: psi^bitrev(idx) as a double (limbs below 2^50 only)
+    double *d_twf_inv = nullptr;       // [W][N]
     // ModDown tables (independent of the level)
     ckks::u64 *d_dn_inv = nullptr;     // [K]: (P/p_k)^-1 mod p_k
     ckks::u64 *d_dn_mat = nullptr;     // [K][L]: P/p_k mod q_i

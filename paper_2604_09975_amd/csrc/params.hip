@@ -257,6 +257,8 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     }
     std::vector<u64> fwd((size_t)W * N, 0), inv((size_t)W * N, 0), ninv((size_t)W * 2);
     std::vector<u64> pw(2 * (size_t)N);
+    std::vector<double> fwd_f((size_t)W * N, 0.0), inv_f((size_t)W * N, 0.0);
+    std::vector<ModFp> modf(W);
     for (u32 i = 0; i < W; ++i) {
         const ModConst &m = P->hmod[i];
         pw[0] = 1;
@@ -269,6 +271,21 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
         u64 ni = hinv(N % m.q, m.q);
         ninv[2 * i] = to_mont(ni, m);
         ninv[2 * i + 1] = to_mont(hmul(ni, pw[2 * N - N / 2], m.q), m);
+        // primes below 2^50 also get plain-integer twiddles as doubles for the FMA butterflies
+        ModFp f;
+        f.q = (double)m.q;
+        f.u = 1.0 / (double)m.q;
+        f.ninv = (double)ni;
+        f.ninv_w = (double)hmul(ni, pw[2 * N - N / 2], m.q);
+        f.ok = (m.q >> 50) == 0;
+        f.pad = 0;
+        modf[i] = f;
+        if (f.ok)
+            for (u32 idx = 1; idx < N; ++idx) {
+                u32 e = bitrev(idx, logN);
+                fwd_f[(size_t)i * N + idx] = (double)pw[e];
+                inv_f[(size_t)i * N + idx] = (double)pw[2 * N - e];
+            }
     }
     std::vector<u64> dn_inv(K), dn_mat((size_t)K * L), pinv(L), qlinv((size_t)L * L, 0);
     for (u32 k = 0; k < K; ++k) {
@@ -294,6 +311,9 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     if (!rc) rc = upload(&P->d_tw_fwd, fwd);
     if (!rc) rc = upload(&P->d_tw_inv, inv);
     if (!rc) rc = upload(&P->d_ninv, ninv);
+    if (!rc) rc = upload(&P->d_modf, modf);
+    if (!rc) rc = upload(&P->d_twf_fwd, fwd_f);
+    if (!rc) rc = upload(&P->d_twf_inv, inv_f);
     if (!rc) rc = upload(&P->d_dn_inv, dn_inv);
     if (!rc) rc = upload(&P->d_dn_mat, dn_mat);
     if (!rc) rc = upload(&P->d_pinv, pinv);
@@ -312,6 +332,9 @@ void ckks_params_destroy(ckks_params_t *P) {
     hipFree(P->d_tw_fwd);
     hipFree(P->d_tw_inv);
     hipFree(P->d_ninv);
+    hipFree(P->d_modf);
+    hipFree(P->d_twf_fwd);
+    hipFree(P->d_twf_inv);
     hipFree(P->d_dn_inv);
     hipFree(P->d_dn_mat);
     hipFree(P->d_pinv);
