@@ -96,7 +96,7 @@ struct ckks_gkey {
 struct ckks_weights {
     const ckks_params *params = nullptr;
     ckks::u32 level = 0, m = 0, C = 0, G = 0, B_out = 0, N1 = 0, N2 = 0;
-    ckks::u64 *d_w = nullptr;          // [B_out][N2][G][N1][level][N], NTT domain, Montgomery form
+    ckks::u64 *d_w = nullptr;          // [B_out][N2][G][N1][level][N], NTT domain; per limb a double (q < 2^50) or Montgomery form
     ckks::u64 *d_bias = nullptr;       // [B_out][level][N], NTT domain, canonical, times bias_mul; or null
 };
 
@@ -117,7 +117,7 @@ struct SwitchItem {
 };
 size_t digits_words(const ckks_params *p, u32 level);
 size_t switch_scratch_words(const ckks_params *p, u32 level, u32 n_items);
-int decompose(ckks_params *p, const u64 *d_c1, u32 level, u64 *d_digits, u64 *d_tmp, hipStream_t stream);
+int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_digits, u64 *d_tmp, hipStream_t stream);
 int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream);
 
 }  // namespace ckks

@@ -30,32 +30,52 @@ __device__ __forceinline__ u32 galois_index(u32 k, u64 g, u32 logN) {
     return __brev((e2 - 1u) >> 1) >> (32 - logN);
 }
 
-// y_i = c_i * (Q_D/q_i)^-1 mod q_i for the limbs of digit j, then for every target t outside the digit
-// out_t = sum_i y_i * (Q_D/q_i mod t) mod t.
-__global__ __launch_bounds__(KS_THREADS) void modup_kernel(const u64 *__restrict__ c1_coeff, u64 *__restrict__ digits,
+struct PtrPack {
+    const u64 *p[ROT_BATCH];
+};
+
+// tmp[r][i][n] = src_r[i][n]: collects the c1 halves of up to ROT_BATCH ciphertexts
+__global__ __launch_bounds__(KS_THREADS) void gather_c1_kernel(PtrPack src, u64 *__restrict__ tmp, u32 level, u32 N) {
+    const u32 n = blockIdx.x * KS_THREADS + threadIdx.x;
+    const u32 i = blockIdx.y, r = blockIdx.z;
+    tmp[((size_t)r * level + i) * N + n] = src.p[r][(size_t)i * N + n];
+}
+
+// Per ciphertext r and digit j: y_i = c_i * (Q_D/q_i)^-1 mod q_i for the limbs of the digit, then for
+// every target t outside the digit out_t = sum_i y_i * (Q_D/q_i mod t) mod t (coefficient domain).
+// Targets inside the digit are copied from the NTT-domain input (they need no transform).
+// grid: x = coefficients, y = digit, z = r * chunks + chunk of UP_CHUNK targets.
+__global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, const u64 *__restrict__ c1_coeff,
+                                                           u64 *__restrict__ digits,
                                                            const ModConst *__restrict__ mods,
                                                            const u64 *__restrict__ up_inv,
                                                            const u64 *__restrict__ up_mat, u32 level, u32 K, u32 L,
-                                                           u32 alpha, u32 N) {
+                                                           u32 alpha, u32 N, u32 chunks, u32 beta) {
     const u32 n = blockIdx.x * KS_THREADS + threadIdx.x;
     const u32 j = blockIdx.y;
+    const u32 r = blockIdx.z / chunks, chunk = blockIdx.z % chunks;
     const u32 Wl = level + K;
     const u32 lo = j * alpha, hi = min(lo + alpha, level);
+    const u64 *coef = c1_coeff + (size_t)r * level * N;
+    u64 *dig = digits + (size_t)r * beta * Wl * N;
     u64 y[MAX_DIGIT];
 #pragma unroll
     for (u32 a = 0; a < MAX_DIGIT; ++a) {
         y[a] = 0;
-        if (lo + a < hi) y[a] = mont_mul(c1_coeff[(size_t)(lo + a) * N + n], up_inv[lo + a], mods[lo + a]);
+        if (lo + a < hi) y[a] = mont_mul(coef[(size_t)(lo + a) * N + n], up_inv[lo + a], mods[lo + a]);
     }
-    const u32 t0 = blockIdx.z * UP_CHUNK, t1 = min(t0 + UP_CHUNK, Wl);
+    const u32 t0 = chunk * UP_CHUNK, t1 = min(t0 + UP_CHUNK, Wl);
     for (u32 t = t0; t < t1; ++t) {
-        if (t >= lo && t < hi) continue;
+        if (t >= lo && t < hi) {
+            dig[((size_t)j * Wl + t) * N + n] = src_ntt.p[r][(size_t)t * N + n];
+            continue;
+        }
         const u32 gl = t < level ? t : L + (t - level);
         u128 acc = {0, 0};
 #pragma unroll
         for (u32 a = 0; a < MAX_DIGIT; ++a)
             if (lo + a < hi) mac(acc, y[a], up_mat[(size_t)(lo + a) * Wl + t]);
-        digits[((size_t)j * Wl + t) * N + n] = redc(acc, mods[gl]);
+        dig[((size_t)j * Wl + t) * N + n] = redc(acc, mods[gl]);
     }
 }
 
@@ -141,23 +161,30 @@ size_t switch_scratch_words(const ckks_params *p, u32 level, u32 n_items) {
     return (size_t)n_items * 2 * ((size_t)(level + p->K) + level) * p->N;
 }
 
-// d_c1 [level][N] NTT domain -> d_digits [beta][level+K][N] NTT domain; d_tmp [level][N] scratch.
-int decompose(ckks_params *p, const u64 *d_c1, u32 level, u64 *d_digits, u64 *d_tmp, hipStream_t stream) {
+// c1[r] [level][N] NTT domain (n <= ROT_BATCH device pointers) -> d_digits [n][beta][level+K][N] NTT domain;
+// d_tmp [n][level][N] scratch.
+int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_digits, u64 *d_tmp,
+              hipStream_t stream) {
+    if (n == 0) return CKKS_OK;
     const u32 N = p->N, K = p->K, L = p->L, Wl = level + K, alpha = p->alpha;
     const LevelTables *lt = nullptr;
     int rc = p->level_tables(level, &lt);
     if (rc) return rc;
     const u32 beta = lt->beta;
-    CKKS_HIP(hipMemcpyAsync(d_tmp, d_c1, sizeof(u64) * level * N, hipMemcpyDeviceToDevice, stream));
+    PtrPack src;
+    for (u32 r = 0; r < ROT_BATCH; ++r) src.p[r] = c1[r < n ? r : 0];
+    hipLaunchKernelGGL(gather_c1_kernel, dim3(N / KS_THREADS, level, n), dim3(KS_THREADS), 0, stream, src, d_tmp,
+                       level, N);
+    CKKS_LAUNCH_CHECK("gather_c1_kernel");
     LimbIds ids;
     for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
-    rc = launch_ntt(p, d_tmp, ids, level, level, true, stream);
+    rc = launch_ntt(p, d_tmp, ids, level, n * level, true, stream);
     if (rc) return rc;
-    dim3 grid(N / KS_THREADS, beta, (Wl + UP_CHUNK - 1) / UP_CHUNK);
-    hipLaunchKernelGGL(modup_kernel, grid, dim3(KS_THREADS), 0, stream, d_tmp, d_digits, p->d_mod, lt->d_up_inv,
-                       lt->d_up_mat, level, K, L, alpha, N);
+    const u32 chunks = (Wl + UP_CHUNK - 1) / UP_CHUNK;
+    hipLaunchKernelGGL(modup_kernel, dim3(N / KS_THREADS, beta, n * chunks), dim3(KS_THREADS), 0, stream, src, d_tmp,
+                       d_digits, p->d_mod, lt->d_up_inv, lt->d_up_mat, level, K, L, alpha, N, chunks, beta);
     CKKS_LAUNCH_CHECK("modup_kernel");
-    // forward NTT of the converted rows; the digit's own limbs are copied from the input instead
+    // forward NTT of the converted rows; the digit's own limbs were copied and are skipped
     auto row_id = [&](u32 j, u32 t) -> uint8_t {
         u32 lo = j * alpha, hi = std::min(lo + alpha, level);
         if (t >= lo && t < hi) return (uint8_t)SKIP_ROW;
@@ -166,19 +193,15 @@ int decompose(ckks_params *p, const u64 *d_c1, u32 level, u64 *d_digits, u64 *d_
     if (beta * Wl <= MAX_ROW_IDS) {
         for (u32 j = 0; j < beta; ++j)
             for (u32 t = 0; t < Wl; ++t) ids.id[j * Wl + t] = row_id(j, t);
-        rc = launch_ntt(p, d_digits, ids, beta * Wl, beta * Wl, false, stream);
+        rc = launch_ntt(p, d_digits, ids, beta * Wl, n * beta * Wl, false, stream);
         if (rc) return rc;
     } else {
-        for (u32 j = 0; j < beta; ++j) {
-            for (u32 t = 0; t < Wl; ++t) ids.id[t] = row_id(j, t);
-            rc = launch_ntt(p, d_digits + (size_t)j * Wl * N, ids, Wl, Wl, false, stream);
-            if (rc) return rc;
-        }
-    }
-    for (u32 j = 0; j < beta; ++j) {
-        u32 lo = j * alpha, hi = std::min(lo + alpha, level);
-        CKKS_HIP(hipMemcpyAsync(d_digits + ((size_t)j * Wl + lo) * N, d_c1 + (size_t)lo * N,
-                                sizeof(u64) * (hi - lo) * N, hipMemcpyDeviceToDevice, stream));
+        for (u32 r = 0; r < n; ++r)
+            for (u32 j = 0; j < beta; ++j) {
+                for (u32 t = 0; t < Wl; ++t) ids.id[t] = row_id(j, t);
+                rc = launch_ntt(p, d_digits + ((size_t)r * beta + j) * Wl * N, ids, Wl, Wl, false, stream);
+                if (rc) return rc;
+            }
     }
     return CKKS_OK;
 }
@@ -316,7 +339,8 @@ int ckks_rotate_hoisted(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t leve
     int rc = P->ensure_scratch((dig_w + tmp_w + switch_scratch_words(P, level, batch)) * sizeof(u64), stream);
     if (rc) return rc;
     u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + dig_w, *d_work = d_tmp + tmp_w;
-    rc = decompose(P, d_ct_in + (size_t)level * N, level, d_digits, d_tmp, stream);
+    const u64 *c1 = d_ct_in + (size_t)level * N;
+    rc = decompose(P, &c1, 1, level, d_digits, d_tmp, stream);
     if (rc) return rc;
     for (auto &it : items) it.digits = d_digits;
     for (size_t done = 0; done < items.size(); done += batch) {

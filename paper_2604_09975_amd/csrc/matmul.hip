@@ -37,20 +37,81 @@ __global__ __launch_bounds__(EW_THREADS) void scale_rows_kernel(u64 *data, const
     data[idx] = mont_mul(data[idx], cm, m);
 }
 
-// acc[bp][comp][i][k] = sum_{gq} bank[gq][comp][i][k] * w[bp][gq][i][k]   (w in Montgomery form)
+// acc[bp][comp][i][k] = sum_{gq} bank[gq][comp][i][k] * w[bp][gq][i][k]
 // grid: x = tile of MM_TB (b,p) pairs (fastest, so neighbouring workgroups share their bank lines in L2),
 //       y = run of 256 coefficients, z = limb (slowest: one limb's bank slice stays cache-resident).
-// flush: number of products that fit a 128-bit lazy sum for the largest modulus.
+// Weight limbs are stored in the library's internal form: for a prime below 2^50 the residue as a
+// double (products are then reduced with the exact FMA scheme of the NTT butterflies and summed as
+// signed doubles, about 7 issue slots per product), otherwise in Montgomery form (128-bit lazy sums;
+// flush = number of products that fit such a sum for the largest modulus).
+// blockIdx.z indexes `limbs`, the list of limbs this launch covers (fp64 limbs and Montgomery limbs
+// go to separate launches so that each kernel keeps its own register budget).
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restrict__ bank,
                                                               const u64 *__restrict__ w, u64 *__restrict__ acc,
-                                                              const ModConst *__restrict__ mods, u32 level, u32 N,
-                                                              u32 GQ, u32 BP, u32 flush) {
+                                                              const ModFp *__restrict__ modf, LimbIds limbs,
+                                                              u32 level, u32 N, u32 GQ, u32 BP) {
     const u32 bp0 = blockIdx.x * MM_TB;
     const u32 k = blockIdx.y * MM_THREADS + threadIdx.x;
-    const u32 i = blockIdx.z;
-    const ModConst m = mods[i];
+    const u32 i = limbs.id[blockIdx.z];
     const size_t limb_off = (size_t)i * N + k;
     const size_t w_stride = (size_t)level * N;         // between consecutive gq of one (b,p)
+    const ModFp mf = modf[i];
+    {
+        const double q = mf.q, u = mf.u;
+        const double *wf = reinterpret_cast<const double *>(w);
+        double a0[MM_TB], a1[MM_TB];
+#pragma unroll
+        for (u32 t = 0; t < MM_TB; ++t) a0[t] = a1[t] = 0.0;
+        for (u32 gq = 0; gq < GQ; ++gq) {
+            const u64 r0 = bank[((size_t)gq * 2 + 0) * w_stride + limb_off];
+            const u64 r1 = bank[((size_t)gq * 2 + 1) * w_stride + limb_off];
+            const double x0 = __longlong_as_double((long long)(r0 | 0x4330000000000000ull)) - 4503599627370496.0;
+            const double x1 = __longlong_as_double((long long)(r1 | 0x4330000000000000ull)) - 4503599627370496.0;
+#pragma unroll
+            for (u32 t = 0; t < MM_TB; ++t) {
+                if (bp0 + t < BP) {
+                    const double wv = wf[((size_t)(bp0 + t) * GQ + gq) * w_stride + limb_off];
+                    // x*w = h + l exactly; subtract the nearest multiple of q: |r| < 0.9 q
+                    const double h0 = x0 * wv, h1 = x1 * wv;
+                    const double l0 = fma(x0, wv, -h0), l1 = fma(x1, wv, -h1);
+                    const double c0 = rint(h0 * u), c1 = rint(h1 * u);
+                    a0[t] += fma(-c0, q, h0) + l0;
+                    a1[t] += fma(-c1, q, h1) + l1;
+                }
+            }
+            if ((gq & 7) == 7) {   // keep the signed sums far below 2^53
+#pragma unroll
+                for (u32 t = 0; t < MM_TB; ++t) {
+                    a0[t] = fma(-rint(a0[t] * u), q, a0[t]);
+                    a1[t] = fma(-rint(a1[t] * u), q, a1[t]);
+                }
+            }
+        }
+#pragma unroll
+        for (u32 t = 0; t < MM_TB; ++t) {
+            if (bp0 + t < BP) {
+                double v0 = fma(-rint(a0[t] * u), q, a0[t]), v1 = fma(-rint(a1[t] * u), q, a1[t]);
+                if (v0 < 0) v0 += q;
+                if (v1 < 0) v1 += q;
+                acc[((size_t)(bp0 + t) * 2 + 0) * w_stride + limb_off] =
+                    (u64)__double_as_longlong(v0 + 4503599627370496.0) & 0x000fffffffffffffull;
+                acc[((size_t)(bp0 + t) * 2 + 1) * w_stride + limb_off] =
+                    (u64)__double_as_longlong(v1 + 4503599627370496.0) & 0x000fffffffffffffull;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(MM_THREADS) void diag_mac_int_kernel(const u64 *__restrict__ bank,
+                                                                  const u64 *__restrict__ w, u64 *__restrict__ acc,
+                                                                  const ModConst *__restrict__ mods, LimbIds limbs,
+                                                                  u32 level, u32 N, u32 GQ, u32 BP, u32 flush) {
+    const u32 bp0 = blockIdx.x * MM_TB;
+    const u32 k = blockIdx.y * MM_THREADS + threadIdx.x;
+    const u32 i = limbs.id[blockIdx.z];
+    const size_t limb_off = (size_t)i * N + k;
+    const size_t w_stride = (size_t)level * N;
+    const ModConst m = mods[i];
     u128 a0[MM_TB], a1[MM_TB];
     u64 s0[MM_TB], s1[MM_TB];
 #pragma unroll
@@ -89,6 +150,23 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
             acc[((size_t)(bp0 + t) * 2 + 0) * w_stride + limb_off] = add_mod(s0[t], redc(a0[t], m), m.q);
             acc[((size_t)(bp0 + t) * 2 + 1) * w_stride + limb_off] = add_mod(s1[t], redc(a1[t], m), m.q);
         }
+    }
+}
+
+// canonical residues -> the internal form diag_mac_kernel reads (rows [rows][N], limb = row % period)
+__global__ __launch_bounds__(EW_THREADS) void to_weight_form_kernel(u64 *data, const ModConst *__restrict__ mods,
+                                                                    const ModFp *__restrict__ modf, u32 period,
+                                                                    u32 N) {
+    const u32 n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const u32 row = blockIdx.y;
+    const u32 limb = row % period;
+    const size_t idx = (size_t)row * N + n;
+    const u64 x = data[idx];
+    if (modf[limb].ok) {
+        data[idx] = (u64)__double_as_longlong((double)x);   // exact: x < 2^50
+    } else {
+        const ModConst m = mods[limb];
+        data[idx] = mont_mul(x, m.r2, m);
     }
 }
 
@@ -140,9 +218,9 @@ static int expand_plain(const ckks_params *P, u32 level, const int64_t *d_coeffs
         int rc = launch_ntt(P, o, ids, level, c * level, false, stream);
         if (rc) return rc;
         if (mont) {
-            hipLaunchKernelGGL(to_mont_kernel, dim3(N / EW_THREADS, c * level), dim3(EW_THREADS), 0, stream, o, o,
-                               P->d_mod, level, N);
-            CKKS_LAUNCH_CHECK("to_mont_kernel");
+            hipLaunchKernelGGL(to_weight_form_kernel, dim3(N / EW_THREADS, c * level), dim3(EW_THREADS), 0, stream, o,
+                               P->d_mod, P->d_modf, level, N);
+            CKKS_LAUNCH_CHECK("to_weight_form_kernel");
         }
     }
     return CKKS_OK;
@@ -278,7 +356,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     // persistent buffers of this call live behind the key-switch scratch
     const u32 batch = std::min<u32>(ROT_BATCH, std::max(N1, B));
     const size_t dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
-    const size_t ks_w = batch * dig_w + tmp_w + switch_scratch_words(P, level, batch);
+    const size_t ks_w = batch * (dig_w + tmp_w) + switch_scratch_words(P, level, batch);
     const size_t bank_w = (size_t)GQ * ctw, acc_w = (size_t)BP * ctw;
     int rc = P->ensure_scratch((ks_w + bank_w + acc_w) * sizeof(u64), stream);
     if (rc) return rc;
@@ -302,9 +380,24 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         }
         CKKS_HIP(hipEventRecord(P->prof_ev[P->prof_used], stream));
     }
-    hipLaunchKernelGGL(diag_mac_kernel, dim3((BP + MM_TB - 1) / MM_TB, N / MM_THREADS, level), dim3(MM_THREADS), 0,
-                       stream, d_bank, w->d_w, d_acc, P->d_mod, level, N, GQ, BP, flush);
-    CKKS_LAUNCH_CHECK("diag_mac_kernel");
+    {
+        LimbIds fp_limbs, int_limbs;
+        u32 n_fp = 0, n_int = 0;
+        for (u32 i = 0; i < level; ++i) {
+            if ((P->mod[i] >> 50) == 0)
+                fp_limbs.id[n_fp++] = (uint8_t)i;
+            else
+                int_limbs.id[n_int++] = (uint8_t)i;
+        }
+        const dim3 tiles((BP + MM_TB - 1) / MM_TB, N / MM_THREADS);
+        if (n_fp)
+            hipLaunchKernelGGL(diag_mac_kernel, dim3(tiles.x, tiles.y, n_fp), dim3(MM_THREADS), 0, stream, d_bank,
+                               w->d_w, d_acc, P->d_modf, fp_limbs, level, N, GQ, BP);
+        if (n_int)
+            hipLaunchKernelGGL(diag_mac_int_kernel, dim3(tiles.x, tiles.y, n_int), dim3(MM_THREADS), 0, stream, d_bank,
+                               w->d_w, d_acc, P->d_mod, int_limbs, level, N, GQ, BP, flush);
+        CKKS_LAUNCH_CHECK("diag_mac_kernel");
+    }
     if (P->prof_on) {
         CKKS_HIP(hipEventRecord(P->prof_ev[P->prof_used + 1], stream));
         P->prof_used += 2;
@@ -313,7 +406,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     for (u32 b = 0; b < B; ++b)
         CKKS_HIP(hipMemcpyAsync(d_ct_y + (size_t)b * ctw, d_acc + (size_t)b * N2 * ctw, ctw * sizeof(u64),
                                 hipMemcpyDeviceToDevice, stream));
-    u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + tmp_w;
+    u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + batch * tmp_w;
     for (u32 p = 1; p < N2; ++p) {
         for (u32 b0 = 0; b0 < B; b0 += batch) {
             const u32 nb = std::min(batch, B - b0);
@@ -327,10 +420,12 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                 continue;
             }
             SwitchItem items[ROT_BATCH];
+            const u64 *c1s[ROT_BATCH];
+            for (u32 r = 0; r < nb; ++r) c1s[r] = d_acc + ((size_t)(b0 + r) * N2 + p) * ctw + (size_t)level * N;
+            rc = decompose(P, c1s, nb, level, d_digits, d_tmp, stream);
+            if (rc) return rc;
             for (u32 r = 0; r < nb; ++r) {
                 const u64 *src = d_acc + ((size_t)(b0 + r) * N2 + p) * ctw;
-                rc = decompose(P, src + (size_t)level * N, level, d_digits + (size_t)r * dig_w, d_tmp, stream);
-                if (rc) return rc;
                 items[r].digits = d_digits + (size_t)r * dig_w;
                 items[r].c0 = src;
                 items[r].key = giant_keys[p - 1]->d_key;

@@ -48,7 +48,7 @@ NTT_RING = RingSpec(logN=16, q_bits=(50,) * 24, p_bits=(), dnum=3, log_scale=40,
 
 TOY_MATMUL = MatmulSpec(ring=TOY_RING, m=16, d_in=64, d_out=64, C=64, N1=64, x_dist="uniform1", w_std=0.0,
                         bias=False, seed=SEED_BASE + 0, name="toy_16x64x64")
-BERT_QKV = MatmulSpec(ring=BIG_RING, m=128, d_in=768, d_out=2304, C=256, N1=16, seed=SEED_BASE + 3,
+BERT_QKV = MatmulSpec(ring=BIG_RING, m=128, d_in=768, d_out=2304, C=256, N1=32, seed=SEED_BASE + 3,
                       name="bert_base_qkv_128x768x2304")
 GPT2_LAYERS = (
     MatmulSpec(ring=BIG_RING, m=128, d_in=768, d_out=2304, C=256, N1=16, seed=SEED_BASE + 40, name="gpt2_qkv"),

@@ -72,17 +72,18 @@ def test_toy_config():
     assert cnt.key_switches == 63
 
 
-@pytest.mark.parametrize("N1", [1, 4, 16])
-def test_bsgs_bias_ragged_shapes(N1):
+@pytest.mark.parametrize("N1,qbits,pbits", [(1, 40, 42), (4, 40, 42), (16, 40, 42), (4, 52, 55), (2, 50, 60)])
+def test_bsgs_bias_ragged_shapes(N1, qbits, pbits):
     """n = 512 slots, m = 4, C = 16 (eight periods of the active columns), d_in = 40 (ragged last group),
-    d_out = 20 (ragged last block), bias, every split of the 16 diagonals."""
-    O = helpers.small_oracle(10, L=3, K=1, dnum=3, qbits=40, pbits=42)
+    d_out = 20 (ragged last block), bias, every split of the 16 diagonals; primes below 2^50 (fp64
+    arithmetic inside the library) and above (Montgomery arithmetic)."""
+    O = helpers.small_oracle(10, L=3, K=1, dnum=3, qbits=qbits, pbits=pbits)
     _, P = make_pair(O)
     r = W.rng(9)
     X = r.uniform(-1, 1, (4, 40))
     Wm = r.uniform(-0.5, 0.5, (40, 20))
     bias = r.uniform(-0.5, 0.5, 20)
-    Y, ref, cnt, slots = run_case(O, P, X, Wm, bias, 4, 16, N1, 30, 3, 19, hw=16)
+    Y, ref, cnt, slots = run_case(O, P, X, Wm, bias, 4, 16, N1, qbits - 10, 3, 19, hw=16)
     assert np.abs(Y - ref).max() <= 1e-3
     assert np.abs(slots.imag).max() <= 1e-3
     assert cnt.key_switches == 3 * (N1 - 1) + 2 * (16 // N1 - 1)
