@@ -79,30 +79,53 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, cons
     }
 }
 
+constexpr u32 KEY_GROUP = 4;   // key switches that share one key are served by one thread
+
 struct ItemPack {
     SwitchItem it[ROT_BATCH];
+    uint8_t grp_first[ROT_BATCH], grp_count[ROT_BATCH];   // runs of items with the same key
 };
 
-// u[r][comp][t][k] = sum_j digits_r[j][t][sigma_g(k)] * key_r[j][comp][limb(t)][k]
+// u[r][comp][t][k] = sum_j digits_r[j][t][sigma_g(k)] * key[j][comp][limb(t)][k] for the items r of one
+// group (same key, same Galois element): each key residue is loaded once and used for all of them.
+// grid: x = coefficients, y = limb t, z = group.
 __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack, u64 *__restrict__ u,
                                                                    const ModConst *__restrict__ mods, u32 level,
                                                                    u32 K, u32 L, u32 beta, u32 logN) {
     const u32 N = 1u << logN;
     const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
-    const u32 t = blockIdx.y, r = blockIdx.z;
+    const u32 t = blockIdx.y;
+    const u32 first = pack.grp_first[blockIdx.z], cnt = pack.grp_count[blockIdx.z];
     const u32 Wl = level + K, Wt = L + K;
     const u32 gl = t < level ? t : L + (t - level);
-    const SwitchItem &it = pack.it[r];
-    const u32 kp = galois_index(k, it.galois_elt, logN);
-    u128 a0 = {0, 0}, a1 = {0, 0};
+    const u64 *key = pack.it[first].key;
+    const u32 kp = galois_index(k, pack.it[first].galois_elt, logN);
+    u128 a0[KEY_GROUP], a1[KEY_GROUP];
+#pragma unroll
+    for (u32 r = 0; r < KEY_GROUP; ++r) {
+        a0[r] = {0, 0};
+        a1[r] = {0, 0};
+    }
     for (u32 j = 0; j < beta; ++j) {
-        const u64 d = it.digits[((size_t)j * Wl + t) * N + kp];
-        mac(a0, d, it.key[(((size_t)j * 2 + 0) * Wt + gl) * N + k]);
-        mac(a1, d, it.key[(((size_t)j * 2 + 1) * Wt + gl) * N + k]);
+        const u64 k0 = key[(((size_t)j * 2 + 0) * Wt + gl) * N + k];
+        const u64 k1 = key[(((size_t)j * 2 + 1) * Wt + gl) * N + k];
+#pragma unroll
+        for (u32 r = 0; r < KEY_GROUP; ++r) {
+            if (r < cnt) {
+                const u64 d = pack.it[first + r].digits[((size_t)j * Wl + t) * N + kp];
+                mac(a0[r], d, k0);
+                mac(a1[r], d, k1);
+            }
+        }
     }
     const ModConst m = mods[gl];
-    u[(((size_t)r * 2 + 0) * Wl + t) * N + k] = redc_wide(a0, m);
-    u[(((size_t)r * 2 + 1) * Wl + t) * N + k] = redc_wide(a1, m);
+#pragma unroll
+    for (u32 r = 0; r < KEY_GROUP; ++r) {
+        if (r < cnt) {
+            u[(((size_t)(first + r) * 2 + 0) * Wl + t) * N + k] = redc_wide(a0[r], m);
+            u[(((size_t)(first + r) * 2 + 1) * Wl + t) * N + k] = redc_wide(a1[r], m);
+        }
+    }
 }
 
 // Special-prime rows of u are in the coefficient domain here.
@@ -213,9 +236,21 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
     const u32 beta = (level + p->alpha - 1) / p->alpha;
     ItemPack pack;
     for (u32 r = 0; r < ROT_BATCH; ++r) pack.it[r] = items[r < n ? r : 0];
+    u32 n_groups = 0;
+    for (u32 r = 0; r < n;) {
+        u32 c = 1;
+        while (r + c < n && c < KEY_GROUP && items[r + c].key == items[r].key &&
+               items[r + c].galois_elt == items[r].galois_elt)
+            ++c;
+        pack.grp_first[n_groups] = (uint8_t)r;
+        pack.grp_count[n_groups] = (uint8_t)c;
+        ++n_groups;
+        r += c;
+    }
+    for (u32 g = n_groups; g < ROT_BATCH; ++g) pack.grp_first[g] = pack.grp_count[g] = 0;
     u64 *u = d_work;
     u64 *w = d_work + (size_t)n * 2 * Wl * N;
-    hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n), dim3(KS_THREADS), 0, stream, pack, u,
+    hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n_groups), dim3(KS_THREADS), 0, stream, pack, u,
                        p->d_mod, level, K, L, beta, p->logN);
     CKKS_LAUNCH_CHECK("inner_product_kernel");
     LimbIds ids;

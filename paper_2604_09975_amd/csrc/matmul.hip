@@ -46,58 +46,74 @@ __global__ __launch_bounds__(EW_THREADS) void scale_rows_kernel(u64 *data, const
 // flush = number of products that fit such a sum for the largest modulus).
 // blockIdx.z indexes `limbs`, the list of limbs this launch covers (fp64 limbs and Montgomery limbs
 // go to separate launches so that each kernel keeps its own register budget).
+// Each thread owns VEC adjacent coefficients (16-byte loads for VEC = 2) and TB (b,p) accumulators.
+template <u32 TB, u32 VEC>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restrict__ bank,
                                                               const u64 *__restrict__ w, u64 *__restrict__ acc,
                                                               const ModFp *__restrict__ modf, LimbIds limbs,
                                                               u32 level, u32 N, u32 GQ, u32 BP) {
-    const u32 bp0 = blockIdx.x * MM_TB;
-    const u32 k = blockIdx.y * MM_THREADS + threadIdx.x;
+    typedef u64 vec_t __attribute__((ext_vector_type(VEC)));
+    const u32 bp0 = blockIdx.x * TB;
+    const u32 k = (blockIdx.y * MM_THREADS + threadIdx.x) * VEC;
     const u32 i = limbs.id[blockIdx.z];
     const size_t limb_off = (size_t)i * N + k;
     const size_t w_stride = (size_t)level * N;         // between consecutive gq of one (b,p)
     const ModFp mf = modf[i];
-    {
-        const double q = mf.q, u = mf.u;
-        const double *wf = reinterpret_cast<const double *>(w);
-        double a0[MM_TB], a1[MM_TB];
+    const double q = mf.q, u = mf.u;
+    double a0[TB][VEC], a1[TB][VEC];
 #pragma unroll
-        for (u32 t = 0; t < MM_TB; ++t) a0[t] = a1[t] = 0.0;
-        for (u32 gq = 0; gq < GQ; ++gq) {
-            const u64 r0 = bank[((size_t)gq * 2 + 0) * w_stride + limb_off];
-            const u64 r1 = bank[((size_t)gq * 2 + 1) * w_stride + limb_off];
-            const double x0 = __longlong_as_double((long long)(r0 | 0x4330000000000000ull)) - 4503599627370496.0;
-            const double x1 = __longlong_as_double((long long)(r1 | 0x4330000000000000ull)) - 4503599627370496.0;
+    for (u32 t = 0; t < TB; ++t)
 #pragma unroll
-            for (u32 t = 0; t < MM_TB; ++t) {
-                if (bp0 + t < BP) {
-                    const double wv = wf[((size_t)(bp0 + t) * GQ + gq) * w_stride + limb_off];
+        for (u32 e = 0; e < VEC; ++e) a0[t][e] = a1[t][e] = 0.0;
+    for (u32 gq = 0; gq < GQ; ++gq) {
+        const vec_t r0 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 0) * w_stride + limb_off);
+        const vec_t r1 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 1) * w_stride + limb_off);
+        double x0[VEC], x1[VEC];
+#pragma unroll
+        for (u32 e = 0; e < VEC; ++e) {
+            x0[e] = __longlong_as_double((long long)(r0[e] | 0x4330000000000000ull)) - 4503599627370496.0;
+            x1[e] = __longlong_as_double((long long)(r1[e] | 0x4330000000000000ull)) - 4503599627370496.0;
+        }
+#pragma unroll
+        for (u32 t = 0; t < TB; ++t) {
+            if (bp0 + t < BP) {
+                const vec_t wr = *reinterpret_cast<const vec_t *>(w + ((size_t)(bp0 + t) * GQ + gq) * w_stride + limb_off);
+#pragma unroll
+                for (u32 e = 0; e < VEC; ++e) {
+                    const double wv = __longlong_as_double((long long)wr[e]);
                     // x*w = h + l exactly; subtract the nearest multiple of q: |r| < 0.9 q
-                    const double h0 = x0 * wv, h1 = x1 * wv;
-                    const double l0 = fma(x0, wv, -h0), l1 = fma(x1, wv, -h1);
+                    const double h0 = x0[e] * wv, h1 = x1[e] * wv;
+                    const double l0 = fma(x0[e], wv, -h0), l1 = fma(x1[e], wv, -h1);
                     const double c0 = rint(h0 * u), c1 = rint(h1 * u);
-                    a0[t] += fma(-c0, q, h0) + l0;
-                    a1[t] += fma(-c1, q, h1) + l1;
-                }
-            }
-            if ((gq & 7) == 7) {   // keep the signed sums far below 2^53
-#pragma unroll
-                for (u32 t = 0; t < MM_TB; ++t) {
-                    a0[t] = fma(-rint(a0[t] * u), q, a0[t]);
-                    a1[t] = fma(-rint(a1[t] * u), q, a1[t]);
+                    a0[t][e] += fma(-c0, q, h0) + l0;
+                    a1[t][e] += fma(-c1, q, h1) + l1;
                 }
             }
         }
+        if ((gq & 7) == 7) {   // keep the signed sums far below 2^53
 #pragma unroll
-        for (u32 t = 0; t < MM_TB; ++t) {
-            if (bp0 + t < BP) {
-                double v0 = fma(-rint(a0[t] * u), q, a0[t]), v1 = fma(-rint(a1[t] * u), q, a1[t]);
+            for (u32 t = 0; t < TB; ++t)
+#pragma unroll
+                for (u32 e = 0; e < VEC; ++e) {
+                    a0[t][e] = fma(-rint(a0[t][e] * u), q, a0[t][e]);
+                    a1[t][e] = fma(-rint(a1[t][e] * u), q, a1[t][e]);
+                }
+        }
+    }
+#pragma unroll
+    for (u32 t = 0; t < TB; ++t) {
+        if (bp0 + t < BP) {
+            vec_t o0, o1;
+#pragma unroll
+            for (u32 e = 0; e < VEC; ++e) {
+                double v0 = fma(-rint(a0[t][e] * u), q, a0[t][e]), v1 = fma(-rint(a1[t][e] * u), q, a1[t][e]);
                 if (v0 < 0) v0 += q;
                 if (v1 < 0) v1 += q;
-                acc[((size_t)(bp0 + t) * 2 + 0) * w_stride + limb_off] =
-                    (u64)__double_as_longlong(v0 + 4503599627370496.0) & 0x000fffffffffffffull;
-                acc[((size_t)(bp0 + t) * 2 + 1) * w_stride + limb_off] =
-                    (u64)__double_as_longlong(v1 + 4503599627370496.0) & 0x000fffffffffffffull;
+                o0[e] = (u64)__double_as_longlong(v0 + 4503599627370496.0) & 0x000fffffffffffffull;
+                o1[e] = (u64)__double_as_longlong(v1 + 4503599627370496.0) & 0x000fffffffffffffull;
             }
+            *reinterpret_cast<vec_t *>(acc + ((size_t)(bp0 + t) * 2 + 0) * w_stride + limb_off) = o0;
+            *reinterpret_cast<vec_t *>(acc + ((size_t)(bp0 + t) * 2 + 1) * w_stride + limb_off) = o1;
         }
     }
 }
@@ -354,18 +370,51 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     const size_t ctw = (size_t)2 * level * N;
     const u32 BP = B * N2, GQ = G * N1;
     // persistent buffers of this call live behind the key-switch scratch
-    const u32 batch = std::min<u32>(ROT_BATCH, std::max(N1, B));
+    const u32 in_chunk = std::min<u32>(ROT_BATCH, G);            // inputs decomposed together
+    const u32 batch = std::min<u32>(ROT_BATCH, std::max(in_chunk, B));
     const size_t dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
-    const size_t ks_w = batch * (dig_w + tmp_w) + switch_scratch_words(P, level, batch);
+    const size_t ks_w = batch * (dig_w + tmp_w) + switch_scratch_words(P, level, ROT_BATCH);
     const size_t bank_w = (size_t)GQ * ctw, acc_w = (size_t)BP * ctw;
     int rc = P->ensure_scratch((ks_w + bank_w + acc_w) * sizeof(u64), stream);
     if (rc) return rc;
+    u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + batch * tmp_w;
     u64 *d_bank = (u64 *)P->d_scratch + ks_w, *d_acc = d_bank + bank_w;
 
-    // 1. baby-step bank (ckks_rotate_hoisted uses the front of the same scratch; it cannot grow it now)
-    for (u32 g = 0; g < G; ++g) {
-        rc = ckks_rotate_hoisted(P, d_ct_x + (size_t)g * ctw, level, baby_steps.data(), N1, bk.data(),
-                                 d_bank + (size_t)g * N1 * ctw, stream);
+    // 1. baby-step bank: the inputs are decomposed once (hoisting); the switches are issued step by step
+    //    with the G inputs of one step next to each other, so that they share the reads of that step's key
+    std::vector<u64> baby_g(N1, 1);
+    for (u32 q = 1; q < N1; ++q) ckks_galois_elt(P, baby_steps[q], &baby_g[q]);
+    for (u32 g0 = 0; g0 < G; g0 += in_chunk) {
+        const u32 ng = std::min(in_chunk, G - g0);
+        const u64 *c1s[ROT_BATCH];
+        for (u32 r = 0; r < ng; ++r) c1s[r] = d_ct_x + (size_t)(g0 + r) * ctw + (size_t)level * N;
+        rc = decompose(P, c1s, ng, level, d_digits, d_tmp, stream);
+        if (rc) return rc;
+        SwitchItem items[ROT_BATCH];
+        u32 n_it = 0;
+        for (u32 q = 0; q < N1; ++q) {
+            if (n_it + ng > ROT_BATCH) {   // keep the inputs of one step in one batch
+                rc = switch_batch(P, level, items, n_it, d_work, stream);
+                if (rc) return rc;
+                n_it = 0;
+            }
+            for (u32 r = 0; r < ng; ++r) {
+                const u64 *src = d_ct_x + (size_t)(g0 + r) * ctw;
+                u64 *dst = d_bank + ((size_t)(g0 + r) * N1 + q) * ctw;
+                if (baby_g[q] == 1) {
+                    CKKS_HIP(hipMemcpyAsync(dst, src, ctw * sizeof(u64), hipMemcpyDeviceToDevice, stream));
+                    continue;
+                }
+                SwitchItem &it = items[n_it++];
+                it.digits = d_digits + (size_t)r * dig_w;
+                it.c0 = src;
+                it.key = bk[q]->d_key;
+                it.dst = dst;
+                it.galois_elt = baby_g[q];
+                it.accumulate = 0;
+            }
+        }
+        rc = switch_batch(P, level, items, n_it, d_work, stream);
         if (rc) return rc;
     }
     // 2. diagonal multiply-accumulate
@@ -390,9 +439,9 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                 int_limbs.id[n_int++] = (uint8_t)i;
         }
         const dim3 tiles((BP + MM_TB - 1) / MM_TB, N / MM_THREADS);
-        if (n_fp)
-            hipLaunchKernelGGL(diag_mac_kernel, dim3(tiles.x, tiles.y, n_fp), dim3(MM_THREADS), 0, stream, d_bank,
-                               w->d_w, d_acc, P->d_modf, fp_limbs, level, N, GQ, BP);
+        if (n_fp)   // 8 accumulators x 2 coefficients per thread measured best (16-byte loads, 92 VGPRs)
+            hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2>), dim3(tiles.x, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS),
+                               0, stream, d_bank, w->d_w, d_acc, P->d_modf, fp_limbs, level, N, GQ, BP);
         if (n_int)
             hipLaunchKernelGGL(diag_mac_int_kernel, dim3(tiles.x, tiles.y, n_int), dim3(MM_THREADS), 0, stream, d_bank,
                                w->d_w, d_acc, P->d_mod, int_limbs, level, N, GQ, BP, flush);
@@ -406,7 +455,6 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     for (u32 b = 0; b < B; ++b)
         CKKS_HIP(hipMemcpyAsync(d_ct_y + (size_t)b * ctw, d_acc + (size_t)b * N2 * ctw, ctw * sizeof(u64),
                                 hipMemcpyDeviceToDevice, stream));
-    u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + batch * tmp_w;
     for (u32 p = 1; p < N2; ++p) {
         for (u32 b0 = 0; b0 < B; b0 += batch) {
             const u32 nb = std::min(batch, B - b0);
