@@ -1,0 +1,67 @@
+"""GPU parity at full size: the BERT-base QKV projection under CKKS (N = 2^16, 24 + 8 primes, scale 2^40,
+128x768 times 768x2304 + bias, 6912 diagonals), run exactly as bench.py runs it.  The oracle recomputes ONE
+sampled output block (all its limbs and coefficients, before and after rescale) bit for bit; every block is
+decrypted and compared with the fp64 product."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import encoding as E
+from tests import helpers
+from tests.gpu_util import load_keys, make_pair, to_dev, to_host
+from paper_2604_09975_amd import workload as W
+
+pytestmark = pytest.mark.gpu
+
+
+def test_bert_qkv_sampled_block_bit_exact():
+    from paper_2604_09975_amd import binding as B
+    t0 = time.time()
+    spec = W.BERT_QKV
+    O, P = make_pair(spec.ring)
+    N, n, m, C, N1 = O.N, O.n, spec.m, spec.C, spec.N1
+    G, B_out, N2 = W.plan(spec)
+    level = O.L
+    scale = 2.0 ** spec.ring.log_scale
+    X, Wm, bias = W.matmul_inputs(spec)
+    cl = helpers.Client(O, spec.seed)
+    mx = E.encode(E.pack_columns(X, n, C) + 0j, scale, N)
+    ct_x = np.stack([cl.encrypt_coeffs(mx[g], level) for g in range(G)])
+    baby_np, baby_h = load_keys(P, O, cl, [q * m for q in range(1, N1)])
+    giant_np, giant_h = load_keys(P, O, cl, [p * N1 * m for p in range(1, N2)])
+    print(f"[full] keys ready {time.time() - t0:.0f}s", flush=True)
+    bias_c = np.stack([E.encode(E.bias_slots(bias, m, n, C, b) + 0j, scale, N) for b in range(B_out)])
+    block = int(W.rng(spec.seed + 7).integers(B_out))          # the sampled block
+    w = B.ckks_weights_create(P, level, m, C, G, B_out, N1)
+    diag_block = None
+    for b in range(B_out):
+        d = E.encode_diagonals(Wm, m, N, C, N1, scale, blocks={b})[b]          # [N2][G][N1][N]
+        B.ckks_weights_set_diagonals(w, b * N2 * G * N1, to_dev(d.reshape(-1, N)))
+        if b == block:
+            diag_block = d
+    B.ckks_weights_set_bias(w, to_dev(bias_c), int(scale))
+    print(f"[full] weights ready {time.time() - t0:.0f}s", flush=True)
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h)
+    y_res = B.ckks_rescale(P, y_dev, level, B_out)
+    torch.cuda.synchronize()
+    got, got_res = to_host(y_dev), to_host(y_res)
+    assert cnt.key_switches == G * (N1 - 1) + B_out * (N2 - 1) and cnt.ptmuls == G * N1 * B_out * N2
+
+    # oracle on the sampled block: it needs that block's diagonals only
+    diag = np.zeros((B_out, N2, G, N1, N), dtype=np.int64)
+    diag[block] = diag_block
+    want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(scale), ct_x, baby_np, giant_np,
+                         b_first=block, b_count=1)
+    print(f"[full] oracle block {block} done {time.time() - t0:.0f}s", flush=True)
+    assert (got[block] == want[block]).all()
+    assert (got_res[block] == O.rescale(want[block:block + 1], level)[0]).all()
+
+    out_scale = scale * scale / O.q[level - 1]
+    slots = np.stack([cl.decrypt_slots(got_res[b], level - 1, out_scale, nlimbs=2) for b in range(B_out)])
+    Y = E.unpack_columns(slots.real, m, C, spec.d_out)
+    err = np.abs(Y - (X @ Wm + bias)).max()
+    print(f"[full] max abs err {err:.2e}, total {time.time() - t0:.0f}s", flush=True)
+    assert err <= 1e-3
+    assert np.abs(slots.imag).max() <= 1e-3
