@@ -65,6 +65,8 @@ struct ckks_params {
     ckks::u64 *d_tw_inv = nullptr;     // [W][N]: psi^-bitrev(idx), Montgomery form
     ckks::u64 *d_ninv = nullptr;       // [W][2]: N^-1 and N^-1 * psi^-(N/2), Montgomery form
     ckks::ModFp *d_modf = nullptr;     // [W]
+    ckks::u64 *d_ninv_dn = nullptr;    // like d_ninv, special limbs scaled by (P/p_k)^-1
+    ckks::ModFp *d_modf_dn = nullptr;  // like d_modf, special limbs scaled by (P/p_k)^-1
     double *d_twf_fwd = nullptr;       // [W][N]: psi^bitrev(idx) as a double (limbs below 2^50 only)
     double *d_twf_inv = nullptr;       // [W][N]
     // ModDown tables (independent of the level)
@@ -103,8 +105,11 @@ struct ckks_weights {
 namespace ckks {
 
 // ntt.hip
+// pass_mask: bit 0 = the pass that runs first, bit 1 = the pass that runs second (3 = whole transform);
+// scaled_dn: inverse only, folds (P/p_k)^-1 into the output of the special limbs.
 int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, bool inverse,
-               hipStream_t stream);
+               hipStream_t stream, u32 pass_mask = 3, bool scaled_dn = false);
+inline bool fast_ring(const ckks_params *p) { return p->logN == 16 || p->logN == 12; }
 
 // keyswitch.hip
 struct SwitchItem {

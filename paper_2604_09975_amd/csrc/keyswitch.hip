@@ -16,6 +16,7 @@
 
 #include "ckks_internal.h"
 #include "common_kernels.h"
+#include "ntt_device.h"
 
 namespace ckks {
 
@@ -128,28 +129,27 @@ __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack
     }
 }
 
-// Special-prime rows of u are in the coefficient domain here.
-// y_k = u_{p_k} * (P/p_k)^-1 mod p_k;  w_i = sum_k y_k * (P/p_k mod q_i) mod q_i.
-__global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__restrict__ u, u64 *__restrict__ w,
+// y holds, per (item, component), the K special-limb rows y_k = INTT(u_{p_k}) * (P/p_k)^-1 in the coefficient
+// domain (the scaling comes out of the inverse transform); row (pc, k) starts at y + (pc*ystride + yoff + k)*N.
+// w_i = sum_k y_k * (P/p_k mod q_i) mod q_i for a chunk of target limbs i.
+__global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__restrict__ y, u64 *__restrict__ w,
                                                                   const ModConst *__restrict__ mods,
-                                                                  const u64 *__restrict__ dn_inv,
                                                                   const u64 *__restrict__ dn_mat, u32 level, u32 K,
-                                                                  u32 L, u32 N) {
+                                                                  u32 L, u32 N, u32 ystride, u32 yoff) {
     const u32 n = blockIdx.x * KS_THREADS + threadIdx.x;
     const u32 pc = blockIdx.y;   // (item, component)
-    const u32 Wl = level + K;
-    u64 y[MAX_DIGIT];
+    u64 yk[MAX_DIGIT];
 #pragma unroll
     for (u32 k = 0; k < MAX_DIGIT; ++k) {
-        y[k] = 0;
-        if (k < K) y[k] = mont_mul(u[((size_t)pc * Wl + level + k) * N + n], dn_inv[k], mods[L + k]);
+        yk[k] = 0;
+        if (k < K) yk[k] = y[((size_t)pc * ystride + yoff + k) * N + n];
     }
     const u32 i0 = blockIdx.z * DN_CHUNK, i1 = min(i0 + DN_CHUNK, level);
     for (u32 i = i0; i < i1; ++i) {
         u128 acc = {0, 0};
 #pragma unroll
         for (u32 k = 0; k < MAX_DIGIT; ++k)
-            if (k < K) mac(acc, y[k], dn_mat[(size_t)k * L + i]);
+            if (k < K) mac(acc, yk[k], dn_mat[(size_t)k * L + i]);
         w[((size_t)pc * level + i) * N + n] = redc(acc, mods[i]);
     }
 }
@@ -173,6 +173,82 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(ItemPack pack
     u64 *dst = it.dst + ((size_t)comp * level + i) * N + k;
     if (it.accumulate) v = add_mod(v, *dst, m.q);
     *dst = v;
+}
+
+// ---- fused kernels for N = 2^12 / 2^16 -------------------------------------------------------------
+// Key inner product on the special limbs feeding straight into the first pass of their inverse transform:
+// row (comp, k, r) of y = INTT-pass-B( sum_j sigma_g(d_j)[p_k] * key_j[comp][p_k] ).
+// grid: x = tile of 4096, y = (comp*K + k)*n + r  (items that share a key sit next to each other).
+__global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64 *__restrict__ y,
+                                                              const ModConst *__restrict__ mods,
+                                                              const ModFp *__restrict__ modf,
+                                                              const u64 *__restrict__ tw_inv,
+                                                              const double *__restrict__ twf_inv,
+                                                              const u64 *__restrict__ ninv, u32 n, u32 level, u32 K,
+                                                              u32 L, u32 beta, u32 logN) {
+    __shared__ u64 lds[FAST_LDS_WORDS];
+    const u32 N = 1u << logN;
+    const u32 r = blockIdx.y % n, ck = blockIdx.y / n, k = ck % K, comp = ck / K;
+    const u32 gl = L + k, t = level + k, Wl = level + K, Wt = L + K;
+    const SwitchItem &it = pack.it[r];
+    const ModConst m = mods[gl];
+    const u64 *dig = it.digits + (size_t)t * N;
+    const u64 *key = it.key + ((size_t)comp * Wt + gl) * N;
+    const u64 g = it.galois_elt;
+    auto load = [&](u32 idx) -> u64 {
+        const u32 kp = galois_index(idx, g, logN);
+        u128 acc = {0, 0};
+        for (u32 j = 0; j < beta; ++j) mac(acc, dig[(size_t)j * Wl * N + kp], key[(size_t)j * 2 * Wt * N + idx]);
+        return redc_wide(acc, m);
+    };
+    u64 *out = y + (((size_t)r * 2 + comp) * K + k) * N;
+    auto store = [&](u32 idx, u64 v) { out[idx] = v; };
+    const ModFp mf = modf[gl];
+    if (mf.ok)
+        pass_b_body<true>(make_field_fp(mf, twf_inv, gl, logN), logN, lds, load, store);
+    else
+        pass_b_body<true>(make_field_int(mods, tw_inv, ninv, gl, logN), logN, lds, load, store);
+}
+
+// Last pass of the forward transform of w fused with the rest of the key switch on limb q_i:
+//   dst[comp][i] (+)= ( sum_j sigma_g(d_j)[q_i] * key_j[comp][q_i] - NTT(w)[i] ) * P^-1  (+ sigma_g(c0)[i] if comp = 0)
+// grid: x = tile of 4096, y = (comp*level + i)*n + r.
+__global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack, const u64 *__restrict__ w,
+                                                                  const ModConst *__restrict__ mods,
+                                                                  const ModFp *__restrict__ modf,
+                                                                  const u64 *__restrict__ tw_fwd,
+                                                                  const double *__restrict__ twf_fwd,
+                                                                  const u64 *__restrict__ ninv,
+                                                                  const u64 *__restrict__ pinv, u32 n, u32 level,
+                                                                  u32 K, u32 L, u32 beta, u32 logN) {
+    __shared__ u64 lds[FAST_LDS_WORDS];
+    const u32 N = 1u << logN;
+    const u32 r = blockIdx.y % n, ci = blockIdx.y / n, i = ci % level, comp = ci / level;
+    const u32 Wl = level + K, Wt = L + K;
+    const SwitchItem &it = pack.it[r];
+    const ModConst m = mods[i];
+    const u64 *wrow = w + (((size_t)r * 2 + comp) * level + i) * N;
+    const u64 *dig = it.digits + (size_t)i * N;
+    const u64 *key = it.key + ((size_t)comp * Wt + i) * N;
+    const u64 *c0 = it.c0 + (size_t)i * N;
+    u64 *dst = it.dst + ((size_t)comp * level + i) * N;
+    const u64 g = it.galois_elt, pi = pinv[i];
+    const u32 accumulate = it.accumulate;
+    auto load = [&](u32 idx) -> u64 { return wrow[idx]; };
+    auto store = [&](u32 idx, u64 what) {
+        const u32 kp = galois_index(idx, g, logN);
+        u128 acc = {0, 0};
+        for (u32 j = 0; j < beta; ++j) mac(acc, dig[(size_t)j * Wl * N + kp], key[(size_t)j * 2 * Wt * N + idx]);
+        u64 v = mont_mul(sub_mod(redc_wide(acc, m), what, m.q), pi, m);
+        if (comp == 0) v = add_mod(v, c0[kp], m.q);
+        if (accumulate) v = add_mod(v, dst[idx], m.q);
+        dst[idx] = v;
+    };
+    const ModFp mf = modf[i];
+    if (mf.ok)
+        pass_b_body<false>(make_field_fp(mf, twf_fwd, i, logN), logN, lds, load, store);
+    else
+        pass_b_body<false>(make_field_int(mods, tw_fwd, ninv, i, logN), logN, lds, load, store);
 }
 
 size_t digits_words(const ckks_params *p, u32 level) {
@@ -248,17 +324,41 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
         r += c;
     }
     for (u32 g = n_groups; g < ROT_BATCH; ++g) pack.grp_first[g] = pack.grp_count[g] = 0;
+    LimbIds ids;
+    if (fast_ring(p)) {
+        // inner product fused into the transforms on both sides of the base conversion
+        u64 *y = d_work;                                   // [n][2][K][N]
+        u64 *w = d_work + (size_t)n * 2 * K * N;           // [n][2][level][N]
+        const u32 tiles = N >> 12;
+        hipLaunchKernelGGL(ip_intt_kernel, dim3(tiles, n * 2 * K), dim3(NTT_THREADS), 0, stream, pack, y, p->d_mod,
+                           p->d_modf, p->d_tw_inv, p->d_twf_inv, p->d_ninv, n, level, K, L, beta, p->logN);
+        CKKS_LAUNCH_CHECK("ip_intt_kernel");
+        p->limb_ntts += (u64)n * 2 * K;
+        for (u32 k = 0; k < K; ++k) ids.id[k] = (uint8_t)(L + k);
+        int rc = launch_ntt(p, y, ids, K, n * 2 * K, true, stream, 2, true);
+        if (rc) return rc;
+        hipLaunchKernelGGL(moddown_conv_kernel, dim3(N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK),
+                           dim3(KS_THREADS), 0, stream, y, w, p->d_mod, p->d_dn_mat, level, K, L, N, K, 0u);
+        CKKS_LAUNCH_CHECK("moddown_conv_kernel");
+        for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
+        rc = launch_ntt(p, w, ids, level, n * 2 * level, false, stream, 1, false);
+        if (rc) return rc;
+        hipLaunchKernelGGL(passb_final_kernel, dim3(tiles, n * 2 * level), dim3(NTT_THREADS), 0, stream, pack, w,
+                           p->d_mod, p->d_modf, p->d_tw_fwd, p->d_twf_fwd, p->d_ninv, p->d_pinv, n, level, K, L, beta,
+                           p->logN);
+        CKKS_LAUNCH_CHECK("passb_final_kernel");
+        return CKKS_OK;
+    }
     u64 *u = d_work;
     u64 *w = d_work + (size_t)n * 2 * Wl * N;
     hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n_groups), dim3(KS_THREADS), 0, stream, pack, u,
                        p->d_mod, level, K, L, beta, p->logN);
     CKKS_LAUNCH_CHECK("inner_product_kernel");
-    LimbIds ids;
     for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
-    int rc = launch_ntt(p, u, ids, Wl, n * 2 * Wl, true, stream);
+    int rc = launch_ntt(p, u, ids, Wl, n * 2 * Wl, true, stream, 3, true);
     if (rc) return rc;
     hipLaunchKernelGGL(moddown_conv_kernel, dim3(N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK),
-                       dim3(KS_THREADS), 0, stream, u, w, p->d_mod, p->d_dn_inv, p->d_dn_mat, level, K, L, N);
+                       dim3(KS_THREADS), 0, stream, u, w, p->d_mod, p->d_dn_mat, level, K, L, N, Wl, level);
     CKKS_LAUNCH_CHECK("moddown_conv_kernel");
     for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
     rc = launch_ntt(p, w, ids, level, n * 2 * level, false, stream);

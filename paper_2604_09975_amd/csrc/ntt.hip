@@ -26,10 +26,10 @@
 #include <algorithm>
 
 #include "ckks_internal.h"
+#include "ntt_device.h"
 
 namespace ckks {
 
-constexpr u32 NTT_THREADS = 256;
 constexpr u32 NTT_TILE_LOG = 12;
 
 // strided != 0: pass A layout, local element (x, lo) = (e / LT, e % LT) sits at
@@ -92,173 +92,6 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_pass_kernel(u64 *__restrict__
     }
 }
 
-
-// ---------------------------------------------------------------------------
-// radix-16 kernels for N = 2^12 and N = 2^16
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ u32 lds_pad(u32 i) { return i + (i >> 4); }
-constexpr u32 FAST_LDS_WORDS = 4096 + 256;
-
-struct FieldInt {
-    typedef u64 T;
-    ModConst m;
-    const u64 *tw;
-    u64 n0, n1;
-    __device__ __forceinline__ T in(u64 x) const { return x; }
-    __device__ __forceinline__ u64 out(T x) const { return x; }
-    __device__ __forceinline__ u64 bits(T x) const { return x; }
-    __device__ __forceinline__ T from_bits(u64 x) const { return x; }
-    __device__ __forceinline__ T twid(u32 idx) const { return tw[idx]; }
-    __device__ __forceinline__ void norm(T &) const {}
-    __device__ __forceinline__ void fwd(T &x, T &y, T w) const {
-        const T v = mont_mul(y, w, m);
-        y = sub_mod(x, v, m.q);
-        x = add_mod(x, v, m.q);
-    }
-    __device__ __forceinline__ void inv(T &x, T &y, T w) const {
-        const T s = add_mod(x, y, m.q);
-        y = mont_mul(sub_mod(x, y, m.q), w, m);
-        x = s;
-    }
-    __device__ __forceinline__ void inv_last(T &x, T &y) const {
-        const T s = add_mod(x, y, m.q), d = sub_mod(x, y, m.q);
-        x = mont_mul(s, n0, m);
-        y = mont_mul(d, n1, m);
-    }
-};
-
-// Exact integer arithmetic in doubles for q < 2^50.  mul(a, w) returns r = a*w - c*q with
-// c = rint(a*w/q) computed in floating point: |r| <= (1/2 + 3|a|/2^53) q, exact as long as
-// |a| <= 2^52.  Sums stay exact below 2^53.  norm() brings a value back to |x| <= q/2.
-struct FieldFp {
-    typedef double T;
-    double q, u, n0, n1;
-    const double *tw;
-    __device__ __forceinline__ T in(u64 x) const {
-        return __longlong_as_double((long long)(x | 0x4330000000000000ull)) - 4503599627370496.0;
-    }
-    __device__ __forceinline__ void norm(T &x) const {
-        const double c = rint(x * u);
-        x = fma(-c, q, x);
-    }
-    __device__ __forceinline__ u64 out(T x) const {
-        norm(x);
-        if (x < 0) x += q;
-        return (u64)__double_as_longlong(x + 4503599627370496.0) & 0x000fffffffffffffull;
-    }
-    __device__ __forceinline__ u64 bits(T x) const { return (u64)__double_as_longlong(x); }
-    __device__ __forceinline__ T from_bits(u64 x) const { return __longlong_as_double((long long)x); }
-    __device__ __forceinline__ T twid(u32 idx) const { return tw[idx]; }
-    __device__ __forceinline__ T mul(T a, T w) const {
-        const double h = a * w;
-        const double l = fma(a, w, -h);
-        const double c = rint(h * u);
-        const double d = fma(-c, q, h);
-        return d + l;
-    }
-    __device__ __forceinline__ void fwd(T &x, T &y, T w) const {
-        const T v = mul(y, w);
-        y = x - v;
-        x = x + v;
-    }
-    __device__ __forceinline__ void inv(T &x, T &y, T w) const {
-        const T s = x + y;
-        y = mul(x - y, w);
-        x = s;
-    }
-    __device__ __forceinline__ void inv_last(T &x, T &y) const {
-        const T s = x + y, d = x - y;
-        x = mul(s, n0);
-        y = mul(d, n1);
-    }
-};
-
-// Four stages on the 16 values a thread holds.  The group is node `nb` of stage s0; at stage
-// s0 + t it covers nodes (nb << t) + k, k < 2^t, and values j, j + (8 >> t) pair up.
-template <class F>
-__device__ __forceinline__ void radix16_fwd(const F &f, typename F::T (&v)[16], u32 s0, u32 nb) {
-#pragma unroll
-    for (u32 j = 0; j < 16; ++j) f.norm(v[j]);
-#pragma unroll
-    for (u32 t = 0; t < 4; ++t) {
-        const u32 g = 8u >> t;
-#pragma unroll
-        for (u32 k = 0; k < (1u << t); ++k) {
-            const typename F::T w = f.twid((1u << (s0 + t)) + (nb << t) + k);
-#pragma unroll
-            for (u32 i = 0; i < g; ++i) f.fwd(v[k * 2 * g + i], v[k * 2 * g + i + g], w);
-        }
-    }
-}
-
-template <class F>
-__device__ __forceinline__ void radix16_inv(const F &f, typename F::T (&v)[16], u32 s0, u32 nb, bool last) {
-#pragma unroll
-    for (u32 j = 0; j < 16; ++j) f.norm(v[j]);
-#pragma unroll
-    for (int t = 3; t >= 0; --t) {
-        const u32 g = 8u >> t;
-        if (t == 1) {
-#pragma unroll
-            for (u32 j = 0; j < 16; ++j) f.norm(v[j]);
-        }
-        if (t == 0 && last) {
-#pragma unroll
-            for (u32 i = 0; i < 8; ++i) f.inv_last(v[i], v[i + 8]);
-        } else {
-#pragma unroll
-            for (u32 k = 0; k < (1u << t); ++k) {
-                const typename F::T w = f.twid((1u << (s0 + t)) + (nb << t) + k);
-#pragma unroll
-                for (u32 i = 0; i < g; ++i) f.inv(v[k * 2 * g + i], v[k * 2 * g + i + g], w);
-            }
-        }
-    }
-}
-
-// pass B: last 8 stages on 4096 consecutive residues (16 runs of 256)
-template <bool INV, class F>
-__device__ __forceinline__ void pass_b_body(const F &f, u64 *__restrict__ poly, u32 logN, u64 *lds) {
-    const u32 tid = threadIdx.x, blk = tid >> 4, c = tid & 15;
-    const u32 base = blockIdx.x << 12;
-    const u32 run = (base >> 8) + blk;              // which run of 256 in the polynomial
-    const u32 sa = logN - 8, sb = logN - 4;
-    const u32 strided = blk * 256 + c, contig = blk * 256 + c * 16;
-    typename F::T v[16];
-    if (!INV) {
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.in(poly[base + strided + j * 16]);
-        radix16_fwd(f, v, sa, run);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad(strided + j * 16)] = f.bits(v[j]);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(contig + j)]);
-        radix16_fwd(f, v, sb, run * 16 + c);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.out(v[j]);
-        __syncthreads();
-#pragma unroll
-        for (u32 i = 0; i < 16; ++i) poly[base + tid + 256 * i] = lds[lds_pad(tid + 256 * i)];
-    } else {
-#pragma unroll
-        for (u32 i = 0; i < 16; ++i) lds[lds_pad(tid + 256 * i)] = poly[base + tid + 256 * i];
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.in(lds[lds_pad(contig + j)]);
-        radix16_inv(f, v, sb, run * 16 + c, false);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.bits(v[j]);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(strided + j * 16)]);
-        radix16_inv(f, v, sa, run, false);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) poly[base + strided + j * 16] = f.out(v[j]);
-    }
-}
 
 // pass A for N = 2^16: first 8 stages on a tile of 256 rows x 16 consecutive residues
 template <bool INV, class F>
@@ -323,46 +156,40 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__
     if (limb == SKIP_ROW) return;
     u64 *poly = data + ((size_t)row << logN);
     const ModFp mf = modf[limb];
+    auto load = [&](u32 idx) { return poly[idx]; };
+    auto store = [&](u32 idx, u64 v) { poly[idx] = v; };
     if (mf.ok) {
-        FieldFp f;
-        f.q = mf.q;
-        f.u = mf.u;
-        f.n0 = mf.ninv;
-        f.n1 = mf.ninv_w;
-        f.tw = twf + ((size_t)limb << logN);
+        const FieldFp f = make_field_fp(mf, twf, limb, logN);
         if (WHICH == 0) pass_a16_body<INV>(f, poly, lds);
         if (WHICH == 1) pass_a12_body<INV>(f, poly);
-        if (WHICH == 2) pass_b_body<INV>(f, poly, logN, lds);
+        if (WHICH == 2) pass_b_body<INV>(f, logN, lds, load, store);
     } else {
-        FieldInt f;
-        f.m = mods[limb];
-        f.tw = tw + ((size_t)limb << logN);
-        f.n0 = ninv[2 * limb];
-        f.n1 = ninv[2 * limb + 1];
+        const FieldInt f = make_field_int(mods, tw, ninv, limb, logN);
         if (WHICH == 0) pass_a16_body<INV>(f, poly, lds);
         if (WHICH == 1) pass_a12_body<INV>(f, poly);
-        if (WHICH == 2) pass_b_body<INV>(f, poly, logN, lds);
+        if (WHICH == 2) pass_b_body<INV>(f, logN, lds, load, store);
     }
 }
 
 template <bool INV, int WHICH>
 static void launch_fast(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, u32 tiles,
-                        hipStream_t stream) {
+                        hipStream_t stream, bool scaled_dn) {
     hipLaunchKernelGGL((ntt_fast_kernel<INV, WHICH>), dim3(tiles, rows), dim3(NTT_THREADS), 0, stream, d_data, p->d_mod,
-                       p->d_modf, INV ? p->d_tw_inv : p->d_tw_fwd, INV ? p->d_twf_inv : p->d_twf_fwd, p->d_ninv, ids,
-                       n_limbs, p->logN);
+                       scaled_dn ? p->d_modf_dn : p->d_modf, INV ? p->d_tw_inv : p->d_tw_fwd,
+                       INV ? p->d_twf_inv : p->d_twf_fwd, scaled_dn ? p->d_ninv_dn : p->d_ninv, ids, n_limbs, p->logN);
 }
 
 int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, bool inverse,
-               hipStream_t stream) {
+               hipStream_t stream, u32 pass_mask, bool scaled_dn) {
     if (rows == 0) return CKKS_OK;
     const u32 logN = p->logN;
     const u32 tile_log = logN < NTT_TILE_LOG ? logN : NTT_TILE_LOG;
     const u32 a = logN > NTT_TILE_LOG ? logN - 8 : 0;
     const size_t lds_bytes = sizeof(u64) << tile_log;
     dim3 grid(p->N >> tile_log, rows), block(NTT_THREADS);
-    for (u32 r = 0; r < rows; ++r)
-        if (ids.id[r % n_limbs] != SKIP_ROW) ++p->limb_ntts;
+    if (pass_mask & 1)
+        for (u32 r = 0; r < rows; ++r)
+            if (ids.id[r % n_limbs] != SKIP_ROW) ++p->limb_ntts;
     if (rows > 65535) {
         set_error("launch_ntt: %u rows exceed one launch", rows);
         return CKKS_E_INVAL;
@@ -370,21 +197,26 @@ int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limb
     if (logN == 16 || logN == 12) {
         const u32 tb = p->N >> 12;
         if (!inverse) {
-            if (logN == 16)
-                launch_fast<false, 0>(p, d_data, ids, n_limbs, rows, 16, stream);
-            else
-                launch_fast<false, 1>(p, d_data, ids, n_limbs, rows, 1, stream);
-            launch_fast<false, 2>(p, d_data, ids, n_limbs, rows, tb, stream);
+            if (pass_mask & 1) {
+                if (logN == 16)
+                    launch_fast<false, 0>(p, d_data, ids, n_limbs, rows, 16, stream, false);
+                else
+                    launch_fast<false, 1>(p, d_data, ids, n_limbs, rows, 1, stream, false);
+            }
+            if (pass_mask & 2) launch_fast<false, 2>(p, d_data, ids, n_limbs, rows, tb, stream, false);
         } else {
-            launch_fast<true, 2>(p, d_data, ids, n_limbs, rows, tb, stream);
-            if (logN == 16)
-                launch_fast<true, 0>(p, d_data, ids, n_limbs, rows, 16, stream);
-            else
-                launch_fast<true, 1>(p, d_data, ids, n_limbs, rows, 1, stream);
+            if (pass_mask & 1) launch_fast<true, 2>(p, d_data, ids, n_limbs, rows, tb, stream, false);
+            if (pass_mask & 2) {
+                if (logN == 16)
+                    launch_fast<true, 0>(p, d_data, ids, n_limbs, rows, 16, stream, scaled_dn);
+                else
+                    launch_fast<true, 1>(p, d_data, ids, n_limbs, rows, 1, stream, scaled_dn);
+            }
         }
         CKKS_LAUNCH_CHECK("ntt_fast_kernel");
         return CKKS_OK;
     }
+    const u64 *ninv_tab = scaled_dn ? p->d_ninv_dn : p->d_ninv;
     if (!inverse) {
         if (a)
             hipLaunchKernelGGL(ntt_pass_kernel<false>, grid, block, lds_bytes, stream, d_data, p->d_mod, p->d_tw_fwd,
@@ -393,10 +225,10 @@ int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limb
                            p->d_ninv, ids, n_limbs, logN, a, logN, tile_log, 0u);
     } else {
         hipLaunchKernelGGL(ntt_pass_kernel<true>, grid, block, lds_bytes, stream, d_data, p->d_mod, p->d_tw_inv,
-                           p->d_ninv, ids, n_limbs, logN, a, logN, tile_log, 0u);
+                           ninv_tab, ids, n_limbs, logN, a, logN, tile_log, 0u);
         if (a)
             hipLaunchKernelGGL(ntt_pass_kernel<true>, grid, block, lds_bytes, stream, d_data, p->d_mod, p->d_tw_inv,
-                               p->d_ninv, ids, n_limbs, logN, 0u, a, tile_log, 1u);
+                               ninv_tab, ids, n_limbs, logN, 0u, a, tile_log, 1u);
     }
     CKKS_LAUNCH_CHECK("ntt_pass_kernel");
     return CKKS_OK;

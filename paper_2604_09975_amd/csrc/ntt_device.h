@@ -1,0 +1,195 @@
+// Device-side building blocks of the radix-16 NTT (N = 2^12 and 2^16), shared by the transform kernels
+// and by the key-switch kernels that fuse other work into a transform pass.
+#pragma once
+#include "ckks_internal.h"
+
+namespace ckks {
+
+constexpr u32 NTT_THREADS = 256;
+
+__device__ __forceinline__ u32 lds_pad(u32 i) { return i + (i >> 4); }
+constexpr u32 FAST_LDS_WORDS = 4096 + 256;
+
+struct FieldInt {
+    typedef u64 T;
+    ModConst m;
+    const u64 *tw;
+    u64 n0, n1;
+    __device__ __forceinline__ T in(u64 x) const { return x; }
+    __device__ __forceinline__ u64 out(T x) const { return x; }
+    __device__ __forceinline__ u64 bits(T x) const { return x; }
+    __device__ __forceinline__ T from_bits(u64 x) const { return x; }
+    __device__ __forceinline__ T twid(u32 idx) const { return tw[idx]; }
+    __device__ __forceinline__ void norm(T &) const {}
+    __device__ __forceinline__ void fwd(T &x, T &y, T w) const {
+        const T v = mont_mul(y, w, m);
+        y = sub_mod(x, v, m.q);
+        x = add_mod(x, v, m.q);
+    }
+    __device__ __forceinline__ void inv(T &x, T &y, T w) const {
+        const T s = add_mod(x, y, m.q);
+        y = mont_mul(sub_mod(x, y, m.q), w, m);
+        x = s;
+    }
+    __device__ __forceinline__ void inv_last(T &x, T &y) const {
+        const T s = add_mod(x, y, m.q), d = sub_mod(x, y, m.q);
+        x = mont_mul(s, n0, m);
+        y = mont_mul(d, n1, m);
+    }
+};
+
+// Exact integer arithmetic in doubles for q < 2^50.  mul(a, w) returns r = a*w - c*q with
+// c = rint(a*w/q) computed in floating point: |r| <= (1/2 + 3|a|/2^53) q, exact as long as
+// |a| <= 2^52.  Sums stay exact below 2^53.  norm() brings a value back to |x| <= q/2.
+struct FieldFp {
+    typedef double T;
+    double q, u, n0, n1;
+    const double *tw;
+    __device__ __forceinline__ T in(u64 x) const {
+        return __longlong_as_double((long long)(x | 0x4330000000000000ull)) - 4503599627370496.0;
+    }
+    __device__ __forceinline__ void norm(T &x) const {
+        const double c = rint(x * u);
+        x = fma(-c, q, x);
+    }
+    __device__ __forceinline__ u64 out(T x) const {
+        norm(x);
+        if (x < 0) x += q;
+        return (u64)__double_as_longlong(x + 4503599627370496.0) & 0x000fffffffffffffull;
+    }
+    __device__ __forceinline__ u64 bits(T x) const { return (u64)__double_as_longlong(x); }
+    __device__ __forceinline__ T from_bits(u64 x) const { return __longlong_as_double((long long)x); }
+    __device__ __forceinline__ T twid(u32 idx) const { return tw[idx]; }
+    __device__ __forceinline__ T mul(T a, T w) const {
+        const double h = a * w;
+        const double l = fma(a, w, -h);
+        const double c = rint(h * u);
+        const double d = fma(-c, q, h);
+        return d + l;
+    }
+    __device__ __forceinline__ void fwd(T &x, T &y, T w) const {
+        const T v = mul(y, w);
+        y = x - v;
+        x = x + v;
+    }
+    __device__ __forceinline__ void inv(T &x, T &y, T w) const {
+        const T s = x + y;
+        y = mul(x - y, w);
+        x = s;
+    }
+    __device__ __forceinline__ void inv_last(T &x, T &y) const {
+        const T s = x + y, d = x - y;
+        x = mul(s, n0);
+        y = mul(d, n1);
+    }
+};
+
+// Four stages on the 16 values a thread holds.  The group is node `nb` of stage s0; at stage
+// s0 + t it covers nodes (nb << t) + k, k < 2^t, and values j, j + (8 >> t) pair up.
+template <class F>
+__device__ __forceinline__ void radix16_fwd(const F &f, typename F::T (&v)[16], u32 s0, u32 nb) {
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) f.norm(v[j]);
+#pragma unroll
+    for (u32 t = 0; t < 4; ++t) {
+        const u32 g = 8u >> t;
+#pragma unroll
+        for (u32 k = 0; k < (1u << t); ++k) {
+            const typename F::T w = f.twid((1u << (s0 + t)) + (nb << t) + k);
+#pragma unroll
+            for (u32 i = 0; i < g; ++i) f.fwd(v[k * 2 * g + i], v[k * 2 * g + i + g], w);
+        }
+    }
+}
+
+template <class F>
+__device__ __forceinline__ void radix16_inv(const F &f, typename F::T (&v)[16], u32 s0, u32 nb, bool last) {
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) f.norm(v[j]);
+#pragma unroll
+    for (int t = 3; t >= 0; --t) {
+        const u32 g = 8u >> t;
+        if (t == 1) {
+#pragma unroll
+            for (u32 j = 0; j < 16; ++j) f.norm(v[j]);
+        }
+        if (t == 0 && last) {
+#pragma unroll
+            for (u32 i = 0; i < 8; ++i) f.inv_last(v[i], v[i + 8]);
+        } else {
+#pragma unroll
+            for (u32 k = 0; k < (1u << t); ++k) {
+                const typename F::T w = f.twid((1u << (s0 + t)) + (nb << t) + k);
+#pragma unroll
+                for (u32 i = 0; i < g; ++i) f.inv(v[k * 2 * g + i], v[k * 2 * g + i + g], w);
+            }
+        }
+    }
+}
+
+// pass B: last 8 stages on 4096 consecutive residues (16 runs of 256).
+// load(idx) / store(idx, value) see canonical residues at index idx of the polynomial.  Forward: loads in
+// the strided register pattern (128-byte runs), stores coalesced.  Inverse: loads coalesced, stores strided.
+template <bool INV, class F, class Load, class Store>
+__device__ __forceinline__ void pass_b_body(const F &f, u32 logN, u64 *lds, Load load, Store store) {
+    const u32 tid = threadIdx.x, blk = tid >> 4, c = tid & 15;
+    const u32 base = blockIdx.x << 12;
+    const u32 run = (base >> 8) + blk;              // which run of 256 in the polynomial
+    const u32 sa = logN - 8, sb = logN - 4;
+    const u32 strided = blk * 256 + c, contig = blk * 256 + c * 16;
+    typename F::T v[16];
+    if (!INV) {
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) v[j] = f.in(load(base + strided + j * 16));
+        radix16_fwd(f, v, sa, run);
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) lds[lds_pad(strided + j * 16)] = f.bits(v[j]);
+        __syncthreads();
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(contig + j)]);
+        radix16_fwd(f, v, sb, run * 16 + c);
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.out(v[j]);   // own slots: no barrier needed before
+        __syncthreads();
+#pragma unroll
+        for (u32 i = 0; i < 16; ++i) store(base + tid + 256 * i, lds[lds_pad(tid + 256 * i)]);
+    } else {
+#pragma unroll
+        for (u32 i = 0; i < 16; ++i) lds[lds_pad(tid + 256 * i)] = load(base + tid + 256 * i);
+        __syncthreads();
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) v[j] = f.in(lds[lds_pad(contig + j)]);
+        radix16_inv(f, v, sb, run * 16 + c, false);
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.bits(v[j]);   // own slots
+        __syncthreads();
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(strided + j * 16)]);
+        radix16_inv(f, v, sa, run, false);
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) store(base + strided + j * 16, f.out(v[j]));
+    }
+}
+
+// Field objects for limb `limb` from the parameter tables.
+__device__ __forceinline__ FieldFp make_field_fp(const ModFp &mf, const double *twf, u32 limb, u32 logN) {
+    FieldFp f;
+    f.q = mf.q;
+    f.u = mf.u;
+    f.n0 = mf.ninv;
+    f.n1 = mf.ninv_w;
+    f.tw = twf + ((size_t)limb << logN);
+    return f;
+}
+
+__device__ __forceinline__ FieldInt make_field_int(const ModConst *mods, const u64 *tw, const u64 *ninv, u32 limb,
+                                                   u32 logN) {
+    FieldInt f;
+    f.m = mods[limb];
+    f.tw = tw + ((size_t)limb << logN);
+    f.n0 = ninv[2 * limb];
+    f.n1 = ninv[2 * limb + 1];
+    return f;
+}
+
+}  // namespace ckks

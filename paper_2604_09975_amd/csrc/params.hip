@@ -259,6 +259,7 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     std::vector<u64> pw(2 * (size_t)N);
     std::vector<double> fwd_f((size_t)W * N, 0.0), inv_f((size_t)W * N, 0.0);
     std::vector<ModFp> modf(W);
+    std::vector<u64> ninv_plain((size_t)W * 2);
     for (u32 i = 0; i < W; ++i) {
         const ModConst &m = P->hmod[i];
         pw[0] = 1;
@@ -269,6 +270,8 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
             inv[(size_t)i * N + idx] = to_mont(pw[2 * N - e], m);
         }
         u64 ni = hinv(N % m.q, m.q);
+        ninv_plain[2 * i] = ni;
+        ninv_plain[2 * i + 1] = hmul(ni, pw[2 * N - N / 2], m.q);
         ninv[2 * i] = to_mont(ni, m);
         ninv[2 * i + 1] = to_mont(hmul(ni, pw[2 * N - N / 2], m.q), m);
         // primes below 2^50 also get plain-integer twiddles as doubles for the FMA butterflies
@@ -307,7 +310,25 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
         for (u32 l = 0; l < L; ++l)
             if (l != i) qlinv[(size_t)l * L + i] = to_mont(hinv(mod[l] % mod[i], mod[i]), P->hmod[i]);
     }
+    // INTT constants of the special limbs with (P/p_k)^-1 folded in: the ModDown of a key switch then reads
+    // y_k = INTT(u_{p_k}) * (P/p_k)^-1 straight from the transform
+    std::vector<u64> ninv_dn = ninv;
+    std::vector<ModFp> modf_dn = modf;
+    for (u32 k = 0; k < K; ++k) {
+        const ModConst &m = P->hmod[L + k];
+        u64 pk = mod[L + k], prod = 1;
+        for (u32 b = 0; b < K; ++b)
+            if (b != k) prod = hmul(prod, mod[L + b] % pk, pk);
+        u64 f = hinv(prod, pk);
+        u64 n0 = hmul(ninv_plain[2 * (L + k)], f, pk), n1 = hmul(ninv_plain[2 * (L + k) + 1], f, pk);
+        ninv_dn[2 * (L + k)] = to_mont(n0, m);
+        ninv_dn[2 * (L + k) + 1] = to_mont(n1, m);
+        modf_dn[L + k].ninv = (double)n0;
+        modf_dn[L + k].ninv_w = (double)n1;
+    }
     int rc = upload(&P->d_mod, P->hmod);
+    if (!rc) rc = upload(&P->d_ninv_dn, ninv_dn);
+    if (!rc) rc = upload(&P->d_modf_dn, modf_dn);
     if (!rc) rc = upload(&P->d_tw_fwd, fwd);
     if (!rc) rc = upload(&P->d_tw_inv, inv);
     if (!rc) rc = upload(&P->d_ninv, ninv);
@@ -333,6 +354,8 @@ void ckks_params_destroy(ckks_params_t *P) {
     hipFree(P->d_tw_inv);
     hipFree(P->d_ninv);
     hipFree(P->d_modf);
+    hipFree(P->d_ninv_dn);
+    hipFree(P->d_modf_dn);
     hipFree(P->d_twf_fwd);
     hipFree(P->d_twf_inv);
     hipFree(P->d_dn_inv);
