@@ -26,7 +26,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def setup_matmul(B, CL, W, P, cl, spec, n1):
+def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None):
     import torch
     N, n = P.N, P.N // 2
     level = P.L
@@ -35,9 +35,16 @@ def setup_matmul(B, CL, W, P, cl, spec, n1):
     N2 = spec.C // n1
     scale = 2.0 ** spec.ring.log_scale
     t0 = time.time()
-    baby = [cl.galois_key(q * spec.m) for q in range(1, n1)]
-    giant = [cl.galois_key(p * n1 * spec.m) for p in range(1, N2)]
-    log(f"[bench] {len(baby) + len(giant)} Galois keys in {time.time() - t0:.1f}s")
+    key_cache = {} if key_cache is None else key_cache
+
+    def key(step):
+        if step not in key_cache:
+            key_cache[step] = cl.galois_key(step)
+        return key_cache[step]
+
+    baby = [key(q * spec.m) for q in range(1, n1)]
+    giant = [key(p * n1 * spec.m) for p in range(1, N2)]
+    log(f"[bench] {len(baby) + len(giant)} Galois keys ready in {time.time() - t0:.1f}s")
     xs = CL.pack_columns(X, n, spec.C)
     ct_x = torch.stack([cl.encrypt_slots(xs[g], scale, level) for g in range(G)])
     w = B.ckks_weights_create(P, level, spec.m, spec.C, G, B_out, n1)
@@ -59,6 +66,19 @@ def setup_matmul(B, CL, W, P, cl, spec, n1):
     log(f"[bench] {G * n1 * B_out * N2} weight diagonals encoded and expanded in {time.time() - t0:.1f}s")
     ref = X @ Wm + (bias if bias is not None else 0.0)
     return dict(ct_x=ct_x, w=w, baby=baby, giant=giant, ref=ref, G=G, B_out=B_out, N2=N2, scale=scale, level=level)
+
+
+def read_traffic(workload, n1):
+    """HBM bytes per diag_mac_kernel launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by the plain-copy factors stated there); None if it is for another plan."""
+    path = os.path.join(ROOT, "profiles", "bert_qkv_diag_mac_hbm_traffic.txt")
+    try:
+        kv = dict(l.strip().split("=", 1) for l in open(path) if "=" in l and not l.startswith("#"))
+        if kv.get("workload") == workload and int(kv.get("N1", -1)) == n1:
+            return float(kv["traffic_bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
 
 
 def cpu_baseline(W, spec, n1):
@@ -112,6 +132,56 @@ def cpu_baseline(W, spec, n1):
                 key_switches_per_s_hoisted=ks_per_s)
 
 
+def run_gpt2_block(args, B, CL, W, P, cl):
+    """The four linear layers of a GPT-2-small block (QKV, attention output, FFN up, FFN down) at sequence
+    length 128, one after the other; weights of one layer resident at a time; inputs freshly encrypted per
+    layer (the MPC boundary between layers is simulated by fresh synthetic activations)."""
+    import torch
+    keys, layers, total = {}, [], 0.0
+    for spec in W.GPT2_LAYERS:
+        n1 = args.n1 or spec.N1
+        S = setup_matmul(B, CL, W, P, cl, spec, n1, keys)
+        level, B_out = S["level"], S["B_out"]
+        y = torch.empty((B_out, 2, level, P.N), dtype=torch.int64, device="cuda")
+        yr = torch.empty((B_out, 2, level - 1, P.N), dtype=torch.int64, device="cuda")
+
+        def step():
+            _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y)
+            B.ckks_rescale(P, y, level, B_out, yr)
+            return cnt
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            cnt = step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        out_scale = S["scale"] * S["scale"] / P.q[level - 1]
+        slots = np.stack([cl.decrypt_slots(yr[b], level - 1, out_scale) for b in range(B_out)])
+        err = float(np.abs(CL.unpack_columns(slots.real, spec.m, spec.C, spec.d_out) - S["ref"]).max())
+        log(f"[bench] {spec.name}: {ms:.2f} ms, {cnt.key_switches} key switches, max abs err {err:.2e}")
+        if not err <= 1e-3:
+            log("[bench] ERROR: decrypted result is outside the 1e-3 bound")
+            sys.exit(1)
+        layers.append({"layer": spec.name, "d_in": spec.d_in, "d_out": spec.d_out, "G": S["G"], "B_out": B_out,
+                       "N1": n1, "N2": S["N2"], "ms": ms, "key_switches": int(cnt.key_switches),
+                       "ptmuls": int(cnt.ptmuls), "max_abs_err": err})
+        total += ms
+        S["w"].close()
+        del S, y, yr
+        torch.cuda.empty_cache()
+    print(json.dumps({
+        "metric": "GPT-2-small block linear layers total latency ms (seq 128, hidden 768)", "value": total,
+        "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "gpt2_small_block_linear_set", "N": P.N, "q_limbs": P.L, "special_limbs": P.K,
+                   "dnum": P.dnum, "layers": layers}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -120,6 +190,11 @@ def main():
     ap.add_argument("--n1", type=int, default=0, help="baby steps (0 = the configuration's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--workload", default="bert_qkv", choices=["bert_qkv", "gpt2_block"],
+                    help="bert_qkv (default, the headline configuration) or the four GPT-2-small block layers")
+    ap.add_argument("--no-hoisted", action="store_true", help="skip the hoisted-rotation batch")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run only a plain 4 GiB device-to-device copy, 10 times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are part of "
@@ -127,8 +202,17 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2604_09975_amd import binding as B, client as CL, workload as W
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        src = torch.ones(1 << 29, dtype=torch.int64, device="cuda")     # 4 GiB
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "copy", "bytes_read_per_launch": src.numel() * 8,
+                          "bytes_written_per_launch": src.numel() * 8, "launches": 10}))
+        return
+    from paper_2604_09975_amd import binding as B, client as CL, workload as W
     spec = W.BERT_QKV
     n1 = args.n1 or spec.N1
     ring = spec.ring
@@ -136,6 +220,9 @@ def main():
     p = B.ckks_find_primes(60, ring.logN, 8)
     P = B.ckks_params_create(ring.logN, q, p, ring.dnum)
     cl = CL.Client(P, spec.seed)
+    if args.workload == "gpt2_block":
+        run_gpt2_block(args, B, CL, W, P, cl)
+        return
     S = setup_matmul(B, CL, W, P, cl, spec, n1)
     N, level, B_out, G, N2 = P.N, S["level"], S["B_out"], S["G"], S["N2"]
     y = torch.empty((B_out, 2, level, N), dtype=torch.int64, device="cuda")
@@ -175,7 +262,7 @@ def main():
             sys.exit(1)
 
     # hoisted rotation batch (N = 2^16, L = 24): 26 rotations + conjugation from one ciphertext
-    steps = [s for s in W.HOISTED_STEPS if s != (1 << 15)]
+    steps = [] if args.no_hoisted else [s for s in W.HOISTED_STEPS if s != (1 << 15)]
     keys = [cl.galois_key(s) for s in steps]
     ct = cl.encrypt_slots(W.unit_disk_slots(W.rng(W.HOISTED_SEED), P.N // 2), S["scale"], level)
     rot_out = torch.empty((len(steps), 2, level, N), dtype=torch.int64, device="cuda")
@@ -188,7 +275,7 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     rot_ms = e0.elapsed_time(e1) / reps
-    ks_per_s = len(steps) / rot_ms * 1e3
+    ks_per_s = len(steps) / rot_ms * 1e3 if steps else None
 
     # algorithmic bytes of one diagonal multiply-accumulate launch: every weight limb once, the bank once,
     # the accumulators once (8 bytes per residue)
@@ -196,6 +283,7 @@ def main():
     mac_bytes = (G * n1 * B_out * N2 * level + G * n1 * 2 * level + B_out * N2 * 2 * level) * limb_poly
     achieved = mac_bytes / (mac_ms * 1e-3) / 1e9
     ks_bytes = 188.7e6
+    traffic = read_traffic(spec.name, n1)
     out = {
         "metric": "ct-pt matmul latency ms (128x768x2304)",
         "value": ms_per_step,
@@ -216,12 +304,12 @@ def main():
                    "limb_ntts_per_step": int(cnt.limb_ntts)},
         "key_switches_per_s": ks_per_s,
         "hoisted_batch": {"key_switches": len(steps), "ms": rot_ms,
-                          "hbm_roofline_frac": ks_bytes * ks_per_s / (HBM_PEAK_GBS * 1e9)},
+                          "hbm_roofline_frac": ks_bytes * ks_per_s / (HBM_PEAK_GBS * 1e9) if steps else None},
         "matmul_hbm_roofline_frac": (90.0e9 / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
         "max_abs_err": max_err,
         "wall_s_timed_region": wall,
         "roofline": {"bound": "hbm", "kernel": "diag_mac_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": mac_bytes, "ms_per_launch": mac_ms},
     }
     if not args.no_cpu_baseline:

@@ -308,6 +308,14 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
 // n <= ROT_BATCH key switches from ready digits.  d_work: switch_scratch_words(level, n).
 int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream) {
     if (n == 0) return CKKS_OK;
+    static const u32 lim = getenv("CKKS_ROT_BATCH") ? (u32)atoi(getenv("CKKS_ROT_BATCH")) : ROT_BATCH;
+    if (n > lim) {
+        for (u32 off = 0; off < n; off += lim) {
+            int rc = switch_batch(p, level, items + off, std::min(lim, n - off), d_work, stream);
+            if (rc) return rc;
+        }
+        return CKKS_OK;
+    }
     const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
     const u32 beta = (level + p->alpha - 1) / p->alpha;
     ItemPack pack;

@@ -38,8 +38,9 @@ __global__ __launch_bounds__(EW_THREADS) void scale_rows_kernel(u64 *data, const
 }
 
 // acc[bp][comp][i][k] = sum_{gq} bank[gq][comp][i][k] * w[bp][gq][i][k]
-// grid: x = tile of MM_TB (b,p) pairs (fastest, so neighbouring workgroups share their bank lines in L2),
-//       y = run of 256 coefficients, z = limb (slowest: one limb's bank slice stays cache-resident).
+// grid: x = tile of (b,p) pairs (fastest), y = run of coefficients, z = limb (slowest: one limb's bank slice
+//       stays resident in the Infinity Cache while all its tiles run).  An XCD-aware remapping of x/y and a
+//       variant whose four wavefronts share their bank loads were measured and did not help.
 // Weight limbs are stored in the library's internal form: for a prime below 2^50 the residue as a
 // double (products are then reduced with the exact FMA scheme of the NTT butterflies and summed as
 // signed doubles, about 7 issue slots per product), otherwise in Montgomery form (128-bit lazy sums;
