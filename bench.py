@@ -182,6 +182,80 @@ def run_gpt2_block(args, B, CL, W, P, cl):
                    "dnum": P.dnum, "layers": layers}}), flush=True)
 
 
+def run_ntt(args, B, W):
+    """NTT microbenchmark: 64 polynomials x 24 limbs of 50-bit primes x 2^16, forward then inverse."""
+    import torch
+    ring = W.NTT_RING
+    q = B.ckks_find_primes(50, ring.logN, 24)
+    P = B.ckks_params_create(ring.logN, q, [], ring.dnum)
+    x = torch.from_numpy(W.uniform_residues(W.rng(W.NTT_SEED), q, P.N, lead=(W.NTT_BATCH,)).view(np.int64)).cuda()
+    ref = x.clone()
+    ids = list(range(24))
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for _ in range(args.warmup):
+        B.ckks_ntt(P, x, ids, W.NTT_BATCH)
+        B.ckks_intt(P, x, ids, W.NTT_BATCH)
+    torch.cuda.synchronize()
+    fwd = inv = 0.0
+    for _ in range(args.steps):
+        e[0].record()
+        B.ckks_ntt(P, x, ids, W.NTT_BATCH)
+        e[1].record()
+        B.ckks_intt(P, x, ids, W.NTT_BATCH)
+        e[2].record()
+        torch.cuda.synchronize()
+        fwd += e[0].elapsed_time(e[1])
+        inv += e[1].elapsed_time(e[2])
+    assert bool((x == ref).all()), "INTT(NTT(x)) != x"
+    fwd, inv = fwd / args.steps, inv / args.steps
+    nbytes = 2 * 8 * W.NTT_BATCH * 24 * P.N                      # each residue read once and written once
+    ach = nbytes / (fwd * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "NTT throughput GB/s (64 x 24 limbs x 2^16, forward)", "value": ach, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": fwd + inv, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": ring.name, "batch": W.NTT_BATCH, "limbs": 24, "N": P.N},
+        "forward_ms": fwd, "inverse_ms": inv, "inverse_GBps": nbytes / (inv * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "ntt_fast_kernel (both passes)", "achieved": ach, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": nbytes,
+                     "ms_per_launch": fwd}}), flush=True)
+
+
+def run_hoisted(args, B, CL, W, P, cl):
+    """Hoisted rotation batch: 26 rotations + conjugation of one fresh ciphertext (N = 2^16, 24 + 8 limbs)."""
+    import torch
+    level = P.L
+    steps = [s for s in W.HOISTED_STEPS if s != (1 << 15)]
+    keys = [cl.galois_key(s) for s in steps]
+    z = W.unit_disk_slots(W.rng(W.HOISTED_SEED), P.N // 2)
+    ct = cl.encrypt_slots(z, 2.0 ** 40, level)
+    out = torch.empty((len(steps), 2, level, P.N), dtype=torch.int64, device="cuda")
+    for _ in range(max(args.warmup, 1)):
+        B.ckks_rotate_hoisted(P, ct, level, steps, keys, out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        B.ckks_rotate_hoisted(P, ct, level, steps, keys, out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    err = max(float(np.abs(cl.decrypt_slots(out[i], level, 2.0 ** 40) - (np.conj(z) if s == "conj" else np.roll(z, -s))).max())
+              for i, s in list(enumerate(steps))[::9])
+    assert err < 585 * P.N / 2.0 ** 40, err
+    ks = len(steps) / ms * 1e3
+    print(json.dumps({
+        "metric": "key-switches/s at N=2^16 L=24 (hoisted batch)", "value": ks, "unit": "key-switches/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "hoisted_rotation_batch", "N": P.N, "q_limbs": P.L, "special_limbs": P.K,
+                   "dnum": P.dnum, "key_switches": len(steps)},
+        "max_abs_err": err,
+        "roofline": {"bound": "hbm", "kernel": "ckks_rotate_hoisted (all kernels)", "achieved": 188.7e6 * ks / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": 188.7e6 * ks / (HBM_PEAK_GBS * 1e9),
+                     "traffic": None, "bytes_per_launch": 188.7e6 * len(steps), "ms_per_launch": ms}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -190,8 +264,9 @@ def main():
     ap.add_argument("--n1", type=int, default=0, help="baby steps (0 = the configuration's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
-    ap.add_argument("--workload", default="bert_qkv", choices=["bert_qkv", "gpt2_block"],
-                    help="bert_qkv (default, the headline configuration) or the four GPT-2-small block layers")
+    ap.add_argument("--workload", default="bert_qkv", choices=["bert_qkv", "gpt2_block", "hoisted", "ntt"],
+                    help="bert_qkv (default, the headline configuration), the four GPT-2-small block layers, the "
+                         "hoisted rotation batch alone, or the NTT microbenchmark")
     ap.add_argument("--no-hoisted", action="store_true", help="skip the hoisted-rotation batch")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 4 GiB device-to-device copy, 10 times (reference for HBM byte counters)")
@@ -213,6 +288,9 @@ def main():
                           "bytes_written_per_launch": src.numel() * 8, "launches": 10}))
         return
     from paper_2604_09975_amd import binding as B, client as CL, workload as W
+    if args.workload == "ntt":
+        run_ntt(args, B, W)
+        return
     spec = W.BERT_QKV
     n1 = args.n1 or spec.N1
     ring = spec.ring
@@ -222,6 +300,9 @@ def main():
     cl = CL.Client(P, spec.seed)
     if args.workload == "gpt2_block":
         run_gpt2_block(args, B, CL, W, P, cl)
+        return
+    if args.workload == "hoisted":
+        run_hoisted(args, B, CL, W, P, cl)
         return
     S = setup_matmul(B, CL, W, P, cl, spec, n1)
     N, level, B_out, G, N2 = P.N, S["level"], S["B_out"], S["G"], S["N2"]

@@ -308,13 +308,9 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
 // n <= ROT_BATCH key switches from ready digits.  d_work: switch_scratch_words(level, n).
 int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream) {
     if (n == 0) return CKKS_OK;
-    static const u32 lim = getenv("CKKS_ROT_BATCH") ? (u32)atoi(getenv("CKKS_ROT_BATCH")) : ROT_BATCH;
-    if (n > lim) {
-        for (u32 off = 0; off < n; off += lim) {
-            int rc = switch_batch(p, level, items + off, std::min(lim, n - off), d_work, stream);
-            if (rc) return rc;
-        }
-        return CKKS_OK;
+    if (n > ROT_BATCH) {
+        set_error("switch_batch: %u items exceed one batch", n);
+        return CKKS_E_INVAL;
     }
     const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
     const u32 beta = (level + p->alpha - 1) / p->alpha;
@@ -345,6 +341,8 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
         for (u32 k = 0; k < K; ++k) ids.id[k] = (uint8_t)(L + k);
         int rc = launch_ntt(p, y, ids, K, n * 2 * K, true, stream, 2, true);
         if (rc) return rc;
+        // (a variant with this base conversion fused into the transform's first pass was measured: its 8 strided
+        // reads per residue from L2 made it slower than the two kernels)
         hipLaunchKernelGGL(moddown_conv_kernel, dim3(N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK),
                            dim3(KS_THREADS), 0, stream, y, w, p->d_mod, p->d_dn_mat, level, K, L, N, K, 0u);
         CKKS_LAUNCH_CHECK("moddown_conv_kernel");

@@ -93,54 +93,6 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_pass_kernel(u64 *__restrict__
 }
 
 
-// pass A for N = 2^16: first 8 stages on a tile of 256 rows x 16 consecutive residues
-template <bool INV, class F>
-__device__ __forceinline__ void pass_a16_body(const F &f, u64 *__restrict__ poly, u64 *lds) {
-    const u32 tid = threadIdx.x, c = tid >> 4, lo = tid & 15;
-    const u32 col = blockIdx.x * 16 + lo;
-    typename F::T v[16];
-    if (!INV) {
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.in(poly[(size_t)(j * 16 + c) * 256 + col]);
-        radix16_fwd(f, v, 0, 0);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad((j * 16 + c) * 16 + lo)] = f.bits(v[j]);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad((c * 16 + j) * 16 + lo)]);
-        radix16_fwd(f, v, 4, c);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) poly[(size_t)(c * 16 + j) * 256 + col] = f.out(v[j]);
-    } else {
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.in(poly[(size_t)(c * 16 + j) * 256 + col]);
-        radix16_inv(f, v, 4, c, false);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad((c * 16 + j) * 16 + lo)] = f.bits(v[j]);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad((j * 16 + c) * 16 + lo)]);
-        radix16_inv(f, v, 0, 0, true);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) poly[(size_t)(j * 16 + c) * 256 + col] = f.out(v[j]);
-    }
-}
-
-// pass A for N = 2^12: first 4 stages, 16 rows x 256 residues, registers only
-template <bool INV, class F>
-__device__ __forceinline__ void pass_a12_body(const F &f, u64 *__restrict__ poly) {
-    const u32 tid = threadIdx.x;
-    typename F::T v[16];
-#pragma unroll
-    for (u32 j = 0; j < 16; ++j) v[j] = f.in(poly[j * 256 + tid]);
-    if (!INV)
-        radix16_fwd(f, v, 0, 0);
-    else
-        radix16_inv(f, v, 0, 0, true);
-#pragma unroll
-    for (u32 j = 0; j < 16; ++j) poly[j * 256 + tid] = f.out(v[j]);
-}
-
 // which: 0 = pass A (N = 2^16), 1 = pass A (N = 2^12), 2 = pass B
 template <bool INV, int WHICH>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__ data,
@@ -160,13 +112,13 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__
     auto store = [&](u32 idx, u64 v) { poly[idx] = v; };
     if (mf.ok) {
         const FieldFp f = make_field_fp(mf, twf, limb, logN);
-        if (WHICH == 0) pass_a16_body<INV>(f, poly, lds);
-        if (WHICH == 1) pass_a12_body<INV>(f, poly);
+        if (WHICH == 0) pass_a16_body<INV>(f, lds, load, store);
+        if (WHICH == 1) pass_a12_body<INV>(f, load, store);
         if (WHICH == 2) pass_b_body<INV>(f, logN, lds, load, store);
     } else {
         const FieldInt f = make_field_int(mods, tw, ninv, limb, logN);
-        if (WHICH == 0) pass_a16_body<INV>(f, poly, lds);
-        if (WHICH == 1) pass_a12_body<INV>(f, poly);
+        if (WHICH == 0) pass_a16_body<INV>(f, lds, load, store);
+        if (WHICH == 1) pass_a12_body<INV>(f, load, store);
         if (WHICH == 2) pass_b_body<INV>(f, logN, lds, load, store);
     }
 }

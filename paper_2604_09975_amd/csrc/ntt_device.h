@@ -171,6 +171,55 @@ __device__ __forceinline__ void pass_b_body(const F &f, u32 logN, u64 *lds, Load
     }
 }
 
+// pass A for N = 2^16: first 8 stages on a tile of 256 rows x 16 consecutive residues (blockIdx.x picks the
+// 16 columns).  load(idx) / store(idx, value) see canonical residues at index idx of the polynomial.
+template <bool INV, class F, class Load, class Store>
+__device__ __forceinline__ void pass_a16_body(const F &f, u64 *lds, Load load, Store store) {
+    const u32 tid = threadIdx.x, c = tid >> 4, lo = tid & 15;
+    const u32 col = blockIdx.x * 16 + lo;
+    typename F::T v[16];
+    if (!INV) {
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) v[j] = f.in(load((j * 16 + c) * 256 + col));
+        radix16_fwd(f, v, 0, 0);
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) lds[lds_pad((j * 16 + c) * 16 + lo)] = f.bits(v[j]);
+        __syncthreads();
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad((c * 16 + j) * 16 + lo)]);
+        radix16_fwd(f, v, 4, c);
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) store((c * 16 + j) * 256 + col, f.out(v[j]));
+    } else {
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) v[j] = f.in(load((c * 16 + j) * 256 + col));
+        radix16_inv(f, v, 4, c, false);
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) lds[lds_pad((c * 16 + j) * 16 + lo)] = f.bits(v[j]);
+        __syncthreads();
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad((j * 16 + c) * 16 + lo)]);
+        radix16_inv(f, v, 0, 0, true);
+#pragma unroll
+        for (u32 j = 0; j < 16; ++j) store((j * 16 + c) * 256 + col, f.out(v[j]));
+    }
+}
+
+// pass A for N = 2^12: first 4 stages, 16 rows x 256 residues, registers only
+template <bool INV, class F, class Load, class Store>
+__device__ __forceinline__ void pass_a12_body(const F &f, Load load, Store store) {
+    const u32 tid = threadIdx.x;
+    typename F::T v[16];
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) v[j] = f.in(load(j * 256 + tid));
+    if (!INV)
+        radix16_fwd(f, v, 0, 0);
+    else
+        radix16_inv(f, v, 0, 0, true);
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) store(j * 256 + tid, f.out(v[j]));
+}
+
 // Field objects for limb `limb` from the parameter tables.
 __device__ __forceinline__ FieldFp make_field_fp(const ModFp &mf, const double *twf, u32 limb, u32 logN) {
     FieldFp f;
