@@ -36,7 +36,14 @@ class Encoder:
         v[..., self.pos] = z
         v[..., self.neg] = np.conj(z)
         m = (np.fft.fft(v, axis=-1) * self.twist).real * (scale / self.N)
-        return np.rint(m).astype(np.int64)
+        m = np.rint(m).astype(np.int64)
+        if np.isrealobj(z):
+            # a real slot vector is fixed by conjugation, so m(X) = m(1/X): m[N-j] = -m[j] exactly.  The FFT
+            # only gives that up to rounding; enforcing it lets the library read half of every weight limb.
+            h = self.N // 2
+            m[..., h + 1:] = -m[..., 1:h][..., ::-1]
+            m[..., h] = 0
+        return m
 
     def decode(self, m, scale):
         """m: N centred integers (array of Python ints or floats) -> n complex slots."""

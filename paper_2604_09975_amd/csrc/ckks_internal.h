@@ -100,6 +100,8 @@ struct ckks_weights {
     ckks::u32 level = 0, m = 0, C = 0, G = 0, B_out = 0, N1 = 0, N2 = 0;
     ckks::u64 *d_w = nullptr;          // [B_out][N2][G][N1][level][N], NTT domain; per limb a double (q < 2^50) or Montgomery form
     ckks::u64 *d_bias = nullptr;       // [B_out][level][N], NTT domain, canonical, times bias_mul; or null
+    bool all_real = true;              // every diagonal loaded so far encodes a real slot vector (palindromic limbs)
+    ckks::u32 *d_flag = nullptr;
 };
 
 namespace ckks {

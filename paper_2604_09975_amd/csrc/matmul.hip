@@ -119,6 +119,127 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
     }
 }
 
+// Same sum for plaintexts that encode REAL slot vectors.  Such a polynomial is fixed by X -> X^-1, so its
+// transform is a palindrome: w[k] = w[N-1-k] (the exponents 2*bitrev(k)+1 and 2*bitrev(N-1-k)+1 are
+// negatives of each other mod 2N).  Only the first half of every weight limb is read; each value serves
+// coefficient k and its mirror.  A thread owns coefficients k, k+1 and N-2-k, N-1-k and TB (b,p) pairs.
+// Workgroups go to the XCDs round-robin and each XCD has its own L2, so when the run count allows it the
+// linear workgroup id is unfolded to let one XCD walk all (b,p) tiles of a run of coefficients back to
+// back: the bank lines of that run are then fetched into one L2 once.
+template <u32 TB>
+__global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__restrict__ bank,
+                                                                  const u64 *__restrict__ w, u64 *__restrict__ acc,
+                                                                  const ModFp *__restrict__ modf, LimbIds limbs,
+                                                                  u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle) {
+    typedef u64 vec_t __attribute__((ext_vector_type(2)));
+    u32 tile = blockIdx.x, run = blockIdx.y;
+    if (swizzle) {
+        const u32 lin = blockIdx.y * gridDim.x + blockIdx.x;
+        const u32 xcd = lin & 7, slot = lin >> 3;
+        tile = slot % gridDim.x;
+        run = (slot / gridDim.x) * 8 + xcd;
+    }
+    const u32 bp0 = tile * TB;
+    const u32 k = (run * MM_THREADS + threadIdx.x) * 2;          // k < N/2
+    const u32 km = N - 2 - k;                                    // mirrors of k+1, k
+    const u32 i = limbs.id[blockIdx.z];
+    const size_t row = (size_t)i * N;
+    const size_t w_stride = (size_t)level * N;
+    const ModFp mf = modf[i];
+    const double q = mf.q, u = mf.u;
+    double a[TB][2][4];                                          // [pair][component][k, k+1, N-2-k, N-1-k]
+#pragma unroll
+    for (u32 t = 0; t < TB; ++t)
+#pragma unroll
+        for (u32 e = 0; e < 4; ++e) a[t][0][e] = a[t][1][e] = 0.0;
+    // loads of step gq+1 are issued before the arithmetic of step gq
+    vec_t xb[2][2], wb[TB];
+    auto fetch = [&](u32 gq) {
+#pragma unroll
+        for (u32 c = 0; c < 2; ++c) {
+            const u64 *b = bank + ((size_t)gq * 2 + c) * w_stride + row;
+            xb[c][0] = *reinterpret_cast<const vec_t *>(b + k);
+            xb[c][1] = *reinterpret_cast<const vec_t *>(b + km);
+        }
+#pragma unroll
+        for (u32 t = 0; t < TB; ++t)
+            if (bp0 + t < BP)
+                wb[t] = *reinterpret_cast<const vec_t *>(w + ((size_t)(bp0 + t) * GQ + gq) * w_stride + row + k);
+    };
+    fetch(0);
+    for (u32 gq = 0; gq < GQ; ++gq) {
+        double x[2][4];
+#pragma unroll
+        for (u32 c = 0; c < 2; ++c) {
+            const u64 r[4] = {xb[c][0][0], xb[c][0][1], xb[c][1][0], xb[c][1][1]};
+#pragma unroll
+            for (u32 e = 0; e < 4; ++e)
+                x[c][e] = __longlong_as_double((long long)(r[e] | 0x4330000000000000ull)) - 4503599627370496.0;
+        }
+        vec_t wc[TB];
+#pragma unroll
+        for (u32 t = 0; t < TB; ++t) wc[t] = wb[t];
+        if (gq + 1 < GQ) fetch(gq + 1);
+#pragma unroll
+        for (u32 t = 0; t < TB; ++t) {
+            if (bp0 + t < BP) {
+                // weight of k serves k and N-1-k; weight of k+1 serves k+1 and N-2-k
+                const double w0 = __longlong_as_double((long long)wc[t][0]);
+                const double w1 = __longlong_as_double((long long)wc[t][1]);
+                const double wv[4] = {w0, w1, w1, w0};
+#pragma unroll
+                for (u32 c = 0; c < 2; ++c)
+#pragma unroll
+                    for (u32 e = 0; e < 4; ++e) {
+                        const double h = x[c][e] * wv[e];
+                        const double l = fma(x[c][e], wv[e], -h);
+                        a[t][c][e] += fma(-rint(h * u), q, h) + l;
+                    }
+            }
+        }
+        if ((gq & 7) == 7) {
+#pragma unroll
+            for (u32 t = 0; t < TB; ++t)
+#pragma unroll
+                for (u32 c = 0; c < 2; ++c)
+#pragma unroll
+                    for (u32 e = 0; e < 4; ++e) a[t][c][e] = fma(-rint(a[t][c][e] * u), q, a[t][c][e]);
+        }
+    }
+#pragma unroll
+    for (u32 t = 0; t < TB; ++t) {
+        if (bp0 + t < BP) {
+#pragma unroll
+            for (u32 c = 0; c < 2; ++c) {
+                u64 o[4];
+#pragma unroll
+                for (u32 e = 0; e < 4; ++e) {
+                    double v = fma(-rint(a[t][c][e] * u), q, a[t][c][e]);
+                    if (v < 0) v += q;
+                    o[e] = (u64)__double_as_longlong(v + 4503599627370496.0) & 0x000fffffffffffffull;
+                }
+                u64 *dst = acc + ((size_t)(bp0 + t) * 2 + c) * w_stride + row;
+                vec_t lo, hi;
+                lo[0] = o[0];
+                lo[1] = o[1];
+                hi[0] = o[2];
+                hi[1] = o[3];
+                *reinterpret_cast<vec_t *>(dst + k) = lo;
+                *reinterpret_cast<vec_t *>(dst + km) = hi;
+            }
+        }
+    }
+}
+
+// sym[0] is cleared if some polynomial of the chunk is not fixed by X -> X^-1, i.e. breaks
+// c[N-j] == -c[j] for 0 < j < N (which also forces c[N/2] == 0)
+__global__ __launch_bounds__(EW_THREADS) void check_real_kernel(const int64_t *__restrict__ coef, u32 *sym, u32 N) {
+    const u32 n = blockIdx.x * EW_THREADS + threadIdx.x;
+    const int64_t *c = coef + (size_t)blockIdx.y * N;
+    if (n == 0) return;
+    if (c[N - n] != -c[n]) sym[0] = 0;
+}
+
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_int_kernel(const u64 *__restrict__ bank,
                                                                   const u64 *__restrict__ w, u64 *__restrict__ acc,
                                                                   const ModConst *__restrict__ mods, LimbIds limbs,
@@ -301,7 +422,21 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
                   (unsigned long long)total);
         return CKKS_E_INVAL;
     }
-    return expand_plain(w->params, w->level, d_coeffs, count, w->d_w + (size_t)first * w->level * w->params->N, true,
+    const ckks_params *P = w->params;
+    if (w->all_real && count) {
+        // real slot vectors are recognised by their coefficients (c[N-j] = -c[j]); one host read per chunk,
+        // this call is the offline weight-loading step
+        if (!w->d_flag) CKKS_HIP(hipMalloc((void **)&w->d_flag, sizeof(u32)));
+        u32 one = 1;
+        CKKS_HIP(hipMemcpyAsync(w->d_flag, &one, sizeof(u32), hipMemcpyHostToDevice, (hipStream_t)stream));
+        hipLaunchKernelGGL(check_real_kernel, dim3(P->N / EW_THREADS, count), dim3(EW_THREADS), 0, (hipStream_t)stream,
+                           d_coeffs, w->d_flag, P->N);
+        CKKS_LAUNCH_CHECK("check_real_kernel");
+        CKKS_HIP(hipMemcpyAsync(&one, w->d_flag, sizeof(u32), hipMemcpyDeviceToHost, (hipStream_t)stream));
+        CKKS_HIP(hipStreamSynchronize((hipStream_t)stream));
+        if (!one) w->all_real = false;
+    }
+    return expand_plain(P, w->level, d_coeffs, count, w->d_w + (size_t)first * w->level * P->N, true,
                         (hipStream_t)stream);
 }
 
@@ -324,6 +459,7 @@ void ckks_weights_destroy(ckks_weights_t *w) {
     if (!w) return;
     hipFree(w->d_w);
     hipFree(w->d_bias);
+    hipFree(w->d_flag);
     delete w;
 }
 
@@ -440,9 +576,16 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                 int_limbs.id[n_int++] = (uint8_t)i;
         }
         const dim3 tiles((BP + MM_TB - 1) / MM_TB, N / MM_THREADS);
-        if (n_fp)   // 8 accumulators x 2 coefficients per thread measured best (16-byte loads, 92 VGPRs)
+        if (n_fp && w->all_real && N >= 4 * MM_THREADS) {
+            const u32 runs = N / (4 * MM_THREADS);
+            // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
+            hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB>), dim3((BP + MM_TB - 1) / MM_TB, runs, n_fp),
+                               dim3(MM_THREADS), 0, stream, d_bank, w->d_w, d_acc, P->d_modf, fp_limbs, level, N, GQ,
+                               BP, runs % 8 == 0 ? 1u : 0u);
+        } else if (n_fp) {   // 8 accumulators x 2 coefficients per thread measured best (16-byte loads, 92 VGPRs)
             hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2>), dim3(tiles.x, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS),
                                0, stream, d_bank, w->d_w, d_acc, P->d_modf, fp_limbs, level, N, GQ, BP);
+        }
         if (n_int)
             hipLaunchKernelGGL(diag_mac_int_kernel, dim3(tiles.x, tiles.y, n_int), dim3(MM_THREADS), 0, stream, d_bank,
                                w->d_w, d_acc, P->d_mod, int_limbs, level, N, GQ, BP, flush);

@@ -17,7 +17,17 @@ def _B():
     return B
 
 
-def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_blocks=None):
+def make_real(m):
+    """Force c[N-j] = -c[j] (and c[N/2] = 0) on encoded coefficient arrays: the exact form of a plaintext
+    with real slots.  The library recognises such diagonals and reads half of each weight limb."""
+    N = m.shape[-1]
+    m = m.copy()
+    m[..., N // 2 + 1:] = -m[..., 1:N // 2][..., ::-1]
+    m[..., N // 2] = 0
+    return m
+
+
+def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_blocks=None, real=False):
     """Runs the projection on both sides from identical integer inputs; returns everything."""
     B = _B()
     N, n = O.N, O.n
@@ -28,6 +38,8 @@ def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_
     mx = E.encode(E.pack_columns(X, n, C) + 0j, sx, N)
     ct_x = np.stack([cl.encrypt_coeffs(mx[g], level) for g in range(G)])
     diag = E.encode_diagonals(Wm, m, N, C, N1, sw)
+    if real:
+        diag = make_real(diag)
     bias_c = None
     if bias is not None:
         bias_c = np.stack([E.encode(E.bias_slots(bias, m, n, C, b) + 0j, sx, N) for b in range(B_out)])
@@ -87,6 +99,29 @@ def test_bsgs_bias_ragged_shapes(N1, qbits, pbits):
     assert np.abs(Y - ref).max() <= 1e-3
     assert np.abs(slots.imag).max() <= 1e-3
     assert cnt.key_switches == 3 * (N1 - 1) + 2 * (16 // N1 - 1)
+
+
+@pytest.mark.parametrize("N1", [1, 4])
+def test_real_plaintexts_use_the_palindrome_path(N1):
+    """Diagonals with exactly antisymmetric coefficients (real slots): only half of each weight limb is read.
+    n = 2048 slots (one run of coefficients per workgroup row), ragged shapes, bias."""
+    O, P = make_pair(W.TOY_RING)
+    r = W.rng(21)
+    X = r.uniform(-1, 1, (16, 100))
+    Wm = r.uniform(-0.1, 0.1, (100, 70))
+    bias = r.uniform(-0.5, 0.5, 70)
+    Y, ref, cnt, slots = run_case(O, P, X, Wm, bias, 16, 64, N1 * 16, 30, 3, 23, real=True)
+    assert np.abs(Y - ref).max() <= 1e-3
+
+
+def test_one_unsymmetric_diagonal_turns_the_palindrome_path_off():
+    B = _B()
+    O, P = make_pair(W.TOY_RING)
+    r = W.rng(22)
+    X = r.uniform(-1, 1, (16, 64))
+    Wm = r.uniform(-0.1, 0.1, (64, 64))
+    Y, ref, cnt, _ = run_case(O, P, X, Wm, None, 16, 64, 16, 30, 3, 25, real=False)
+    assert np.abs(Y - ref).max() <= 1e-3
 
 
 def test_more_blocks_than_one_switch_batch():
