@@ -80,6 +80,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, cons
     }
 }
 
+constexpr u32 MAX_BETA = 4;    // digits the fused kernels unroll (larger dnum uses the plain kernels)
 constexpr u32 KEY_GROUP = 4;   // key switches that share one key are served by one thread
 
 struct ItemPack {
@@ -178,7 +179,8 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(ItemPack pack
 // ---- fused kernels for N = 2^12 / 2^16 -------------------------------------------------------------
 // Key inner product on the special limbs feeding straight into the first pass of their inverse transform:
 // row (comp, k, r) of y = INTT-pass-B( sum_j sigma_g(d_j)[p_k] * key_j[comp][p_k] ).
-// grid: x = tile of 4096, y = (comp*K + k)*n + r  (items that share a key sit next to each other).
+// grid: x = tile of 4096, y = ((k*n + r)*2 + comp): the two components of an item (same digit reads) and the
+// items of a batch that share a key sit next to each other and, with 16 tiles per row, on the same XCD.
 __global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64 *__restrict__ y,
                                                               const ModConst *__restrict__ mods,
                                                               const ModFp *__restrict__ modf,
@@ -188,31 +190,50 @@ __global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64
                                                               u32 L, u32 beta, u32 logN) {
     __shared__ u64 lds[FAST_LDS_WORDS];
     const u32 N = 1u << logN;
-    const u32 r = blockIdx.y % n, ck = blockIdx.y / n, k = ck % K, comp = ck / K;
+    const u32 comp = blockIdx.y & 1, r = (blockIdx.y >> 1) % n, k = (blockIdx.y >> 1) / n;
     const u32 gl = L + k, t = level + k, Wl = level + K, Wt = L + K;
     const SwitchItem &it = pack.it[r];
     const ModConst m = mods[gl];
     const u64 *dig = it.digits + (size_t)t * N;
     const u64 *key = it.key + ((size_t)comp * Wt + gl) * N;
     const u64 g = it.galois_elt;
-    auto load = [&](u32 idx) -> u64 {
-        const u32 kp = galois_index(idx, g, logN);
-        u128 acc = {0, 0};
-        for (u32 j = 0; j < beta; ++j) mac(acc, dig[(size_t)j * Wl * N + kp], key[(size_t)j * 2 * Wt * N + idx]);
-        return redc_wide(acc, m);
-    };
     u64 *out = y + (((size_t)r * 2 + comp) * K + k) * N;
     auto store = [&](u32 idx, u64 v) { out[idx] = v; };
+    // inner product into LDS, four residues at a time so that their 6*4 loads are in flight together
+    const u32 tid = threadIdx.x, base = blockIdx.x << 12;
+    for (u32 i0 = 0; i0 < 16; i0 += 4) {
+        u64 dv[4][MAX_BETA], kv[4][MAX_BETA];
+#pragma unroll
+        for (u32 e = 0; e < 4; ++e) {
+            const u32 idx = base + tid + 256 * (i0 + e);
+            const u32 kp = galois_index(idx, g, logN);
+#pragma unroll
+            for (u32 j = 0; j < MAX_BETA; ++j)
+                if (j < beta) {
+                    dv[e][j] = dig[(size_t)j * Wl * N + kp];
+                    kv[e][j] = __builtin_nontemporal_load(key + (size_t)j * 2 * Wt * N + idx);
+                }
+        }
+#pragma unroll
+        for (u32 e = 0; e < 4; ++e) {
+            u128 acc = {0, 0};
+#pragma unroll
+            for (u32 j = 0; j < MAX_BETA; ++j)
+                if (j < beta) mac(acc, dv[e][j], kv[e][j]);
+            lds[lds_pad(tid + 256 * (i0 + e))] = redc_wide(acc, m);
+        }
+    }
+    __syncthreads();
     const ModFp mf = modf[gl];
     if (mf.ok)
-        pass_b_body<true>(make_field_fp(mf, twf_inv, gl, logN), logN, lds, load, store);
+        pass_b_inv_from_lds(make_field_fp(mf, twf_inv, gl, logN), logN, lds, store);
     else
-        pass_b_body<true>(make_field_int(mods, tw_inv, ninv, gl, logN), logN, lds, load, store);
+        pass_b_inv_from_lds(make_field_int(mods, tw_inv, ninv, gl, logN), logN, lds, store);
 }
 
 // Last pass of the forward transform of w fused with the rest of the key switch on limb q_i:
 //   dst[comp][i] (+)= ( sum_j sigma_g(d_j)[q_i] * key_j[comp][q_i] - NTT(w)[i] ) * P^-1  (+ sigma_g(c0)[i] if comp = 0)
-// grid: x = tile of 4096, y = (comp*level + i)*n + r.
+// grid: x = tile of 4096, y = ((i*n + r)*2 + comp), neighbours share digit and key lines in L2 as above.
 __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack, const u64 *__restrict__ w,
                                                                   const ModConst *__restrict__ mods,
                                                                   const ModFp *__restrict__ modf,
@@ -223,7 +244,7 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
                                                                   u32 K, u32 L, u32 beta, u32 logN) {
     __shared__ u64 lds[FAST_LDS_WORDS];
     const u32 N = 1u << logN;
-    const u32 r = blockIdx.y % n, ci = blockIdx.y / n, i = ci % level, comp = ci / level;
+    const u32 comp = blockIdx.y & 1, r = (blockIdx.y >> 1) % n, i = (blockIdx.y >> 1) / n;
     const u32 Wl = level + K, Wt = L + K;
     const SwitchItem &it = pack.it[r];
     const ModConst m = mods[i];
@@ -234,21 +255,44 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
     u64 *dst = it.dst + ((size_t)comp * level + i) * N;
     const u64 g = it.galois_elt, pi = pinv[i];
     const u32 accumulate = it.accumulate;
-    auto load = [&](u32 idx) -> u64 { return wrow[idx]; };
-    auto store = [&](u32 idx, u64 what) {
-        const u32 kp = galois_index(idx, g, logN);
-        u128 acc = {0, 0};
-        for (u32 j = 0; j < beta; ++j) mac(acc, dig[(size_t)j * Wl * N + kp], key[(size_t)j * 2 * Wt * N + idx]);
-        u64 v = mont_mul(sub_mod(redc_wide(acc, m), what, m.q), pi, m);
-        if (comp == 0) v = add_mod(v, c0[kp], m.q);
-        if (accumulate) v = add_mod(v, dst[idx], m.q);
-        dst[idx] = v;
-    };
+    auto load = [&](u32 idx) -> u64 { return __builtin_nontemporal_load(wrow + idx); };
     const ModFp mf = modf[i];
     if (mf.ok)
-        pass_b_body<false>(make_field_fp(mf, twf_fwd, i, logN), logN, lds, load, store);
+        pass_b_fwd_to_lds(make_field_fp(mf, twf_fwd, i, logN), logN, lds, load);
     else
-        pass_b_body<false>(make_field_int(mods, tw_fwd, ninv, i, logN), logN, lds, load, store);
+        pass_b_fwd_to_lds(make_field_int(mods, tw_fwd, ninv, i, logN), logN, lds, load);
+    // epilogue, four residues at a time so that their loads are in flight together.  Keys, w and the output
+    // are streamed once: non-temporal, so that they do not push the digit rows (re-read by every item of the
+    // batch) out of L2.
+    const u32 tid = threadIdx.x, base = blockIdx.x << 12;
+    for (u32 i0 = 0; i0 < 16; i0 += 4) {
+        u64 dv[4][MAX_BETA], kv[4][MAX_BETA], cv[4], ov[4];
+#pragma unroll
+        for (u32 e = 0; e < 4; ++e) {
+            const u32 idx = base + tid + 256 * (i0 + e);
+            const u32 kp = galois_index(idx, g, logN);
+#pragma unroll
+            for (u32 j = 0; j < MAX_BETA; ++j)
+                if (j < beta) {
+                    dv[e][j] = dig[(size_t)j * Wl * N + kp];
+                    kv[e][j] = __builtin_nontemporal_load(key + (size_t)j * 2 * Wt * N + idx);
+                }
+            cv[e] = comp == 0 ? c0[kp] : 0;
+            ov[e] = accumulate ? __builtin_nontemporal_load(dst + idx) : 0;
+        }
+#pragma unroll
+        for (u32 e = 0; e < 4; ++e) {
+            const u32 idx = base + tid + 256 * (i0 + e);
+            u128 acc = {0, 0};
+#pragma unroll
+            for (u32 j = 0; j < MAX_BETA; ++j)
+                if (j < beta) mac(acc, dv[e][j], kv[e][j]);
+            u64 v = mont_mul(sub_mod(redc_wide(acc, m), lds[lds_pad(tid + 256 * (i0 + e))], m.q), pi, m);
+            v = add_mod(v, cv[e], m.q);
+            v = add_mod(v, ov[e], m.q);
+            __builtin_nontemporal_store(v, dst + idx);
+        }
+    }
 }
 
 size_t digits_words(const ckks_params *p, u32 level) {
@@ -329,7 +373,7 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
     }
     for (u32 g = n_groups; g < ROT_BATCH; ++g) pack.grp_first[g] = pack.grp_count[g] = 0;
     LimbIds ids;
-    if (fast_ring(p)) {
+    if (fast_ring(p) && beta <= MAX_BETA) {
         // inner product fused into the transforms on both sides of the base conversion
         u64 *y = d_work;                                   // [n][2][K][N]
         u64 *w = d_work + (size_t)n * 2 * K * N;           // [n][2][level][N]

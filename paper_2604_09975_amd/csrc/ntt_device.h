@@ -127,47 +127,67 @@ __device__ __forceinline__ void radix16_inv(const F &f, typename F::T (&v)[16], 
     }
 }
 
-// pass B: last 8 stages on 4096 consecutive residues (16 runs of 256).
-// load(idx) / store(idx, value) see canonical residues at index idx of the polynomial.  Forward: loads in
-// the strided register pattern (128-byte runs), stores coalesced.  Inverse: loads coalesced, stores strided.
-template <bool INV, class F, class Load, class Store>
-__device__ __forceinline__ void pass_b_body(const F &f, u32 logN, u64 *lds, Load load, Store store) {
+// pass B: last 8 stages on 4096 consecutive residues (16 runs of 256), in two halves so that callers can
+// put their own code between global memory and LDS.  LDS slot of residue e of the tile: lds[lds_pad(e)].
+//
+// forward: load(idx) gives the canonical residue at index idx of the polynomial (strided register pattern,
+// 128-byte runs); on return the tile's transformed, canonical residues are in LDS and the workgroup is synced.
+template <class F, class Load>
+__device__ __forceinline__ void pass_b_fwd_to_lds(const F &f, u32 logN, u64 *lds, Load load) {
     const u32 tid = threadIdx.x, blk = tid >> 4, c = tid & 15;
     const u32 base = blockIdx.x << 12;
     const u32 run = (base >> 8) + blk;              // which run of 256 in the polynomial
-    const u32 sa = logN - 8, sb = logN - 4;
     const u32 strided = blk * 256 + c, contig = blk * 256 + c * 16;
     typename F::T v[16];
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) v[j] = f.in(load(base + strided + j * 16));
+    radix16_fwd(f, v, logN - 8, run);
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) lds[lds_pad(strided + j * 16)] = f.bits(v[j]);
+    __syncthreads();
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(contig + j)]);
+    radix16_fwd(f, v, logN - 4, run * 16 + c);
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.out(v[j]);   // a thread's own slots
+    __syncthreads();
+}
+
+// inverse: expects the tile's canonical residues in LDS (workgroup synced); store(idx, value) receives the
+// canonical results in the strided register pattern.
+template <class F, class Store>
+__device__ __forceinline__ void pass_b_inv_from_lds(const F &f, u32 logN, u64 *lds, Store store) {
+    const u32 tid = threadIdx.x, blk = tid >> 4, c = tid & 15;
+    const u32 base = blockIdx.x << 12;
+    const u32 run = (base >> 8) + blk;
+    const u32 strided = blk * 256 + c, contig = blk * 256 + c * 16;
+    typename F::T v[16];
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) v[j] = f.in(lds[lds_pad(contig + j)]);
+    radix16_inv(f, v, logN - 4, run * 16 + c, false);
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.bits(v[j]);   // a thread's own slots
+    __syncthreads();
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(strided + j * 16)]);
+    radix16_inv(f, v, logN - 8, run, false);
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) store(base + strided + j * 16, f.out(v[j]));
+}
+
+// Whole pass with coalesced stores (forward) / coalesced loads (inverse).
+template <bool INV, class F, class Load, class Store>
+__device__ __forceinline__ void pass_b_body(const F &f, u32 logN, u64 *lds, Load load, Store store) {
+    const u32 tid = threadIdx.x, base = blockIdx.x << 12;
     if (!INV) {
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.in(load(base + strided + j * 16));
-        radix16_fwd(f, v, sa, run);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad(strided + j * 16)] = f.bits(v[j]);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(contig + j)]);
-        radix16_fwd(f, v, sb, run * 16 + c);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.out(v[j]);   // own slots: no barrier needed before
-        __syncthreads();
+        pass_b_fwd_to_lds(f, logN, lds, load);
 #pragma unroll
         for (u32 i = 0; i < 16; ++i) store(base + tid + 256 * i, lds[lds_pad(tid + 256 * i)]);
     } else {
 #pragma unroll
         for (u32 i = 0; i < 16; ++i) lds[lds_pad(tid + 256 * i)] = load(base + tid + 256 * i);
         __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.in(lds[lds_pad(contig + j)]);
-        radix16_inv(f, v, sb, run * 16 + c, false);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.bits(v[j]);   // own slots
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(strided + j * 16)]);
-        radix16_inv(f, v, sa, run, false);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) store(base + strided + j * 16, f.out(v[j]));
+        pass_b_inv_from_lds(f, logN, lds, store);
     }
 }
 
