@@ -81,6 +81,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, cons
 }
 
 constexpr u32 MAX_BETA = 4;    // digits the fused kernels unroll (larger dnum uses the plain kernels)
+constexpr u32 EPI = 4;         // residues whose loads are issued together in the fused kernels
 constexpr u32 KEY_GROUP = 4;   // key switches that share one key are served by one thread
 
 struct ItemPack {
@@ -201,10 +202,10 @@ __global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64
     auto store = [&](u32 idx, u64 v) { out[idx] = v; };
     // inner product into LDS, four residues at a time so that their 6*4 loads are in flight together
     const u32 tid = threadIdx.x, base = blockIdx.x << 12;
-    for (u32 i0 = 0; i0 < 16; i0 += 4) {
-        u64 dv[4][MAX_BETA], kv[4][MAX_BETA];
+    for (u32 i0 = 0; i0 < 16; i0 += EPI) {
+        u64 dv[EPI][MAX_BETA], kv[EPI][MAX_BETA];
 #pragma unroll
-        for (u32 e = 0; e < 4; ++e) {
+        for (u32 e = 0; e < EPI; ++e) {
             const u32 idx = base + tid + 256 * (i0 + e);
             const u32 kp = galois_index(idx, g, logN);
 #pragma unroll
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64
                 }
         }
 #pragma unroll
-        for (u32 e = 0; e < 4; ++e) {
+        for (u32 e = 0; e < EPI; ++e) {
             u128 acc = {0, 0};
 #pragma unroll
             for (u32 j = 0; j < MAX_BETA; ++j)
@@ -265,10 +266,10 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
     // are streamed once: non-temporal, so that they do not push the digit rows (re-read by every item of the
     // batch) out of L2.
     const u32 tid = threadIdx.x, base = blockIdx.x << 12;
-    for (u32 i0 = 0; i0 < 16; i0 += 4) {
-        u64 dv[4][MAX_BETA], kv[4][MAX_BETA], cv[4], ov[4];
+    for (u32 i0 = 0; i0 < 16; i0 += EPI) {
+        u64 dv[EPI][MAX_BETA], kv[EPI][MAX_BETA], cv[EPI], ov[EPI];
 #pragma unroll
-        for (u32 e = 0; e < 4; ++e) {
+        for (u32 e = 0; e < EPI; ++e) {
             const u32 idx = base + tid + 256 * (i0 + e);
             const u32 kp = galois_index(idx, g, logN);
 #pragma unroll
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
             ov[e] = accumulate ? __builtin_nontemporal_load(dst + idx) : 0;
         }
 #pragma unroll
-        for (u32 e = 0; e < 4; ++e) {
+        for (u32 e = 0; e < EPI; ++e) {
             const u32 idx = base + tid + 256 * (i0 + e);
             u128 acc = {0, 0};
 #pragma unroll
