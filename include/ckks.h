@@ -128,17 +128,26 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
 int ckks_weights_set_bias(ckks_weights_t *w, const int64_t *d_bias_coeffs, uint64_t bias_mul, void *stream);
 void ckks_weights_destroy(ckks_weights_t *w);
 
-/* Y = XW + bias on ciphertexts (Sec. 3.2 with real packing):
+/* Y = XW + bias on ciphertexts (Sec. 3.2):
  *   bank x_q^(g) = rot(x^(g); q*m), q < N1 (hoisted, one call per input);
  *   acc_{b,p} = sum_g sum_q x_q^(g) (.) w_{b,p,g,q};
- *   y_b = acc_{b,0} + sum_{p>=1} rot(acc_{b,p}; p*N1*m) + bias_b.
+ *   y_b = acc_{b,0} + sum_{p>=1} rot(acc_{b,p}; p*N1*m);
+ *   y_b += conj(y_b) if conj_key is given (decomplexification of Sec. 3.2: the inputs are then the
+ *          complexified x^(2u) + i*x^(2u+1), G counts them, and the complex weights of App. A.2.1 carry the
+ *          factor 1/2; one conjugation per output block, the count of App. A.2.2);
+ *   y_b += bias_b.
+ * The library is agnostic of what the slots hold: real packing (real diagonals), complex-pair compression
+ * (complex diagonals + conj_key) and the fused QK projection of App. A.2.3 (weights W_Q + i*W_K, no
+ * conj_key, Q and K come out in the real and imaginary parts) differ only in the plaintexts handed to
+ * ckks_weights_set_diagonals.
  * d_ct_x [G][2][level][N]; baby_keys: N1-1 handles for steps q*m (q = 1..);
- * giant_keys: N2-1 handles for steps p*N1*m; d_ct_y [B_out][2][level][N] at the
+ * giant_keys: N2-1 handles for steps p*N1*m; conj_key: NULL or the key of
+ * CKKS_STEP_CONJ; d_ct_y [B_out][2][level][N] at the
  * input level and scale(x)*scale(w) -- follow with ckks_rescale.  counters
  * (host, may be NULL) receives the operation counts. */
 int ckks_ctpt_matmul(ckks_params_t *params, const ckks_weights_t *w, const uint64_t *d_ct_x,
                      const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys,
-                     uint64_t *d_ct_y, ckks_counters_t *counters, void *stream);
+                     const ckks_gkey_t *conj_key, uint64_t *d_ct_y, ckks_counters_t *counters, void *stream);
 
 /* rescale (Sec. 2.2): drops limb level_in-1 and divides by its prime with
  * centred rounding.  d_ct_in [n_ct][2][level_in][N] -> d_ct_out

@@ -433,6 +433,7 @@ void orc_expand_plain(const orc_ctx *c, int level, const i64 *coef, u64 *out) {
  * call per input; q = 0 is the input itself);
  *   acc_{b,p} = sum_g sum_q x^(g)_q (.) w_{b,p,g,q}
  *   y_b = acc_{b,0} + sum_{p>=1} rot(acc_{b,p}; p*N1*m)   (each a full key switch)
+ *   y_b += conj(y_b)                                       (only if conj_key is given)
  *   y_b.c0 += bias_b * bias_mul.
  * diag [B_out][N2][G][N1][N] int64 coefficient-domain encodings; bias
  * [B_out][N] int64 or NULL; baby_keys[q-1] for step q*m, giant_keys[p-1] for
@@ -440,7 +441,7 @@ void orc_expand_plain(const orc_ctx *c, int level, const i64 *coef, u64 *out) {
  * written (at their own position in ct_y [B_out][2][level][N]). */
 void orc_ctpt_matmul(const orc_ctx *c, int level, int m, int G, int B_out, int N1, int N2,
                      const i64 *diag, const i64 *bias, u64 bias_mul, const u64 *ct_x,
-                     const u64 *const *baby_keys, const u64 *const *giant_keys, u64 *ct_y,
+                     const u64 *const *baby_keys, const u64 *const *giant_keys, const u64 *conj_key, u64 *ct_y,
                      int b_first, int b_count) {
     u64 N = c->N;
     u64 ctw = (u64)2 * level * N;
@@ -484,6 +485,17 @@ void orc_ctpt_matmul(const orc_ctx *c, int level, int m, int G, int B_out, int N
             u64 g = orc_galois_elt(c, (i64)p * N1 * m, 0);
             const u64 *key = giant_keys[p - 1];
             orc_rotate_hoisted(c, acc + (u64)p * ctw, level, &g, 1, &key, rot);
+            for (int ci = 0; ci < 2 * level; ci++) {
+                u64 qi = c->mod[ci % level];
+                for (u64 k = 0; k < N; k++) y[(u64)ci * N + k] = addmod(y[(u64)ci * N + k], rot[(u64)ci * N + k], qi);
+            }
+        }
+        /* decomplexification (Sec. 3.2): with complexified inputs x^(2u) + i x^(2u+1) and weights that carry
+         * the factor 1/2, the real part is y + conj(y).  Taken once per output block after the giant-step fold,
+         * the count of App. A.2.2 (#conj = O(B_out)). */
+        if (conj_key) {
+            u64 g = orc_galois_elt(c, 0, 1);
+            orc_rotate_hoisted(c, y, level, &g, 1, &conj_key, rot);
             for (int ci = 0; ci < 2 * level; ci++) {
                 u64 qi = c->mod[ci % level];
                 for (u64 k = 0; k < N; k++) y[(u64)ci * N + k] = addmod(y[(u64)ci * N + k], rot[(u64)ci * N + k], qi);

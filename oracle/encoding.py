@@ -163,3 +163,70 @@ def encode_diagonals(W, m, N, C, N1, scale, blocks=None):
             z = np.stack([weight_diagonal(W, m, n, C, N1, b, p, g, q) for g in range(G) for q in range(N1)])
             out[b, p] = encode(z, scale, N).reshape(G, N1, N)
     return out
+
+
+# ---------------------------------------------------------------------------
+# complex-pair compression and the fused QK projection (Sec. 3.2, App. A.2.1 / A.2.3)
+# ---------------------------------------------------------------------------
+def pack_columns_complex(X, n, C):
+    """Complexified inputs: ciphertext u holds x^(2u) + i*x^(2u+1), the real groups of pack_columns
+    (an odd last group has imaginary part zero).  [U][n] complex."""
+    real = pack_columns(X, n, C)
+    G = real.shape[0]
+    U = -(-G // 2)
+    out = np.zeros((U, n), dtype=np.complex128)
+    for u in range(U):
+        out[u] = real[2 * u]
+        if 2 * u + 1 < G:
+            out[u] = out[u] + 1j * real[2 * u + 1]
+    return out
+
+
+def weight_diagonal_complex(W, m, n, C, N1, b, p, u, q, half=True):
+    """Complex plaintext of App. A.2.1 for pair u: segment c holds
+        W[(2u)C + (c+q) mod C, bC + (c - p*N1) mod C] - i * W[(2u+1)C + (c+q) mod C, bC + (c - p*N1) mod C],
+    times 1/2 when the result is to be recovered as y + conj(y)."""
+    re = weight_diagonal(W, m, n, C, N1, b, p, 2 * u, q)
+    G = -(-W.shape[0] // C)
+    im = weight_diagonal(W, m, n, C, N1, b, p, 2 * u + 1, q) if 2 * u + 1 < G else np.zeros(n)
+    z = re - 1j * im
+    return 0.5 * z if half else z
+
+
+def encode_diagonals_complex(W, m, N, C, N1, scale, half=True):
+    """int64 [B_out][N2][U][N1][N] encodings of the complexified diagonals."""
+    n = N // 2
+    d_in, d_out = W.shape
+    G, B_out, N2 = -(-d_in // C), -(-d_out // C), C // N1
+    U = -(-G // 2)
+    out = np.zeros((B_out, N2, U, N1, N), dtype=np.int64)
+    for b in range(B_out):
+        for p in range(N2):
+            z = np.stack([weight_diagonal_complex(W, m, n, C, N1, b, p, u, q, half) for u in range(U) for q in range(N1)])
+            out[b, p] = encode(z, scale, N).reshape(U, N1, N)
+    return out
+
+
+def encode_diagonals_fused(WQ, WK, m, N, C, N1, scale):
+    """Fused QK projection (App. A.2.3): one projection with the complex weights W_Q + i*W_K on a REAL-packed
+    input yields Q in the real parts and K in the imaginary parts.  int64 [B_out][N2][G][N1][N]."""
+    n = N // 2
+    d_in, d_out = WQ.shape
+    G, B_out, N2 = -(-d_in // C), -(-d_out // C), C // N1
+    out = np.zeros((B_out, N2, G, N1, N), dtype=np.int64)
+    for b in range(B_out):
+        for p in range(N2):
+            z = np.stack([weight_diagonal(WQ, m, n, C, N1, b, p, g, q) + 1j * weight_diagonal(WK, m, n, C, N1, b, p, g, q)
+                          for g in range(G) for q in range(N1)])
+            out[b, p] = encode(z, scale, N).reshape(G, N1, N)
+    return out
+
+
+def score_friendly_permutation(H, d_h):
+    """pi_S of App. A.2.1: column k(h,u) = h*d_h + u of W_Q / W_K moves to position u*H + h.
+    Returns `perm` with W_perm[:, perm[k]] = W[:, k]."""
+    perm = np.empty(H * d_h, dtype=np.int64)
+    for h in range(H):
+        for u in range(d_h):
+            perm[h * d_h + u] = u * H + h
+    return perm

@@ -98,6 +98,24 @@ def diagonal_slots(Wm, m, n, C, N1, b, p):
     return np.repeat(vals, m, axis=-1)
 
 
+def pack_columns_complex(X, n, C):
+    """Complex-pair compression (Sec. 3.2): ciphertext u holds x^(2u) + i*x^(2u+1)."""
+    real = pack_columns(X, n, C)
+    if real.shape[0] % 2:
+        real = np.concatenate([real, np.zeros((1, n))])
+    return real[0::2] + 1j * real[1::2]
+
+
+def diagonal_slots_complex(Wm, m, n, C, N1, b, p, half=True):
+    """[U][N1][n] complex plaintexts of App. A.2.1: W[(2u)C + .., ..] - i*W[(2u+1)C + .., ..] (times 1/2 when the
+    real part is recovered as y + conj(y))."""
+    d = diagonal_slots(Wm, m, n, C, N1, b, p)                       # [G][N1][n]
+    if d.shape[0] % 2:
+        d = np.concatenate([d, np.zeros((1,) + d.shape[1:])])
+    z = d[0::2] - 1j * d[1::2]
+    return 0.5 * z if half else z
+
+
 class Client:
     """Secret-key holder bound to one parameter set."""
 

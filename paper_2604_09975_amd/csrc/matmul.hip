@@ -464,8 +464,8 @@ void ckks_weights_destroy(ckks_weights_t *w) {
 }
 
 int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *d_ct_x,
-                     const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys, uint64_t *d_ct_y,
-                     ckks_counters_t *counters, void *stream_) {
+                     const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys,
+                     const ckks_gkey_t *conj_key, uint64_t *d_ct_y, ckks_counters_t *counters, void *stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (!P || !w || !d_ct_x || !d_ct_y) {
         set_error("ckks_ctpt_matmul: null argument");
@@ -502,6 +502,10 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             set_error("ckks_ctpt_matmul: giant key %u missing or for the wrong Galois element", p);
             return k ? CKKS_E_INVAL : CKKS_E_NOKEY;
         }
+    }
+    if (conj_key && (conj_key->params != P || conj_key->galois_elt != 2ull * P->N - 1)) {
+        set_error("ckks_ctpt_matmul: conj_key is not a key for conjugation");
+        return CKKS_E_INVAL;
     }
     const uint64_t ntt0 = P->limb_ntts;
     const size_t ctw = (size_t)2 * level * N;
@@ -629,6 +633,31 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             if (rc) return rc;
         }
     }
+    // 3b. decomplexification: y_b += conj(y_b), one key switch per output block.  The switch gathers from
+    //     y_b while it writes, so it goes to the (now free) accumulator area first.
+    if (conj_key) {
+        for (u32 b0 = 0; b0 < B; b0 += batch) {
+            const u32 nb = std::min(batch, B - b0);
+            SwitchItem items[ROT_BATCH];
+            const u64 *c1s[ROT_BATCH];
+            for (u32 r = 0; r < nb; ++r) c1s[r] = d_ct_y + (size_t)(b0 + r) * ctw + (size_t)level * N;
+            rc = decompose(P, c1s, nb, level, d_digits, d_tmp, stream);
+            if (rc) return rc;
+            for (u32 r = 0; r < nb; ++r) {
+                items[r].digits = d_digits + (size_t)r * dig_w;
+                items[r].c0 = d_ct_y + (size_t)(b0 + r) * ctw;
+                items[r].key = conj_key->d_key;
+                items[r].dst = d_acc + (size_t)r * ctw;
+                items[r].galois_elt = conj_key->galois_elt;
+                items[r].accumulate = 0;
+            }
+            rc = switch_batch(P, level, items, nb, d_work, stream);
+            if (rc) return rc;
+            hipLaunchKernelGGL(add_rows_kernel, dim3(N / EW_THREADS, nb * 2 * level), dim3(EW_THREADS), 0, stream,
+                               d_ct_y + (size_t)b0 * ctw, d_acc, P->d_mod, level, N);
+            CKKS_LAUNCH_CHECK("add_rows_kernel");
+        }
+    }
     // 4. bias into c0
     if (w->d_bias) {
         for (u32 b = 0; b < B; ++b) {
@@ -645,6 +674,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             ks += (g != 1) ? G : 0;
         }
         for (u32 p = 1; p < N2; ++p) ks += (giant_g[p] != 1) ? B : 0;
+        if (conj_key) ks += B;
         counters->key_switches = ks;
         counters->ptmuls = (u64)GQ * BP;
         counters->limb_ntts = P->limb_ntts - ntt0;

@@ -167,3 +167,88 @@ def test_matmul_errors():
     with pytest.raises(B.CkksError) as e:
         B.ckks_ctpt_matmul(P, w, x, [None] * 31, [None])
     assert e.value.code == -3
+
+
+@pytest.mark.parametrize("d_in,spec", [(40, "small"), (100, "toy")])
+def test_complex_pair_compression_with_decomplexification(d_in, spec):
+    """Complexified inputs x^(2u) + i x^(2u+1), complex weights (times 1/2), y + conj(y) per output block:
+    residues bit for bit against the oracle, decrypted result against X @ W + b."""
+    B = _B()
+    if spec == "small":
+        O = helpers.small_oracle(10, L=3, K=1, dnum=3, qbits=40, pbits=42)
+        _, P = make_pair(O)
+        m, C, N1, d_out, hw = 4, 16, 4, 20, 16
+    else:
+        O, P = make_pair(W.TOY_RING)
+        m, C, N1, d_out, hw = 16, 64, 16, 70, 64
+    N, n, level = O.N, O.n, 3
+    r = W.rng(d_in)
+    X = r.uniform(-1, 1, (m, d_in))
+    Wm = r.uniform(-0.1, 0.1, (d_in, d_out))
+    bias = r.uniform(-0.5, 0.5, d_out)
+    G, B_out, N2 = -(-d_in // C), -(-d_out // C), C // N1
+    U = -(-G // 2)
+    cl = helpers.Client(O, 41, hamming_weight=hw)
+    sc = 2.0**30
+    mx = E.encode(E.pack_columns_complex(X, n, C), sc, N)
+    ct_x = np.stack([cl.encrypt_coeffs(mx[u], level) for u in range(U)])
+    diag = E.encode_diagonals_complex(Wm, m, N, C, N1, sc, half=True)
+    bias_c = np.stack([E.encode(E.bias_slots(bias, m, n, C, b) + 0j, sc, N) for b in range(B_out)])
+    baby_np, baby_h = load_keys(P, O, cl, [q * m for q in range(1, N1)])
+    giant_np, giant_h = load_keys(P, O, cl, [p * N1 * m for p in range(1, N2)])
+    (conj_np,), (conj_h,) = load_keys(P, O, cl, ["conj"])
+    w = B.ckks_weights_create(P, level, m, C, U, B_out, N1)
+    B.ckks_weights_set_diagonals(w, 0, to_dev(diag.reshape(-1, N)))
+    B.ckks_weights_set_bias(w, to_dev(bias_c), int(sc))
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, conj_key=conj_h)
+    y_res = B.ckks_rescale(P, y_dev, level, B_out)
+    torch.cuda.synchronize()
+    want = O.ctpt_matmul(level, m, U, B_out, N1, N2, diag, bias_c, int(sc), ct_x, baby_np, giant_np, conj_key=conj_np)
+    assert (to_host(y_dev) == want).all()
+    assert (to_host(y_res) == O.rescale(want, level)).all()
+    assert cnt.key_switches == U * (N1 - 1) + B_out * (N2 - 1) + B_out
+    got = to_host(y_res)
+    slots = np.stack([cl.decrypt_slots(got[b], 2, sc * sc / O.q[2], nlimbs=2) for b in range(B_out)])
+    assert np.abs(E.unpack_columns(slots.real, m, C, d_out) - (X @ Wm + bias)).max() <= 1e-3
+    assert np.abs(slots.imag).max() <= 1e-3
+
+
+def test_fused_qk_projection():
+    """Weights W_Q + i W_K on a real-packed input: one projection, Q in the real and K in the imaginary parts."""
+    B = _B()
+    O, P = make_pair(W.TOY_RING)
+    m, C, N1, level = 16, 64, 16, 3
+    N, n = O.N, O.n
+    r = W.rng(55)
+    X = r.uniform(-1, 1, (m, 128))
+    WQ, WK = r.uniform(-0.1, 0.1, (128, 64)), r.uniform(-0.1, 0.1, (128, 64))
+    G, B_out, N2 = 2, 1, C // N1
+    cl = helpers.Client(O, 43)
+    sc = 2.0**30
+    mx = E.encode(E.pack_columns(X, n, C) + 0j, sc, N)
+    ct_x = np.stack([cl.encrypt_coeffs(mx[g], level) for g in range(G)])
+    diag = E.encode_diagonals_fused(WQ, WK, m, N, C, N1, sc)
+    baby_np, baby_h = load_keys(P, O, cl, [q * m for q in range(1, N1)])
+    giant_np, giant_h = load_keys(P, O, cl, [p * N1 * m for p in range(1, N2)])
+    w = B.ckks_weights_create(P, level, m, C, G, B_out, N1)
+    B.ckks_weights_set_diagonals(w, 0, to_dev(diag.reshape(-1, N)))
+    y_dev, _ = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h)
+    y_res = to_host(B.ckks_rescale(P, y_dev, level, B_out))
+    want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, None, 0, ct_x, baby_np, giant_np)
+    assert (to_host(y_dev) == want).all()
+    slots = cl.decrypt_slots(y_res[0], 2, sc * sc / O.q[2], nlimbs=2)[None]
+    assert np.abs(E.unpack_columns(slots.real, m, C, 64) - X @ WQ).max() <= 1e-3
+    assert np.abs(E.unpack_columns(slots.imag, m, C, 64) - X @ WK).max() <= 1e-3
+
+
+def test_conj_key_must_be_a_conjugation_key():
+    B = _B()
+    O, P = make_pair(W.TOY_RING)
+    cl = helpers.Client(O, 44)
+    _, (k1,) = load_keys(P, O, cl, [1])
+    w = B.ckks_weights_create(P, 3, 16, 64, 1, 1, 1)
+    x = torch.zeros((1, 2, 3, O.N), dtype=torch.int64, device="cuda")
+    _, giant = load_keys(P, O, cl, [p * 16 for p in range(1, 64)])
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_ctpt_matmul(P, w, x, [], giant, conj_key=k1)
+    assert e.value.code == -1
