@@ -100,8 +100,9 @@ struct ckks_weights {
     ckks::u32 level = 0, m = 0, C = 0, G = 0, B_out = 0, N1 = 0, N2 = 0;
     ckks::u64 *d_w = nullptr;          // [B_out][N2][G][N1][level][N], NTT domain; per limb a double (q < 2^50) or Montgomery form
     ckks::u64 *d_bias = nullptr;       // [B_out][level][N], NTT domain, canonical, times bias_mul; or null
-    bool all_real = true;              // every diagonal loaded so far encodes a real slot vector (palindromic limbs)
-    ckks::u32 *d_flag = nullptr;
+    std::vector<uint8_t> block_real;   // per output block: every diagonal loaded so far encodes a real slot vector
+    ckks::u32 *d_flag = nullptr;       // per-diagonal check results of the chunk being loaded
+    ckks::u32 flag_cap = 0;
 };
 
 namespace ckks {

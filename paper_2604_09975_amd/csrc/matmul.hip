@@ -66,22 +66,34 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
     for (u32 t = 0; t < TB; ++t)
 #pragma unroll
         for (u32 e = 0; e < VEC; ++e) a0[t][e] = a1[t][e] = 0.0;
+    // loads of step gq+1 are issued before the arithmetic of step gq
+    vec_t xb0, xb1, wb[TB];
+    auto fetch = [&](u32 gq) {
+        xb0 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 0) * w_stride + limb_off);
+        xb1 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 1) * w_stride + limb_off);
+#pragma unroll
+        for (u32 t = 0; t < TB; ++t)
+            if (bp0 + t < BP)
+                wb[t] = *reinterpret_cast<const vec_t *>(w + ((size_t)(bp0 + t) * GQ + gq) * w_stride + limb_off);
+    };
+    fetch(0);
     for (u32 gq = 0; gq < GQ; ++gq) {
-        const vec_t r0 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 0) * w_stride + limb_off);
-        const vec_t r1 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 1) * w_stride + limb_off);
         double x0[VEC], x1[VEC];
 #pragma unroll
         for (u32 e = 0; e < VEC; ++e) {
-            x0[e] = __longlong_as_double((long long)(r0[e] | 0x4330000000000000ull)) - 4503599627370496.0;
-            x1[e] = __longlong_as_double((long long)(r1[e] | 0x4330000000000000ull)) - 4503599627370496.0;
+            x0[e] = __longlong_as_double((long long)(xb0[e] | 0x4330000000000000ull)) - 4503599627370496.0;
+            x1[e] = __longlong_as_double((long long)(xb1[e] | 0x4330000000000000ull)) - 4503599627370496.0;
         }
+        vec_t wc[TB];
+#pragma unroll
+        for (u32 t = 0; t < TB; ++t) wc[t] = wb[t];
+        if (gq + 1 < GQ) fetch(gq + 1);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t) {
             if (bp0 + t < BP) {
-                const vec_t wr = *reinterpret_cast<const vec_t *>(w + ((size_t)(bp0 + t) * GQ + gq) * w_stride + limb_off);
 #pragma unroll
                 for (u32 e = 0; e < VEC; ++e) {
-                    const double wv = __longlong_as_double((long long)wr[e]);
+                    const double wv = __longlong_as_double((long long)wc[t][e]);
                     // x*w = h + l exactly; subtract the nearest multiple of q: |r| < 0.9 q
                     const double h0 = x0[e] * wv, h1 = x1[e] * wv;
                     const double l0 = fma(x0[e], wv, -h0), l1 = fma(x1[e], wv, -h1);
@@ -231,13 +243,18 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
     }
 }
 
-// sym[0] is cleared if some polynomial of the chunk is not fixed by X -> X^-1, i.e. breaks
+// sym[d] is cleared if polynomial d of the chunk is not fixed by X -> X^-1, i.e. breaks
 // c[N-j] == -c[j] for 0 < j < N (which also forces c[N/2] == 0)
 __global__ __launch_bounds__(EW_THREADS) void check_real_kernel(const int64_t *__restrict__ coef, u32 *sym, u32 N) {
     const u32 n = blockIdx.x * EW_THREADS + threadIdx.x;
     const int64_t *c = coef + (size_t)blockIdx.y * N;
     if (n == 0) return;
-    if (c[N - n] != -c[n]) sym[0] = 0;
+    if (c[N - n] != -c[n]) sym[blockIdx.y] = 0;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void fill_u32_kernel(u32 *p, u32 v, u32 n) {
+    const u32 i = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (i < n) p[i] = v;
 }
 
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_int_kernel(const u64 *__restrict__ bank,
@@ -400,6 +417,7 @@ int ckks_weights_create(const ckks_params_t *P, uint32_t level, uint32_t m, uint
     w->B_out = B_out;
     w->N1 = N1;
     w->N2 = C / N1;
+    w->block_real.assign(B_out, 1);
     size_t words = (size_t)B_out * w->N2 * G * N1 * level * P->N;
     hipError_t e = hipMalloc((void **)&w->d_w, words * sizeof(u64));
     if (e != hipSuccess) {
@@ -423,18 +441,28 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
         return CKKS_E_INVAL;
     }
     const ckks_params *P = w->params;
-    if (w->all_real && count) {
-        // real slot vectors are recognised by their coefficients (c[N-j] = -c[j]); one host read per chunk,
-        // this call is the offline weight-loading step
-        if (!w->d_flag) CKKS_HIP(hipMalloc((void **)&w->d_flag, sizeof(u32)));
-        u32 one = 1;
-        CKKS_HIP(hipMemcpyAsync(w->d_flag, &one, sizeof(u32), hipMemcpyHostToDevice, (hipStream_t)stream));
+    if (count) {
+        // real slot vectors are recognised by their coefficients (c[N-j] = -c[j]); an output block whose
+        // diagonals all pass is read through the palindrome kernel.  One host read per chunk: this call is
+        // the offline weight-loading step.
+        if (w->flag_cap < count) {
+            hipFree(w->d_flag);
+            w->d_flag = nullptr;
+            CKKS_HIP(hipMalloc((void **)&w->d_flag, count * sizeof(u32)));
+            w->flag_cap = count;
+        }
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((count + EW_THREADS - 1) / EW_THREADS), dim3(EW_THREADS), 0,
+                           (hipStream_t)stream, w->d_flag, 1u, count);
         hipLaunchKernelGGL(check_real_kernel, dim3(P->N / EW_THREADS, count), dim3(EW_THREADS), 0, (hipStream_t)stream,
                            d_coeffs, w->d_flag, P->N);
         CKKS_LAUNCH_CHECK("check_real_kernel");
-        CKKS_HIP(hipMemcpyAsync(&one, w->d_flag, sizeof(u32), hipMemcpyDeviceToHost, (hipStream_t)stream));
+        std::vector<u32> flags(count);
+        CKKS_HIP(hipMemcpyAsync(flags.data(), w->d_flag, count * sizeof(u32), hipMemcpyDeviceToHost,
+                                (hipStream_t)stream));
         CKKS_HIP(hipStreamSynchronize((hipStream_t)stream));
-        if (!one) w->all_real = false;
+        const u32 per_block = w->N2 * w->G * w->N1;
+        for (u32 d = 0; d < count; ++d)
+            if (!flags[d]) w->block_real[(first + d) / per_block] = 0;
     }
     return expand_plain(P, w->level, d_coeffs, count, w->d_w + (size_t)first * w->level * P->N, true,
                         (hipStream_t)stream);
@@ -580,15 +608,26 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                 int_limbs.id[n_int++] = (uint8_t)i;
         }
         const dim3 tiles((BP + MM_TB - 1) / MM_TB, N / MM_THREADS);
-        if (n_fp && w->all_real && N >= 4 * MM_THREADS) {
-            const u32 runs = N / (4 * MM_THREADS);
-            // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
-            hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB>), dim3((BP + MM_TB - 1) / MM_TB, runs, n_fp),
-                               dim3(MM_THREADS), 0, stream, d_bank, w->d_w, d_acc, P->d_modf, fp_limbs, level, N, GQ,
-                               BP, runs % 8 == 0 ? 1u : 0u);
-        } else if (n_fp) {   // 8 accumulators x 2 coefficients per thread measured best (16-byte loads, 92 VGPRs)
-            hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2>), dim3(tiles.x, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS),
-                               0, stream, d_bank, w->d_w, d_acc, P->d_modf, fp_limbs, level, N, GQ, BP);
+        // runs of output blocks of one kind: real diagonals (palindrome kernel, half of each weight limb read)
+        // or general ones
+        for (u32 b0 = 0; n_fp && b0 < B;) {
+            u32 b1 = b0 + 1;
+            while (b1 < B && w->block_real[b1] == w->block_real[b0]) ++b1;
+            const u32 bp_first = b0 * N2, bp_count = (b1 - b0) * N2;
+            const u64 *wp = w->d_w + (size_t)bp_first * GQ * level * N;
+            u64 *ap = d_acc + (size_t)bp_first * ctw;
+            if (w->block_real[b0] && N >= 4 * MM_THREADS) {
+                const u32 runs = N / (4 * MM_THREADS);
+                // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
+                hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB>), dim3((bp_count + MM_TB - 1) / MM_TB, runs, n_fp),
+                                   dim3(MM_THREADS), 0, stream, d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ,
+                                   bp_count, runs % 8 == 0 ? 1u : 0u);
+            } else {   // 8 accumulators x 2 coefficients per thread (16-byte loads)
+                hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2>),
+                                   dim3((bp_count + MM_TB - 1) / MM_TB, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS), 0,
+                                   stream, d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count);
+            }
+            b0 = b1;
         }
         if (n_int)
             hipLaunchKernelGGL(diag_mac_int_kernel, dim3(tiles.x, tiles.y, n_int), dim3(MM_THREADS), 0, stream, d_bank,
