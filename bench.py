@@ -26,12 +26,20 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None):
+def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False):
+    """fused_qk: the d_out columns are [Q | K | V]; Q and K go through ONE projection with the complex weights
+    W_Q + i*W_K (App. A.2.3), V through real weights: 2/3 of the output blocks and giant steps."""
     import torch
     N, n = P.N, P.N // 2
     level = P.L
     X, Wm, bias = W.matmul_inputs(spec)
-    G, B_out = -(-spec.d_in // spec.C), -(-spec.d_out // spec.C)
+    third = spec.d_out // 3
+    parts = [(Wm, 0)]                                        # (matrix, first output block)
+    if fused_qk:
+        parts = [(Wm[:, :third] + 1j * Wm[:, third:2 * third], 0), (Wm[:, 2 * third:], -(-third // spec.C))]
+        bias = None
+    G = -(-spec.d_in // spec.C)
+    B_out = sum(-(-M.shape[1] // spec.C) for M, _ in parts)
     N2 = spec.C // n1
     scale = 2.0 ** spec.ring.log_scale
     t0 = time.time()
@@ -49,11 +57,12 @@ def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None):
     ct_x = torch.stack([cl.encrypt_slots(xs[g], scale, level) for g in range(G)])
     w = B.ckks_weights_create(P, level, spec.m, spec.C, G, B_out, n1)
     t0 = time.time()
-    for b in range(B_out):
-        for p in range(N2):
-            z = CL.diagonal_slots(Wm, spec.m, n, spec.C, n1, b, p).reshape(G * n1, n)
-            coeffs = cl.enc.encode(z, scale)
-            B.ckks_weights_set_diagonals(w, (b * N2 + p) * G * n1, torch.from_numpy(coeffs).cuda())
+    for M, b_first in parts:
+        for b in range(-(-M.shape[1] // spec.C)):
+            for p in range(N2):
+                z = CL.diagonal_slots(M, spec.m, n, spec.C, n1, b, p).reshape(G * n1, n)
+                coeffs = cl.enc.encode(z, scale)
+                B.ckks_weights_set_diagonals(w, ((b_first + b) * N2 + p) * G * n1, torch.from_numpy(coeffs).cuda())
     if bias is not None:
         nseg = n // spec.m
         bz = np.zeros((B_out, n))
@@ -65,6 +74,8 @@ def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None):
     torch.cuda.synchronize()
     log(f"[bench] {G * n1 * B_out * N2} weight diagonals encoded and expanded in {time.time() - t0:.1f}s")
     ref = X @ Wm + (bias if bias is not None else 0.0)
+    if fused_qk:
+        ref = np.concatenate([X @ parts[0][0], X @ parts[1][0] + 0j], axis=1)       # [Q + iK | V]
     return dict(ct_x=ct_x, w=w, baby=baby, giant=giant, ref=ref, G=G, B_out=B_out, N2=N2, scale=scale, level=level)
 
 
@@ -268,6 +279,8 @@ def main():
                     help="bert_qkv (default, the headline configuration), the four GPT-2-small block layers, the "
                          "hoisted rotation batch alone, or the NTT microbenchmark")
     ap.add_argument("--no-hoisted", action="store_true", help="skip the hoisted-rotation batch")
+    ap.add_argument("--fused-qk", action="store_true",
+                    help="bert_qkv only: Q and K through one projection with weights W_Q + i*W_K (no bias)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 4 GiB device-to-device copy, 10 times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -304,7 +317,7 @@ def main():
     if args.workload == "hoisted":
         run_hoisted(args, B, CL, W, P, cl)
         return
-    S = setup_matmul(B, CL, W, P, cl, spec, n1)
+    S = setup_matmul(B, CL, W, P, cl, spec, n1, fused_qk=args.fused_qk)
     N, level, B_out, G, N2 = P.N, S["level"], S["B_out"], S["G"], S["N2"]
     y = torch.empty((B_out, 2, level, N), dtype=torch.int64, device="cuda")
     yr = torch.empty((B_out, 2, level - 1, N), dtype=torch.int64, device="cuda")
@@ -335,7 +348,10 @@ def main():
     if not args.no_check:
         out_scale = S["scale"] * S["scale"] / P.q[level - 1]
         slots = np.stack([cl.decrypt_slots(yr[b], level - 1, out_scale) for b in range(B_out)])
-        Y = CL.unpack_columns(slots.real, spec.m, spec.C, spec.d_out)
+        if args.fused_qk:
+            Y = CL.unpack_columns(slots, spec.m, spec.C, S["ref"].shape[1])
+        else:
+            Y = CL.unpack_columns(slots.real, spec.m, spec.C, spec.d_out)
         max_err = float(np.abs(Y - S["ref"]).max())
         log(f"[bench] decrypted max abs error vs fp64 X@W+b: {max_err:.3e}")
         if not max_err <= 1e-3:
@@ -363,6 +379,8 @@ def main():
     # vectors, whose transforms are palindromes), 8 bytes per residue
     limb_poly = 8 * N
     mac_bytes = (G * n1 * B_out * N2 * level // 2 + G * n1 * 2 * level + B_out * N2 * 2 * level) * limb_poly
+    if args.fused_qk:   # the complex Q+iK blocks (half of the blocks) are read in full
+        mac_bytes += G * n1 * (B_out // 2) * N2 * level // 2 * limb_poly
     achieved = mac_bytes / (mac_ms * 1e-3) / 1e9
     ks_bytes = 188.7e6
     traffic = read_traffic(spec.name, n1)
@@ -379,7 +397,7 @@ def main():
         "vs_baseline": None,
         "dtype": "u64",
         "data": "synthetic",
-        "config": {"workload": spec.name, "N": N, "q_limbs": P.L, "special_limbs": P.K, "dnum": P.dnum,
+        "config": {"workload": spec.name + ("_fused_qk" if args.fused_qk else ""), "N": N, "q_limbs": P.L, "special_limbs": P.K, "dnum": P.dnum,
                    "log_scale": ring.log_scale, "m": spec.m, "d_in": spec.d_in, "d_out": spec.d_out,
                    "C": spec.C, "G": G, "B_out": B_out, "N1": n1, "N2": N2,
                    "key_switches_per_step": int(cnt.key_switches), "ptmuls_per_step": int(cnt.ptmuls),

@@ -79,7 +79,7 @@ def pack_columns(X, n, C):
 
 def unpack_columns(slots, m, C, d_out):
     Bn = slots.shape[0]
-    Y = slots.reshape(Bn, -1, m)[:, :C, :]          # [B][C][m]
+    Y = slots.reshape(Bn, -1, m)[:, :C, :]          # [B][C][m] (real or complex)
     return Y.transpose(2, 0, 1).reshape(m, Bn * C)[:, :d_out]
 
 
@@ -89,7 +89,7 @@ def diagonal_slots(Wm, m, n, C, N1, b, p):
     d_in, d_out = Wm.shape
     nseg = n // m
     G = -(-d_in // C)
-    Wp = np.zeros((G * C, (-(-d_out // C)) * C))
+    Wp = np.zeros((G * C, (-(-d_out // C)) * C), dtype=Wm.dtype)
     Wp[:d_in, :d_out] = Wm
     c = np.arange(nseg) % C
     col = b * C + (c - p * N1) % C                                               # [nseg]
