@@ -68,3 +68,44 @@ def test_bert_qkv_sampled_block_bit_exact():
     print(f"[full] max abs err {err:.2e}, total {time.time() - t0:.0f}s", flush=True)
     assert err <= 1e-3
     assert np.abs(slots.imag).max() <= 1e-3
+
+
+def test_gpt2_ffn_down_width_one_block_bit_exact():
+    """Full ring, the input width of the GPT-2 FFN-down layer (d_in = 3072: twelve input ciphertexts, so the
+    baby-step batches hold one step of all inputs each), one output block of 256 columns, every residue of it
+    against the oracle.  Run at level 9 of 24 (two digits, the second with a single limb) to keep the oracle
+    under half a minute and to cover a partial last digit at N = 2^16."""
+    from paper_2604_09975_amd import binding as B
+    t0 = time.time()
+    spec = W.GPT2_LAYERS[3]
+    O, P = make_pair(spec.ring)
+    N, n, m, C, N1 = O.N, O.n, spec.m, spec.C, spec.N1
+    G, N2, B_out, d_out = 12, C // N1, 1, 256
+    level = 9
+    scale = 2.0 ** spec.ring.log_scale
+    X, Wm, bias = W.matmul_inputs(spec)
+    Wm, bias = Wm[:, :d_out], bias[:d_out]
+    cl = helpers.Client(O, spec.seed)
+    mx = E.encode(E.pack_columns(X, n, C) + 0j, scale, N)
+    ct_x = np.stack([cl.encrypt_coeffs(mx[g], level) for g in range(G)])
+    baby_np, baby_h = load_keys(P, O, cl, [q * m for q in range(1, N1)])
+    giant_np, giant_h = load_keys(P, O, cl, [p * N1 * m for p in range(1, N2)])
+    bias_c = np.stack([E.encode(E.bias_slots(bias, m, n, C, 0) + 0j, scale, N)])
+    diag = make_real(E.encode_diagonals(Wm, m, N, C, N1, scale))
+    w = B.ckks_weights_create(P, level, m, C, G, B_out, N1)
+    B.ckks_weights_set_diagonals(w, 0, to_dev(diag.reshape(-1, N)))
+    B.ckks_weights_set_bias(w, to_dev(bias_c), int(scale))
+    print(f"[ffn] inputs ready {time.time() - t0:.0f}s", flush=True)
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h)
+    y_res = B.ckks_rescale(P, y_dev, level, B_out)
+    torch.cuda.synchronize()
+    assert cnt.key_switches == G * (N1 - 1) + B_out * (N2 - 1)
+    want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(scale), ct_x, baby_np, giant_np)
+    print(f"[ffn] oracle done {time.time() - t0:.0f}s", flush=True)
+    assert (to_host(y_dev) == want).all()
+    got_res = to_host(y_res)
+    assert (got_res == O.rescale(want, level)).all()
+    slots = cl.decrypt_slots(got_res[0], level - 1, scale * scale / O.q[level - 1], nlimbs=2)[None]
+    err = np.abs(E.unpack_columns(slots.real, m, C, d_out) - (X @ Wm + bias)).max()
+    print(f"[ffn] max abs err {err:.2e}, total {time.time() - t0:.0f}s", flush=True)
+    assert err <= 1e-3
