@@ -279,6 +279,8 @@ def main():
                     help="bert_qkv (default, the headline configuration), the four GPT-2-small block layers, the "
                          "hoisted rotation batch alone, or the NTT microbenchmark")
     ap.add_argument("--no-hoisted", action="store_true", help="skip the hoisted-rotation batch")
+    ap.add_argument("--merged-giant", action="store_true",
+                    help="giant step with one ModDown per output block (CKKS_MATMUL_MERGED_GIANT)")
     ap.add_argument("--fused-qk", action="store_true",
                     help="bert_qkv only: Q and K through one projection with weights W_Q + i*W_K (no bias)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -323,7 +325,8 @@ def main():
     yr = torch.empty((B_out, 2, level - 1, N), dtype=torch.int64, device="cuda")
 
     def step():
-        _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y)
+        _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y,
+                                    flags=B.MATMUL_MERGED_GIANT if args.merged_giant else 0)
         B.ckks_rescale(P, y, level, B_out, yr)
         return cnt
 
@@ -400,6 +403,7 @@ def main():
         "config": {"workload": spec.name + ("_fused_qk" if args.fused_qk else ""), "N": N, "q_limbs": P.L, "special_limbs": P.K, "dnum": P.dnum,
                    "log_scale": ring.log_scale, "m": spec.m, "d_in": spec.d_in, "d_out": spec.d_out,
                    "C": spec.C, "G": G, "B_out": B_out, "N1": n1, "N2": N2,
+                   "giant_step": "merged ModDown" if args.merged_giant else "one key switch per rotation",
                    "key_switches_per_step": int(cnt.key_switches), "ptmuls_per_step": int(cnt.ptmuls),
                    "limb_ntts_per_step": int(cnt.limb_ntts)},
         "key_switches_per_s": ks_per_s,

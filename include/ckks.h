@@ -136,6 +136,11 @@ void ckks_weights_destroy(ckks_weights_t *w);
  *          complexified x^(2u) + i*x^(2u+1), G counts them, and the complex weights of App. A.2.1 carry the
  *          factor 1/2; one conjugation per output block, the count of App. A.2.2);
  *   y_b += bias_b.
+ * flags = CKKS_MATMUL_MERGED_GIANT evaluates the giant step as
+ *   y_b = acc_{b,0} + (sum_p sigma_p(acc_{b,p}.c0), 0) + ModDown(sum_p sum_j sigma_p(d_j(acc_{b,p}.c1)) key_{p,j}),
+ * i.e. the N2-1 switched accumulators are summed over the extended basis and brought down once.  ModDown is
+ * not exactly linear, so the residues differ from the default (each rotation a complete key switch) while
+ * decrypting to the same values; both orders are defined bit for bit.
  * The library is agnostic of what the slots hold: real packing (real diagonals), complex-pair compression
  * (complex diagonals + conj_key) and the fused QK projection of App. A.2.3 (weights W_Q + i*W_K, no
  * conj_key, Q and K come out in the real and imaginary parts) differ only in the plaintexts handed to
@@ -145,9 +150,11 @@ void ckks_weights_destroy(ckks_weights_t *w);
  * CKKS_STEP_CONJ; d_ct_y [B_out][2][level][N] at the
  * input level and scale(x)*scale(w) -- follow with ckks_rescale.  counters
  * (host, may be NULL) receives the operation counts. */
+#define CKKS_MATMUL_MERGED_GIANT 1u /* flags: one ModDown per output block for the whole giant step */
 int ckks_ctpt_matmul(ckks_params_t *params, const ckks_weights_t *w, const uint64_t *d_ct_x,
                      const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys,
-                     const ckks_gkey_t *conj_key, uint64_t *d_ct_y, ckks_counters_t *counters, void *stream);
+                     const ckks_gkey_t *conj_key, uint32_t flags, uint64_t *d_ct_y, ckks_counters_t *counters,
+                     void *stream);
 
 /* rescale (Sec. 2.2): drops limb level_in-1 and divides by its prime with
  * centred rounding.  d_ct_in [n_ct][2][level_in][N] -> d_ct_out

@@ -406,6 +406,46 @@ void orc_rotate_hoisted(const orc_ctx *c, const u64 *ct_in, int level, const u64
     free(dig);
 }
 
+/* Variant used by the merged giant step: the key switch of one ciphertext up to, but not including,
+ * ModDown.  u_acc [2][level+K][N] += sum_j sigma_g(d_j) (.) key_j  (all limbs, NTT domain) and
+ * c0_acc [level][N] += sigma_g(c0).  The decomposition of c1 is that of orc_rotate_hoisted. */
+void orc_switch_accumulate(const orc_ctx *c, const u64 *ct_in, int level, u64 g, const u64 *key, u64 *u_acc,
+                           u64 *c0_acc) {
+    u64 N = c->N;
+    int K = c->K, L = c->L, W = level + K;
+    int beta = (level + c->alpha - 1) / c->alpha;
+    const u64 *c0 = ct_in, *c1 = ct_in + (u64)level * N;
+    u64 *c1c = (u64 *)malloc(sizeof(u64) * level * N);
+    memcpy(c1c, c1, sizeof(u64) * level * N);
+#pragma omp parallel for schedule(dynamic)
+    for (int i = 0; i < level; i++) orc_intt(c, i, c1c + (u64)i * N);
+    u64 *dig = (u64 *)malloc(sizeof(u64) * beta * W * N);
+    for (int j = 0; j < beta; j++) orc_modup(c, level, j, c1c, dig + (u64)j * W * N);
+#pragma omp parallel for schedule(dynamic)
+    for (int jt = 0; jt < beta * W; jt++) orc_ntt(c, ext_limb(c, level, jt % W), dig + (u64)jt * N);
+    free(c1c);
+#pragma omp parallel for schedule(dynamic)
+    for (int t = 0; t < W; t++) {
+        int gl = ext_limb(c, level, t);
+        u64 mt = c->mod[gl];
+        u64 *perm = (u64 *)malloc(sizeof(u64) * N);
+        for (int j = 0; j < beta; j++) {
+            orc_automorph_ntt(c, g, dig + ((u64)j * W + t) * N, perm);
+            for (int comp = 0; comp < 2; comp++) {
+                const u64 *kk = key + (((u64)j * 2 + comp) * (L + K) + gl) * N;
+                u64 *uu = u_acc + ((u64)comp * W + t) * N;
+                for (u64 x = 0; x < N; x++) uu[x] = addmod(uu[x], mulmod(perm[x], kk[x], mt), mt);
+            }
+        }
+        if (t < level) {
+            orc_automorph_ntt(c, g, c0 + (u64)t * N, perm);
+            for (u64 x = 0; x < N; x++) c0_acc[(u64)t * N + x] = addmod(c0_acc[(u64)t * N + x], perm[x], mt);
+        }
+        free(perm);
+    }
+    free(dig);
+}
+
 /* ------------------------------------------------------------------ */
 /* plaintext handling                                                  */
 /* ------------------------------------------------------------------ */
@@ -442,7 +482,7 @@ void orc_expand_plain(const orc_ctx *c, int level, const i64 *coef, u64 *out) {
 void orc_ctpt_matmul(const orc_ctx *c, int level, int m, int G, int B_out, int N1, int N2,
                      const i64 *diag, const i64 *bias, u64 bias_mul, const u64 *ct_x,
                      const u64 *const *baby_keys, const u64 *const *giant_keys, const u64 *conj_key, u64 *ct_y,
-                     int b_first, int b_count) {
+                     int b_first, int b_count, int merged) {
     u64 N = c->N;
     u64 ctw = (u64)2 * level * N;
     (void)B_out;
@@ -481,14 +521,38 @@ void orc_ctpt_matmul(const orc_ctx *c, int level, int m, int G, int B_out, int N
         u64 *y = ct_y + (u64)b * ctw;
         memcpy(y, acc, sizeof(u64) * ctw);
         u64 *rot = (u64 *)malloc(sizeof(u64) * ctw);
-        for (int p = 1; p < N2; p++) {
-            u64 g = orc_galois_elt(c, (i64)p * N1 * m, 0);
-            const u64 *key = giant_keys[p - 1];
-            orc_rotate_hoisted(c, acc + (u64)p * ctw, level, &g, 1, &key, rot);
+        if (!merged) {
+            for (int p = 1; p < N2; p++) {
+                u64 g = orc_galois_elt(c, (i64)p * N1 * m, 0);
+                const u64 *key = giant_keys[p - 1];
+                orc_rotate_hoisted(c, acc + (u64)p * ctw, level, &g, 1, &key, rot);
+                for (int ci = 0; ci < 2 * level; ci++) {
+                    u64 qi = c->mod[ci % level];
+                    for (u64 k = 0; k < N; k++)
+                        y[(u64)ci * N + k] = addmod(y[(u64)ci * N + k], rot[(u64)ci * N + k], qi);
+                }
+            }
+        } else if (N2 > 1) {
+            /* merged giant step (variant): the N2-1 switched accumulators are summed over the extended basis
+             * and brought down by ONE ModDown per component:
+             *   y_b = acc_{b,0} + (sum_p sigma_p(acc_{b,p}.c0), 0) + ModDown(sum_p sum_j sigma_p(d_j) key_{p,j}). */
+            int Wl = level + c->K;
+            u64 *u_acc = (u64 *)calloc((size_t)2 * Wl * N, sizeof(u64));
+            u64 *c0_acc = (u64 *)calloc((size_t)level * N, sizeof(u64));
+            for (int p = 1; p < N2; p++)
+                orc_switch_accumulate(c, acc + (u64)p * ctw, level, orc_galois_elt(c, (i64)p * N1 * m, 0),
+                                      giant_keys[p - 1], u_acc, c0_acc);
+            orc_moddown(c, level, u_acc, rot);
+            orc_moddown(c, level, u_acc + (u64)Wl * N, rot + (u64)level * N);
             for (int ci = 0; ci < 2 * level; ci++) {
                 u64 qi = c->mod[ci % level];
-                for (u64 k = 0; k < N; k++) y[(u64)ci * N + k] = addmod(y[(u64)ci * N + k], rot[(u64)ci * N + k], qi);
+                for (u64 k = 0; k < N; k++) {
+                    u64 v = addmod(y[(u64)ci * N + k], rot[(u64)ci * N + k], qi);
+                    if (ci < level) v = addmod(v, c0_acc[(u64)ci * N + k], qi);
+                    y[(u64)ci * N + k] = v;
+                }
             }
+            free(c0_acc); free(u_acc);
         }
         /* decomplexification (Sec. 3.2): with complexified inputs x^(2u) + i x^(2u+1) and weights that carry
          * the factor 1/2, the real part is y + conj(y).  Taken once per output block after the giant-step fold,

@@ -44,7 +44,8 @@ _SIGS = {
     "ckks_weights_create": [_vp] + [C.c_uint32] * 6 + [C.POINTER(_vp)],
     "ckks_weights_set_diagonals": [_vp, C.c_uint32, C.c_uint32, _vp, _vp],
     "ckks_weights_set_bias": [_vp, _vp, C.c_uint64, _vp],
-    "ckks_ctpt_matmul": [_vp, _vp, _vp, C.POINTER(_vp), C.POINTER(_vp), _vp, _vp, C.POINTER(Counters), _vp],
+    "ckks_ctpt_matmul": [_vp, _vp, _vp, C.POINTER(_vp), C.POINTER(_vp), _vp, C.c_uint32, _vp, C.POINTER(Counters),
+                         _vp],
     "ckks_rescale": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
 }
 for _n, _a in _SIGS.items():
@@ -200,7 +201,10 @@ def ckks_weights_set_bias(w, d_bias_coeffs, bias_mul):
     _check(lib.ckks_weights_set_bias(w.h, _dev(d_bias_coeffs), int(bias_mul), _stream()))
 
 
-def ckks_ctpt_matmul(P, w, d_ct_x, baby_keys, giant_keys, d_ct_y=None, conj_key=None):
+MATMUL_MERGED_GIANT = 1
+
+
+def ckks_ctpt_matmul(P, w, d_ct_x, baby_keys, giant_keys, d_ct_y=None, conj_key=None, flags=0):
     if d_ct_x.numel() != w.G * 2 * w.level * P.N:
         raise ValueError("input must be [G][2][level][N]")
     if len(baby_keys) != w.N1 - 1 or len(giant_keys) != w.N2 - 1:
@@ -211,7 +215,8 @@ def ckks_ctpt_matmul(P, w, d_ct_x, baby_keys, giant_keys, d_ct_y=None, conj_key=
         raise ValueError("output must be [B_out][2][level][N]")
     cnt = Counters()
     _check(lib.ckks_ctpt_matmul(P.h, w.h, _dev(d_ct_x), _keyarr(baby_keys), _keyarr(giant_keys),
-                                conj_key.h if conj_key is not None else None, _dev(d_ct_y), C.byref(cnt), _stream()))
+                                conj_key.h if conj_key is not None else None, flags, _dev(d_ct_y), C.byref(cnt),
+                                _stream()))
     return d_ct_y, cnt
 
 

@@ -127,5 +127,8 @@ size_t digits_words(const ckks_params *p, u32 level);
 size_t switch_scratch_words(const ckks_params *p, u32 level, u32 n_items);
 int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_digits, u64 *d_tmp, hipStream_t stream);
 int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream);
+int switch_accumulate(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_u, bool accumulate,
+                      hipStream_t stream);
+int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64 *d_w, hipStream_t stream);
 
 }  // namespace ckks

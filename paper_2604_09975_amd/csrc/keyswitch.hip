@@ -92,9 +92,13 @@ struct ItemPack {
 // u[r][comp][t][k] = sum_j digits_r[j][t][sigma_g(k)] * key[j][comp][limb(t)][k] for the items r of one
 // group (same key, same Galois element): each key residue is loaded once and used for all of them.
 // grid: x = coefficients, y = limb t, z = group.
+// accumulate: add to what u holds (merged giant step: sums over the giant index stay in the extended basis).
+// fold_c0: also add sigma_g(c0) of each item into component 0 of its dst (the part of a rotation that needs
+// no key), so that nothing but ModDown(u) is left to add later.
 __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack, u64 *__restrict__ u,
                                                                    const ModConst *__restrict__ mods, u32 level,
-                                                                   u32 K, u32 L, u32 beta, u32 logN) {
+                                                                   u32 K, u32 L, u32 beta, u32 logN, u32 accumulate,
+                                                                   u32 fold_c0) {
     const u32 N = 1u << logN;
     const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
     const u32 t = blockIdx.y;
@@ -125,8 +129,20 @@ __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack
 #pragma unroll
     for (u32 r = 0; r < KEY_GROUP; ++r) {
         if (r < cnt) {
-            u[(((size_t)(first + r) * 2 + 0) * Wl + t) * N + k] = redc_wide(a0[r], m);
-            u[(((size_t)(first + r) * 2 + 1) * Wl + t) * N + k] = redc_wide(a1[r], m);
+            u64 *u0 = u + (((size_t)(first + r) * 2 + 0) * Wl + t) * N + k;
+            u64 *u1 = u + (((size_t)(first + r) * 2 + 1) * Wl + t) * N + k;
+            u64 v0 = redc_wide(a0[r], m), v1 = redc_wide(a1[r], m);
+            if (accumulate) {
+                v0 = add_mod(v0, *u0, m.q);
+                v1 = add_mod(v1, *u1, m.q);
+            }
+            *u0 = v0;
+            *u1 = v1;
+            if (fold_c0 && t < level) {
+                const SwitchItem &it = pack.it[first + r];
+                u64 *d = it.dst + (size_t)t * N + k;
+                *d = add_mod(*d, it.c0[(size_t)t * N + kp], m.q);
+            }
         }
     }
 }
@@ -171,7 +187,7 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(ItemPack pack
     const u64 uq = u[(((size_t)r * 2 + comp) * Wl + i) * N + k];
     const u64 wq = w[(((size_t)r * 2 + comp) * level + i) * N + k];
     u64 v = mont_mul(sub_mod(uq, wq, m.q), pinv[i], m);
-    if (comp == 0) v = add_mod(v, it.c0[(size_t)i * N + galois_index(k, it.galois_elt, logN)], m.q);
+    if (comp == 0 && it.c0) v = add_mod(v, it.c0[(size_t)i * N + galois_index(k, it.galois_elt, logN)], m.q);
     u64 *dst = it.dst + ((size_t)comp * level + i) * N + k;
     if (it.accumulate) v = add_mod(v, *dst, m.q);
     *dst = v;
@@ -350,16 +366,7 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
     return CKKS_OK;
 }
 
-// n <= ROT_BATCH key switches from ready digits.  d_work: switch_scratch_words(level, n).
-int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream) {
-    if (n == 0) return CKKS_OK;
-    if (n > ROT_BATCH) {
-        set_error("switch_batch: %u items exceed one batch", n);
-        return CKKS_E_INVAL;
-    }
-    const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
-    const u32 beta = (level + p->alpha - 1) / p->alpha;
-    ItemPack pack;
+static u32 build_pack(const SwitchItem *items, u32 n, ItemPack &pack) {
     for (u32 r = 0; r < ROT_BATCH; ++r) pack.it[r] = items[r < n ? r : 0];
     u32 n_groups = 0;
     for (u32 r = 0; r < n;) {
@@ -373,6 +380,70 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
         r += c;
     }
     for (u32 g = n_groups; g < ROT_BATCH; ++g) pack.grp_first[g] = pack.grp_count[g] = 0;
+    return n_groups;
+}
+
+// Merged giant step, part 1: d_u[r] (+)= key inner product of item r over all level+K limbs (NTT domain),
+// dst_r.c0 += sigma_g(c0_r).  d_u [n][2][level+K][N].
+int switch_accumulate(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_u, bool accumulate,
+                      hipStream_t stream) {
+    if (n == 0) return CKKS_OK;
+    if (n > ROT_BATCH) {
+        set_error("switch_accumulate: %u items exceed one batch", n);
+        return CKKS_E_INVAL;
+    }
+    const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
+    const u32 beta = (level + p->alpha - 1) / p->alpha;
+    ItemPack pack;
+    const u32 n_groups = build_pack(items, n, pack);
+    hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n_groups), dim3(KS_THREADS), 0, stream, pack,
+                       d_u, p->d_mod, level, K, L, beta, p->logN, accumulate ? 1u : 0u, 1u);
+    CKKS_LAUNCH_CHECK("inner_product_kernel");
+    return CKKS_OK;
+}
+
+// Merged giant step, part 2: dst_r += ModDown(d_u[r]) for n <= ROT_BATCH ciphertexts; d_u is consumed.
+// d_w: n*2*level*N words of scratch.
+int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64 *d_w, hipStream_t stream) {
+    if (n == 0) return CKKS_OK;
+    const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
+    ItemPack pack;
+    for (u32 r = 0; r < ROT_BATCH; ++r) {
+        SwitchItem &it = pack.it[r];
+        it.digits = nullptr;
+        it.c0 = nullptr;                       // already folded in by switch_accumulate
+        it.key = nullptr;
+        it.dst = dst[r < n ? r : 0];
+        it.galois_elt = 1;
+        it.accumulate = 1;
+    }
+    LimbIds ids;
+    for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
+    int rc = launch_ntt(p, d_u, ids, Wl, n * 2 * Wl, true, stream, 3, true);
+    if (rc) return rc;
+    hipLaunchKernelGGL(moddown_conv_kernel, dim3(N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK),
+                       dim3(KS_THREADS), 0, stream, d_u, d_w, p->d_mod, p->d_dn_mat, level, K, L, N, Wl, level);
+    CKKS_LAUNCH_CHECK("moddown_conv_kernel");
+    for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
+    rc = launch_ntt(p, d_w, ids, level, n * 2 * level, false, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(moddown_final_kernel, dim3(N / KS_THREADS, level, n * 2), dim3(KS_THREADS), 0, stream, pack,
+                       d_u, d_w, p->d_mod, p->d_pinv, level, K, p->logN);
+    CKKS_LAUNCH_CHECK("moddown_final_kernel");
+    return CKKS_OK;
+}
+
+// n <= ROT_BATCH key switches from ready digits.  d_work: switch_scratch_words(level, n).
+int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream) {
+    if (n == 0) return CKKS_OK;
+    if (n > ROT_BATCH) {
+        set_error("switch_batch: %u items exceed one batch", n);
+        return CKKS_E_INVAL;
+    }
+    const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
+    const u32 beta = (level + p->alpha - 1) / p->alpha;
+    ItemPack pack;
+    const u32 n_groups = build_pack(items, n, pack);
     LimbIds ids;
     if (fast_ring(p) && beta <= MAX_BETA) {
         // inner product fused into the transforms on both sides of the base conversion
@@ -403,7 +474,7 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
     u64 *u = d_work;
     u64 *w = d_work + (size_t)n * 2 * Wl * N;
     hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n_groups), dim3(KS_THREADS), 0, stream, pack, u,
-                       p->d_mod, level, K, L, beta, p->logN);
+                       p->d_mod, level, K, L, beta, p->logN, 0u, 0u);
     CKKS_LAUNCH_CHECK("inner_product_kernel");
     for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
     int rc = launch_ntt(p, u, ids, Wl, n * 2 * Wl, true, stream, 3, true);

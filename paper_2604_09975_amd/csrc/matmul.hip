@@ -493,7 +493,8 @@ void ckks_weights_destroy(ckks_weights_t *w) {
 
 int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *d_ct_x,
                      const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys,
-                     const ckks_gkey_t *conj_key, uint64_t *d_ct_y, ckks_counters_t *counters, void *stream_) {
+                     const ckks_gkey_t *conj_key, uint32_t flags, uint64_t *d_ct_y, ckks_counters_t *counters,
+                     void *stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (!P || !w || !d_ct_x || !d_ct_y) {
         set_error("ckks_ctpt_matmul: null argument");
@@ -544,7 +545,9 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     const size_t dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
     const size_t ks_w = batch * (dig_w + tmp_w) + switch_scratch_words(P, level, ROT_BATCH);
     const size_t bank_w = (size_t)GQ * ctw, acc_w = (size_t)BP * ctw;
-    int rc = P->ensure_scratch((ks_w + bank_w + acc_w) * sizeof(u64), stream);
+    const bool merged = (flags & CKKS_MATMUL_MERGED_GIANT) && N2 > 1;
+    const size_t u_w = merged ? (size_t)B * 2 * (level + P->K) * N : 0;   // extended-basis sums of the giant step
+    int rc = P->ensure_scratch((ks_w + bank_w + acc_w + u_w) * sizeof(u64), stream);
     if (rc) return rc;
     u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + batch * tmp_w;
     u64 *d_bank = (u64 *)P->d_scratch + ks_w, *d_acc = d_bank + bank_w;
@@ -642,6 +645,8 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     for (u32 b = 0; b < B; ++b)
         CKKS_HIP(hipMemcpyAsync(d_ct_y + (size_t)b * ctw, d_acc + (size_t)b * N2 * ctw, ctw * sizeof(u64),
                                 hipMemcpyDeviceToDevice, stream));
+    u64 *d_u = d_acc + acc_w;
+    bool u_started = false;
     for (u32 p = 1; p < N2; ++p) {
         for (u32 b0 = 0; b0 < B; b0 += batch) {
             const u32 nb = std::min(batch, B - b0);
@@ -668,7 +673,21 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                 items[r].galois_elt = giant_g[p];
                 items[r].accumulate = 1;
             }
-            rc = switch_batch(P, level, items, nb, d_work, stream);
+            if (merged)   // keep the switched accumulators in the extended basis; one ModDown per block follows
+                rc = switch_accumulate(P, level, items, nb, d_u + (size_t)b0 * 2 * (level + P->K) * N, u_started,
+                                       stream);
+            else
+                rc = switch_batch(P, level, items, nb, d_work, stream);
+            if (rc) return rc;
+        }
+        if (merged && giant_g[p] != 1) u_started = true;
+    }
+    if (merged && u_started) {
+        for (u32 b0 = 0; b0 < B; b0 += batch) {
+            const u32 nb = std::min(batch, B - b0);
+            u64 *dsts[ROT_BATCH];
+            for (u32 r = 0; r < nb; ++r) dsts[r] = d_ct_y + (size_t)(b0 + r) * ctw;
+            rc = moddown_add(P, level, d_u + (size_t)b0 * 2 * (level + P->K) * N, dsts, nb, d_work, stream);
             if (rc) return rc;
         }
     }

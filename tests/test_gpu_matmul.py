@@ -27,7 +27,8 @@ def make_real(m):
     return m
 
 
-def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_blocks=None, real=False):
+def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_blocks=None, real=False,
+             merged=False):
     """Runs the projection on both sides from identical integer inputs; returns everything."""
     B = _B()
     N, n = O.N, O.n
@@ -54,7 +55,8 @@ def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_
         B.ckks_weights_set_diagonals(w, half, to_dev(flat[half:]))
     if bias_c is not None:
         B.ckks_weights_set_bias(w, to_dev(bias_c), int(sw))
-    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h)
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h,
+                                    flags=B.MATMUL_MERGED_GIANT if merged else 0)
     y_res = B.ckks_rescale(P, y_dev, level, B_out)
     torch.cuda.synchronize()
     got, got_res = to_host(y_dev), to_host(y_res)
@@ -62,7 +64,7 @@ def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_
     blocks = list(range(B_out)) if oracle_blocks is None else oracle_blocks
     for b in blocks:
         want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(sw), ct_x, baby_np, giant_np,
-                             b_first=b, b_count=1)
+                             b_first=b, b_count=1, merged=merged)
         assert (got[b] == want[b]).all(), f"block {b}"
         assert (got_res[b] == O.rescale(want[b:b + 1], level)[0]).all(), f"rescaled block {b}"
     assert cnt.key_switches == sum(1 for k in baby_np if k is not None) * G + sum(1 for k in giant_np if k is not None) * B_out
@@ -122,6 +124,26 @@ def test_one_unsymmetric_diagonal_turns_the_palindrome_path_off():
     Wm = r.uniform(-0.1, 0.1, (64, 64))
     Y, ref, cnt, _ = run_case(O, P, X, Wm, None, 16, 64, 16, 30, 3, 25, real=False)
     assert np.abs(Y - ref).max() <= 1e-3
+
+
+@pytest.mark.parametrize("ring,N1", [("toy", 16), ("toy", 4), ("small", 2), ("small", 16)])
+def test_merged_giant_step(ring, N1):
+    """CKKS_MATMUL_MERGED_GIANT: one ModDown per output block for the whole giant step, bit for bit against the
+    oracle's merged variant (N1 = C: no giant step, the flag changes nothing)."""
+    if ring == "toy":
+        O, P = make_pair(W.TOY_RING)
+        m, C, hw = 16, 64, 64
+    else:
+        O = helpers.small_oracle(10, L=4, K=2, dnum=2, qbits=40, pbits=45)
+        _, P = make_pair(O)
+        m, C, hw = 4, 16, 16
+    r = W.rng(61)
+    X = r.uniform(-1, 1, (m, 2 * C + 3))
+    Wm = r.uniform(-0.1, 0.1, (2 * C + 3, C + 5))
+    bias = r.uniform(-0.5, 0.5, C + 5)
+    Y, ref, cnt, _ = run_case(O, P, X, Wm, bias, m, C, N1, 30, O.L, 63, hw=hw, merged=True, real=(ring == "toy"))
+    assert np.abs(Y - ref).max() <= 1e-3
+    assert cnt.key_switches == 3 * (N1 - 1) + 2 * (C // N1 - 1)
 
 
 def test_more_blocks_than_one_switch_batch():

@@ -17,7 +17,8 @@ from paper_2604_09975_amd import workload as W
 pytestmark = pytest.mark.gpu
 
 
-def test_bert_qkv_sampled_block_bit_exact():
+@pytest.mark.parametrize("merged", [False, True], ids=["default", "merged_giant"])
+def test_bert_qkv_sampled_block_bit_exact(merged):
     from paper_2604_09975_amd import binding as B
     t0 = time.time()
     spec = W.BERT_QKV
@@ -46,7 +47,8 @@ def test_bert_qkv_sampled_block_bit_exact():
             diag_block = d
     B.ckks_weights_set_bias(w, to_dev(bias_c), int(scale))
     print(f"[full] weights ready {time.time() - t0:.0f}s", flush=True)
-    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h)
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h,
+                                    flags=B.MATMUL_MERGED_GIANT if merged else 0)
     y_res = B.ckks_rescale(P, y_dev, level, B_out)
     torch.cuda.synchronize()
     got, got_res = to_host(y_dev), to_host(y_res)
@@ -56,7 +58,7 @@ def test_bert_qkv_sampled_block_bit_exact():
     diag = np.zeros((B_out, N2, G, N1, N), dtype=np.int64)
     diag[block] = diag_block
     want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(scale), ct_x, baby_np, giant_np,
-                         b_first=block, b_count=1)
+                         b_first=block, b_count=1, merged=merged)
     print(f"[full] oracle block {block} done {time.time() - t0:.0f}s", flush=True)
     assert (got[block] == want[block]).all()
     assert (got_res[block] == O.rescale(want[block:block + 1], level)[0]).all()

@@ -72,7 +72,7 @@ def test_null_arguments_are_errors_not_crashes():
     assert B.lib.ckks_ntt(None, None, None, 0, 0, None) == -1
     assert B.lib.ckks_rescale(None, None, 2, 1, None, None) == -1
     assert B.lib.ckks_rotate_hoisted(None, None, 1, None, 0, None, None, None) == -1
-    assert B.lib.ckks_ctpt_matmul(None, None, None, None, None, None, None, None, None) == -1
+    assert B.lib.ckks_ctpt_matmul(None, None, None, None, None, None, 0, None, None, None) == -1
     assert B.lib.ckks_weights_create(None, 1, 1, 1, 1, 1, 1, C.byref(h)) == -1
     assert B.lib.ckks_galois_key_load(None, 3, None, None, C.byref(h)) == -1
     B.lib.ckks_params_destroy(None)

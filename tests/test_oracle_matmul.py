@@ -22,7 +22,7 @@ def int_negacyclic(a, b, N):
     return out
 
 
-def run_matmul(O, cl, X, Wm, bias, m, C, N1, sx, sw, level, blocks=None):
+def run_matmul(O, cl, X, Wm, bias, m, C, N1, sx, sw, level, blocks=None, merged=False):
     N, n = O.N, O.n
     d_in, d_out = Wm.shape
     G, B_out, N2 = -(-d_in // C), -(-d_out // C), C // N1
@@ -35,12 +35,14 @@ def run_matmul(O, cl, X, Wm, bias, m, C, N1, sx, sw, level, blocks=None):
         bias_c = np.stack([E.encode(E.bias_slots(bias, m, n, C, b) + 0j, sx, N) for b in range(B_out)])
     baby = [cl.galois_key(O.galois_elt(q * m)) for q in range(1, N1)]
     giant = [cl.galois_key(O.galois_elt(p * N1 * m)) for p in range(1, N2)]
-    y = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(sw), ct_x, baby, giant)
+    y = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(sw), ct_x, baby, giant, merged=merged)
     return dict(ct_x=ct_x, mx=mx, diag=diag, bias_c=bias_c, y=y, G=G, B_out=B_out, N2=N2)
 
 
-def test_tiny_ring_against_integer_polynomials():
-    """N = 32, m = 2, C = N_seg = 8: every step redone over Z[X]/(X^N+1) with Python ints, no RNS."""
+@pytest.mark.parametrize("merged", [False, True])
+def test_tiny_ring_against_integer_polynomials(merged):
+    """N = 32, m = 2, C = N_seg = 8: every step redone over Z[X]/(X^N+1) with Python ints, no RNS.
+    merged: the giant-step variant with one ModDown per output block (same integers up to the switch noise)."""
     O = helpers.small_oracle(5, L=3, K=1, dnum=3, qbits=30, pbits=33)
     N, n, m, C, N1 = O.N, O.n, 2, 8, 4
     r = np.random.default_rng(77)
@@ -50,7 +52,7 @@ def test_tiny_ring_against_integer_polynomials():
     sx, sw = 2.0**25, 2.0**20
     hw = 8
     cl = helpers.Client(O, 5, hamming_weight=hw)
-    R = run_matmul(O, cl, X, Wm, bias, m, C, N1, sx, sw, 3)
+    R = run_matmul(O, cl, X, Wm, bias, m, C, N1, sx, sw, 3, merged=merged)
     G, B_out, N2 = R["G"], R["B_out"], R["N2"]
     assert (G, B_out, N2) == (2, 2, 2)
     Q = O.q[0] * O.q[1] * O.q[2]
@@ -97,6 +99,28 @@ def test_toy_config_matches_fp64_matmul(toy_oracle):
     # the replicated copy in segments 64..127 holds the same columns
     Y2 = np.stack([slots[0, (64 + c) * 16:(65 + c) * 16].real for c in range(64)], axis=1)
     assert np.abs(Y2 - X @ Wm).max() <= 1e-3
+
+
+def test_merged_giant_step_differs_in_bits_but_not_in_value():
+    O = helpers.small_oracle(8, L=3, K=1, dnum=3, qbits=40, pbits=42)
+    m, C, N1 = 4, 16, 2
+    r = np.random.default_rng(10)
+    X, Wm = r.uniform(-1, 1, (m, 40)), r.uniform(-0.5, 0.5, (40, 20))
+    outs = []
+    for merged in (False, True):
+        cl = helpers.Client(O, 20, hamming_weight=16)
+        R = run_matmul(O, cl, X, Wm, None, m, C, N1, 2.0**30, 2.0**30, 3, merged=merged)
+        y = O.rescale(R["y"], 3)
+        slots = np.stack([cl.decrypt_slots(y[b], 2, 2.0**60 / O.q[2], nlimbs=2) for b in range(R["B_out"])])
+        assert np.abs(E.unpack_columns(slots.real, m, C, 20) - X @ Wm).max() < 1e-3
+        outs.append(R["y"])
+    assert not (outs[0] == outs[1]).all()           # ModDown is not linear: a different, equally valid ciphertext
+    O1 = helpers.small_oracle(8, L=3, K=1, dnum=3, qbits=40, pbits=42)
+    cl = helpers.Client(O1, 20, hamming_weight=16)
+    R1 = run_matmul(O1, cl, X, Wm, None, m, C, 16, 2.0**30, 2.0**30, 3, merged=True)      # N2 = 1: nothing to merge
+    cl = helpers.Client(O1, 20, hamming_weight=16)
+    R2 = run_matmul(O1, cl, X, Wm, None, m, C, 16, 2.0**30, 2.0**30, 3, merged=False)
+    assert (R1["y"] == R2["y"]).all()
 
 
 @pytest.mark.parametrize("N1", [1, 4, 16])
