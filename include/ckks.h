@@ -98,6 +98,17 @@ int ckks_galois_key_load(const ckks_params_t *params, uint64_t galois_elt, const
                          void *stream, ckks_gkey_t **out);
 void ckks_galois_key_destroy(ckks_gkey_t *key);
 
+/* Relinearisation key (Sec. 2.1 "relinearization keys"): same layout as a Galois key, with
+ * b_j = -a_j*s + e_j + P*T_j*s^2. */
+int ckks_relin_key_load(const ckks_params_t *params, const uint64_t *d_key, void *stream, ckks_gkey_t **out);
+
+/* ctmul of Table 1: slotwise product of two ciphertexts at `level`, relinearised with the same hybrid key
+ * switch as a rotation: (t0,t1,t2) = (a0*b0, a0*b1+a1*b0, a1*b1), out = (t0,t1) + ModDown(<digits(t2), key>).
+ * d_ct_a, d_ct_b, d_ct_out: [2][level][N] (out may not alias the inputs).  scale(out) = scale(a)*scale(b):
+ * follow with ckks_rescale.  CKKS_E_NOKEY without a key. */
+int ckks_ctmul(ckks_params_t *params, const uint64_t *d_ct_a, const uint64_t *d_ct_b, uint32_t level,
+               const ckks_gkey_t *relin_key, uint64_t *d_ct_out, void *stream);
+
 /* rot / conj of Table 1 for many steps of ONE ciphertext (the rotation banks
  * of Sec. 3.2/3.3 share their input): INTT(c1), digit decomposition and ModUp
  * are done once, then per step: automorphism, inner product with the key,
@@ -184,6 +195,10 @@ void ckks_client_secret_destroy(ckks_secret_t *secret);
  * d_key out [dnum][2][L+K][N] canonical, NTT domain (the layout ckks_galois_key_load takes). */
 int ckks_client_galois_keygen(ckks_params_t *params, const ckks_secret_t *secret, uint64_t galois_elt,
                               const uint64_t *d_a, const int64_t *d_e, uint64_t *d_key, void *stream);
+
+/* Relinearisation key: as above with s^2 in place of sigma_g(s). */
+int ckks_client_relin_keygen(ckks_params_t *params, const ckks_secret_t *secret, const uint64_t *d_a,
+                             const int64_t *d_e, uint64_t *d_key, void *stream);
 
 /* Symmetric encryption at `level`: c1 = a, c0 = -a*s + e + m.  d_m int64 [N] encoded plaintext
  * coefficients, d_a [level][N] uniform residues (NTT domain), d_e int64 [N]; d_ct out [2][level][N]. */

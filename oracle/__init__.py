@@ -57,6 +57,8 @@ def _lib():
                                     _u64p, C.c_int, C.c_int, C.c_int]
     lib.orc_rescale.argtypes = [C.c_void_p, _u64p, C.c_int, C.c_int, _u64p]
     lib.orc_galois_keygen.argtypes = [C.c_void_p, _i8p, C.c_uint64, _u64p, _i64p, _u64p]
+    lib.orc_relin_keygen.argtypes = [C.c_void_p, _i8p, _u64p, _i64p, _u64p]
+    lib.orc_ctmul.argtypes = [C.c_void_p, _u64p, _u64p, C.c_int, _u64p, _u64p]
     lib.orc_encrypt.argtypes = [C.c_void_p, C.c_int, _i64p, _i8p, _u64p, _i64p, _u64p]
     lib.orc_decrypt.argtypes = [C.c_void_p, _u64p, C.c_int, _i8p, C.c_int, _u64p]
     return lib
@@ -262,6 +264,25 @@ class Oracle:
         key = np.zeros((self.dnum, 2, W, self.N), dtype=np.uint64)
         LIB.orc_galois_keygen(self._h, sp, g, ap, ep, key.ctypes.data_as(_u64p))
         return key
+
+    def relin_keygen(self, s, a, e):
+        s_, sp = _i8(s)
+        a_, ap = _u64(a)
+        e_, ep = _i64(e)
+        W = self.L + self.K
+        assert a_.shape == (self.dnum, W, self.N) and e_.shape == (self.dnum, self.N)
+        key = np.zeros((self.dnum, 2, W, self.N), dtype=np.uint64)
+        LIB.orc_relin_keygen(self._h, sp, ap, ep, key.ctypes.data_as(_u64p))
+        return key
+
+    def ctmul(self, ct_a, ct_b, level, relin_key):
+        a_, ap = _u64(ct_a)
+        b_, bp = _u64(ct_b)
+        k_, kp = _u64(relin_key)
+        assert a_.shape == b_.shape == (2, level, self.N)
+        out = np.zeros((2, level, self.N), dtype=np.uint64)
+        LIB.orc_ctmul(self._h, ap, bp, level, kp, out.ctypes.data_as(_u64p))
+        return out
 
     def encrypt(self, level, m, s, a, e):
         m_, mp = _i64(m)

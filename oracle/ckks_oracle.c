@@ -630,24 +630,21 @@ static u64 *secret_ntt(const orc_ctx *c, const int8_t *s) {
     return sn;
 }
 
-/* Galois key for element g (reading: hybrid key switching, dnum digits):
- *   b_j = -a_j*s + e_j + [P*T_j] * sigma_g(s),   key[j] = (b_j, a_j)
- * over all L+K limbs, NTT domain; [P*T_j] is P mod q_i on the limbs of digit j
- * and 0 on every other limb.  a [dnum][L+K][N] are NTT-domain residues given
- * by the caller; e [dnum][N] are small signed coefficients. */
-void orc_galois_keygen(const orc_ctx *c, const int8_t *s, u64 g, const u64 *a, const i64 *e, u64 *key) {
+/* Evaluation key that switches from the secret `target` to s (reading: hybrid key switching, dnum digits):
+ *   b_j = -a_j*s + e_j + [P*T_j] * target,   key[j] = (b_j, a_j)
+ * over all L+K limbs, NTT domain; [P*T_j] is P mod q_i on the limbs of digit j and 0 on every other limb.
+ * a [dnum][L+K][N] are NTT-domain residues given by the caller; e [dnum][N] are small signed coefficients;
+ * tg [L+K][N] is NTT(target). */
+static void keygen_for_target(const orc_ctx *c, const u64 *sn, const u64 *tg, const u64 *a, const i64 *e, u64 *key) {
     u64 N = c->N;
     int L = c->L, K = c->K, W = L + K;
-    u64 *sn = secret_ntt(c, s);
 #pragma omp parallel for schedule(dynamic)
     for (int jt = 0; jt < c->dnum * W; jt++) {
         int j = jt / W, t = jt % W;
         u64 mt = c->mod[t];
         u64 *en = (u64 *)malloc(sizeof(u64) * N);
-        u64 *sg = (u64 *)malloc(sizeof(u64) * N);
         for (u64 x = 0; x < N; x++) en[x] = reduce_signed(e[(u64)j * N + x], mt);
         orc_ntt(c, t, en);
-        orc_automorph_ntt(c, g, sn + (u64)t * N, sg);
         u64 f = 0;
         if (t < L && t / c->alpha == j) {
             f = 1;
@@ -659,13 +656,69 @@ void orc_galois_keygen(const orc_ctx *c, const int8_t *s, u64 g, const u64 *a, c
         for (u64 x = 0; x < N; x++) {
             u64 as = mulmod(aj[x], sn[(u64)t * N + x], mt);
             u64 v = submod(en[x], as, mt);
-            v = addmod(v, mulmod(f, sg[x], mt), mt);
+            v = addmod(v, mulmod(f, tg[(u64)t * N + x], mt), mt);
             kb[x] = v;
             ka[x] = aj[x];
         }
-        free(sg); free(en);
+        free(en);
     }
-    free(sn);
+}
+
+/* Galois key for element g: target = sigma_g(s). */
+void orc_galois_keygen(const orc_ctx *c, const int8_t *s, u64 g, const u64 *a, const i64 *e, u64 *key) {
+    u64 N = c->N;
+    int W = c->L + c->K;
+    u64 *sn = secret_ntt(c, s);
+    u64 *tg = (u64 *)malloc(sizeof(u64) * W * N);
+    for (int t = 0; t < W; t++) orc_automorph_ntt(c, g, sn + (u64)t * N, tg + (u64)t * N);
+    keygen_for_target(c, sn, tg, a, e, key);
+    free(tg); free(sn);
+}
+
+/* Relinearisation key: target = s^2 (the degree-2 term of a ciphertext product, Table 1 ctmul). */
+void orc_relin_keygen(const orc_ctx *c, const int8_t *s, const u64 *a, const i64 *e, u64 *key) {
+    u64 N = c->N;
+    int W = c->L + c->K;
+    u64 *sn = secret_ntt(c, s);
+    u64 *tg = (u64 *)malloc(sizeof(u64) * W * N);
+    for (int t = 0; t < W; t++)
+        for (u64 x = 0; x < N; x++) tg[(u64)t * N + x] = mulmod(sn[(u64)t * N + x], sn[(u64)t * N + x], c->mod[t]);
+    keygen_for_target(c, sn, tg, a, e, key);
+    free(tg); free(sn);
+}
+
+/* ctmul of Table 1: slotwise product of two ciphertexts at `level`, relinearised.
+ *   (t0, t1, t2) = (a0*b0, a0*b1 + a1*b0, a1*b1)          pointwise in the NTT domain
+ *   (v0, v1) = ModDown( sum_j d_j(t2) (.) key_j )           the same decomposition / ModDown as a rotation
+ *   out = (t0 + v0, t1 + v1).                               scale(out) = scale(a)*scale(b): rescale next. */
+void orc_ctmul(const orc_ctx *c, const u64 *ct_a, const u64 *ct_b, int level, const u64 *relin_key, u64 *out) {
+    u64 N = c->N;
+    int Wl = level + c->K;
+    u64 *tmp = (u64 *)malloc(sizeof(u64) * 2 * level * N);     /* (t0, t2) laid out like a ciphertext */
+    u64 *t1 = (u64 *)malloc(sizeof(u64) * level * N);
+    for (int i = 0; i < level; i++) {
+        u64 q = c->mod[i];
+        const u64 *a0 = ct_a + (u64)i * N, *a1 = ct_a + ((u64)level + i) * N;
+        const u64 *b0 = ct_b + (u64)i * N, *b1 = ct_b + ((u64)level + i) * N;
+        for (u64 x = 0; x < N; x++) {
+            tmp[(u64)i * N + x] = mulmod(a0[x], b0[x], q);
+            tmp[((u64)level + i) * N + x] = mulmod(a1[x], b1[x], q);
+            t1[(u64)i * N + x] = addmod(mulmod(a0[x], b1[x], q), mulmod(a1[x], b0[x], q), q);
+        }
+    }
+    u64 *u_acc = (u64 *)calloc((size_t)2 * Wl * N, sizeof(u64));
+    u64 *c0_acc = (u64 *)calloc((size_t)level * N, sizeof(u64));
+    orc_switch_accumulate(c, tmp, level, 1, relin_key, u_acc, c0_acc);       /* g = 1: no automorphism */
+    orc_moddown(c, level, u_acc, out);
+    orc_moddown(c, level, u_acc + (u64)Wl * N, out + (u64)level * N);
+    for (int i = 0; i < level; i++) {
+        u64 q = c->mod[i];
+        for (u64 x = 0; x < N; x++) {
+            out[(u64)i * N + x] = addmod(out[(u64)i * N + x], c0_acc[(u64)i * N + x], q);
+            out[((u64)level + i) * N + x] = addmod(out[((u64)level + i) * N + x], t1[(u64)i * N + x], q);
+        }
+    }
+    free(c0_acc); free(u_acc); free(t1); free(tmp);
 }
 
 /* Symmetric encryption at `level`: c1 = a (NTT-domain residues, [level][N]),

@@ -47,6 +47,8 @@ _SIGS = {
     "ckks_ctpt_matmul": [_vp, _vp, _vp, C.POINTER(_vp), C.POINTER(_vp), _vp, C.c_uint32, _vp, C.POINTER(Counters),
                          _vp],
     "ckks_rescale": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
+    "ckks_relin_key_load": [_vp, _vp, _vp, C.POINTER(_vp)],
+    "ckks_ctmul": [_vp, _vp, _vp, C.c_uint32, _vp, _vp, _vp],
 }
 for _n, _a in _SIGS.items():
     getattr(lib, _n).argtypes = _a
@@ -159,6 +161,26 @@ def ckks_galois_key_load(P, galois_elt, d_key):
     return k
 
 
+def ckks_relin_key_load(P, d_key):
+    if d_key.numel() != P.dnum * 2 * (P.L + P.K) * P.N:
+        raise ValueError("key tensor must be [dnum][2][L+K][N]")
+    h = _vp()
+    _check(lib.ckks_relin_key_load(P.h, _dev(d_key), _stream(), C.byref(h)))
+    k = GaloisKey(h)
+    k.galois_elt = 1
+    return k
+
+
+def ckks_ctmul(P, d_ct_a, d_ct_b, level, relin_key, d_ct_out=None):
+    if d_ct_a.numel() != 2 * level * P.N or d_ct_b.numel() != 2 * level * P.N:
+        raise ValueError("ciphertexts must be [2][level][N]")
+    if d_ct_out is None:
+        d_ct_out = torch.empty((2, level, P.N), dtype=torch.int64, device=d_ct_a.device)
+    _check(lib.ckks_ctmul(P.h, _dev(d_ct_a), _dev(d_ct_b), level, relin_key.h if relin_key is not None else None,
+                          _dev(d_ct_out), _stream()))
+    return d_ct_out
+
+
 def _keyarr(keys):
     arr = (_vp * max(len(keys), 1))()
     for i, k in enumerate(keys):
@@ -255,6 +277,7 @@ _i8p = C.POINTER(C.c_int8)
 for _n, _a in {
     "ckks_client_secret_load": [_vp, _i8p, _vp, C.POINTER(_vp)],
     "ckks_client_galois_keygen": [_vp, _vp, C.c_uint64, _vp, _vp, _vp, _vp],
+    "ckks_client_relin_keygen": [_vp, _vp, _vp, _vp, _vp, _vp],
     "ckks_client_encrypt": [_vp, _vp, C.c_uint32, _vp, _vp, _vp, _vp, _vp],
     "ckks_client_decrypt": [_vp, _vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
 }.items():
@@ -282,6 +305,16 @@ def ckks_client_galois_keygen(P, S, galois_elt, d_a, d_e, d_key=None):
     if d_key is None:
         d_key = torch.empty((P.dnum, 2, W, P.N), dtype=torch.int64, device=d_a.device)
     _check(lib.ckks_client_galois_keygen(P.h, S.h, galois_elt, _dev(d_a), _dev(d_e), _dev(d_key), _stream()))
+    return d_key
+
+
+def ckks_client_relin_keygen(P, S, d_a, d_e, d_key=None):
+    W = P.L + P.K
+    if d_a.numel() != P.dnum * W * P.N or d_e.numel() != P.dnum * P.N:
+        raise ValueError("a must be [dnum][L+K][N], e [dnum][N]")
+    if d_key is None:
+        d_key = torch.empty((P.dnum, 2, W, P.N), dtype=torch.int64, device=d_a.device)
+    _check(lib.ckks_client_relin_keygen(P.h, S.h, _dev(d_a), _dev(d_e), _dev(d_key), _stream()))
     return d_key
 
 

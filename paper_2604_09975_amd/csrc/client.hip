@@ -28,12 +28,13 @@ __global__ __launch_bounds__(EW_THREADS) void small_to_residues_kernel(const T *
     dst[(size_t)row * N + n] = reduce_signed((int64_t)src[(size_t)(row / period) * N + n], m);
 }
 
-// key[j][0][t] = e_hat[j][t] - a[j][t]*s[t] + f(j,t) * s[t][sigma_g],  key[j][1][t] = a[j][t]
+// key[j][0][t] = e_hat[j][t] - a[j][t]*s[t] + f(j,t) * target[t],  key[j][1][t] = a[j][t]
+// target = sigma_g(s) (Galois key) or s^2 (relin != 0: relinearisation key)
 __global__ __launch_bounds__(EW_THREADS) void keygen_kernel(const u64 *__restrict__ s, const u64 *__restrict__ a,
                                                             const u64 *__restrict__ e_hat, u64 *__restrict__ key,
                                                             const ModConst *__restrict__ mods,
                                                             const u64 *__restrict__ pmod, u64 g, u32 W, u32 L,
-                                                            u32 alpha, u32 logN) {
+                                                            u32 alpha, u32 logN, u32 relin) {
     const u32 N = 1u << logN;
     const u32 k = blockIdx.x * EW_THREADS + threadIdx.x;
     const u32 t = blockIdx.y, j = blockIdx.z;
@@ -43,7 +44,7 @@ __global__ __launch_bounds__(EW_THREADS) void keygen_kernel(const u64 *__restric
     const u64 as = mont_mul(av, mont_mul(sv, m.r2, m), m);
     u64 v = sub_mod(e_hat[jt], as, m.q);
     if (t < L && t / alpha == j) {
-        const u64 sg = s[(size_t)t * N + galois_index_c(k, g, logN)];
+        const u64 sg = relin ? mont_mul(sv, mont_mul(sv, m.r2, m), m) : s[(size_t)t * N + galois_index_c(k, g, logN)];
         v = add_mod(v, mont_mul(sg, pmod[t], m), m.q);   // pmod: P mod q_t in Montgomery form
     }
     key[(((size_t)j * 2 + 0) * W + t) * N + k] = v;
@@ -136,8 +137,21 @@ void ckks_client_secret_destroy(ckks_secret_t *S) {
     delete S;
 }
 
+static int keygen_common(ckks_params_t *P, const ckks_secret_t *S, uint64_t g, const uint64_t *d_a,
+                         const int64_t *d_e, uint64_t *d_key, void *stream_, uint32_t relin);
+
 int ckks_client_galois_keygen(ckks_params_t *P, const ckks_secret_t *S, uint64_t g, const uint64_t *d_a,
-                              const int64_t *d_e, uint64_t *d_key, void *stream_) {
+                              const int64_t *d_e, uint64_t *d_key, void *stream) {
+    return keygen_common(P, S, g, d_a, d_e, d_key, stream, 0);
+}
+
+int ckks_client_relin_keygen(ckks_params_t *P, const ckks_secret_t *S, const uint64_t *d_a, const int64_t *d_e,
+                             uint64_t *d_key, void *stream) {
+    return keygen_common(P, S, 1, d_a, d_e, d_key, stream, 1);
+}
+
+static int keygen_common(ckks_params_t *P, const ckks_secret_t *S, uint64_t g, const uint64_t *d_a,
+                         const int64_t *d_e, uint64_t *d_key, void *stream_, uint32_t relin) {
     hipStream_t stream = (hipStream_t)stream_;
     if (!P || !S || !d_a || !d_e || !d_key || S->params != P) {
         set_error("ckks_client_galois_keygen: null argument or secret of another parameter set");
@@ -169,7 +183,7 @@ int ckks_client_galois_keygen(ckks_params_t *P, const ckks_secret_t *S, uint64_t
     rc = launch_ntt(P, d_ehat, ids, W, dnum * W, false, stream);
     if (rc) return rc;
     hipLaunchKernelGGL(keygen_kernel, dim3(N / EW_THREADS, W, dnum), dim3(EW_THREADS), 0, stream, S->d_s, d_a, d_ehat,
-                       d_key, P->d_mod, d_pmod, g, W, P->L, P->alpha, P->logN);
+                       d_key, P->d_mod, d_pmod, g, W, P->L, P->alpha, P->logN, relin);
     CKKS_LAUNCH_CHECK("keygen_kernel");
     return CKKS_OK;
 }

@@ -294,7 +294,7 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
                     dv[e][j] = dig[(size_t)j * Wl * N + kp];
                     kv[e][j] = __builtin_nontemporal_load(key + (size_t)j * 2 * Wt * N + idx);
                 }
-            cv[e] = comp == 0 ? c0[kp] : 0;
+            cv[e] = (comp == 0 && it.c0) ? c0[kp] : 0;
             ov[e] = accumulate ? __builtin_nontemporal_load(dst + idx) : 0;
         }
 #pragma unroll
@@ -310,6 +310,21 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
             __builtin_nontemporal_store(v, dst + idx);
         }
     }
+}
+
+// (out0, out1, t2) = (a0*b0, a0*b1 + a1*b0, a1*b1), pointwise on limb blockIdx.y
+__global__ __launch_bounds__(KS_THREADS) void tensor_kernel(const u64 *__restrict__ a, const u64 *__restrict__ b,
+                                                            u64 *__restrict__ out, u64 *__restrict__ t2,
+                                                            const ModConst *__restrict__ mods, u32 level, u32 N) {
+    const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
+    const u32 i = blockIdx.y;
+    const ModConst m = mods[i];
+    const size_t o0 = (size_t)i * N + k, o1 = ((size_t)level + i) * N + k;
+    const u64 a0 = a[o0], a1 = a[o1];
+    const u64 b0 = mont_mul(b[o0], m.r2, m), b1 = mont_mul(b[o1], m.r2, m);   // Montgomery form
+    out[o0] = mont_mul(a0, b0, m);
+    out[o1] = add_mod(mont_mul(a0, b1, m), mont_mul(a1, b0, m), m.q);
+    t2[o0] = mont_mul(a1, b1, m);
 }
 
 size_t digits_words(const ckks_params *p, u32 level) {
@@ -535,6 +550,77 @@ int ckks_galois_key_load(const ckks_params_t *P, uint64_t galois_elt, const uint
     }
     *out = k;
     return CKKS_OK;
+}
+
+int ckks_relin_key_load(const ckks_params_t *P, const uint64_t *d_key, void *stream, ckks_gkey_t **out) {
+    if (!out) {
+        set_error("ckks_relin_key_load: out is null");
+        return CKKS_E_INVAL;
+    }
+    *out = nullptr;
+    if (!P || !d_key || P->K == 0) {
+        set_error("ckks_relin_key_load: null argument or no special primes");
+        return CKKS_E_INVAL;
+    }
+    ckks_gkey *k = new ckks_gkey();
+    k->params = P;
+    k->galois_elt = 1;   // no automorphism: the key switches from s^2
+    size_t rows = (size_t)P->dnum * 2 * P->W;
+    hipError_t e = hipMalloc((void **)&k->d_key, rows * P->N * sizeof(u64));
+    if (e != hipSuccess) {
+        delete k;
+        return hip_fail(e, "hipMalloc(key)");
+    }
+    hipLaunchKernelGGL(to_mont_kernel, dim3(P->N / KS_THREADS, (u32)rows), dim3(KS_THREADS), 0, (hipStream_t)stream,
+                       d_key, k->d_key, P->d_mod, P->W, P->N);
+    e = hipGetLastError();
+    if (e != hipSuccess) {
+        hipFree(k->d_key);
+        delete k;
+        return hip_fail(e, "to_mont_kernel");
+    }
+    *out = k;
+    return CKKS_OK;
+}
+
+int ckks_ctmul(ckks_params_t *P, const uint64_t *d_ct_a, const uint64_t *d_ct_b, uint32_t level,
+               const ckks_gkey_t *relin_key, uint64_t *d_ct_out, void *stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!P || !d_ct_a || !d_ct_b || !d_ct_out) {
+        set_error("ckks_ctmul: null argument");
+        return CKKS_E_INVAL;
+    }
+    if (level == 0 || level > P->L) {
+        set_error("ckks_ctmul: level %u outside [1,%u]", level, P->L);
+        return CKKS_E_LEVEL;
+    }
+    if (!relin_key) {
+        set_error("ckks_ctmul: no relinearisation key");
+        return CKKS_E_NOKEY;
+    }
+    if (relin_key->params != P || relin_key->galois_elt != 1) {
+        set_error("ckks_ctmul: the key is not a relinearisation key of this parameter set");
+        return CKKS_E_INVAL;
+    }
+    const u32 N = P->N;
+    const size_t dig_w = digits_words(P, level), lim_w = (size_t)level * N;
+    int rc = P->ensure_scratch((dig_w + 2 * lim_w + switch_scratch_words(P, level, 1)) * sizeof(u64), stream);
+    if (rc) return rc;
+    u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + dig_w, *d_t2 = d_tmp + lim_w, *d_work = d_t2 + lim_w;
+    hipLaunchKernelGGL(tensor_kernel, dim3(N / KS_THREADS, level), dim3(KS_THREADS), 0, stream, d_ct_a, d_ct_b,
+                       d_ct_out, d_t2, P->d_mod, level, N);
+    CKKS_LAUNCH_CHECK("tensor_kernel");
+    const u64 *c1 = d_t2;
+    rc = decompose(P, &c1, 1, level, d_digits, d_tmp, stream);
+    if (rc) return rc;
+    SwitchItem it;
+    it.digits = d_digits;
+    it.c0 = nullptr;            // (t0, t1) are already in the output: the switch only adds ModDown(...)
+    it.key = relin_key->d_key;
+    it.dst = d_ct_out;
+    it.galois_elt = 1;
+    it.accumulate = 1;
+    return switch_batch(P, level, &it, 1, d_work, stream);
 }
 
 void ckks_galois_key_destroy(ckks_gkey_t *key) {

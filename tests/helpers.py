@@ -49,6 +49,12 @@ class Client:
         e = W.gaussian_error(self.r, (O.dnum, O.N))
         return O.galois_keygen(self.s, g, a, e)
 
+    def relin_key(self):
+        O = self.O
+        a = W.uniform_residues(self.r, O.moduli, O.N, lead=(O.dnum,))
+        e = W.gaussian_error(self.r, (O.dnum, O.N))
+        return O.relin_keygen(self.s, a, e)
+
     def encrypt_coeffs(self, m, level):
         O = self.O
         a = W.uniform_residues(self.r, O.q[:level], O.N)
