@@ -167,6 +167,40 @@ int ckks_ctpt_matmul(ckks_params_t *params, const ckks_weights_t *w, const uint6
                      const ckks_gkey_t *conj_key, uint32_t flags, uint64_t *d_ct_y, ckks_counters_t *counters,
                      void *stream);
 
+/* Plaintext in evaluation form for ckks_ptmul / ckks_rot_first: int64 coefficient polynomials d_coeffs
+ * [count][N] (an encoding at the caller's scale, Sec. 2.2) -> canonical NTT-domain residues d_out
+ * [count][level][N] on limbs 0..level-1. */
+int ckks_plain_expand(const ckks_params_t *params, uint32_t level, const int64_t *d_coeffs, uint32_t count,
+                      uint64_t *d_out, void *stream);
+
+/* add of Table 1: d_ct_out = d_ct_a + d_ct_b, limb-wise, for n_ct ciphertexts [n_ct][2][level][N] of equal
+ * level and scale.  d_ct_out may alias either input. */
+int ckks_add(const ckks_params_t *params, const uint64_t *d_ct_a, const uint64_t *d_ct_b, uint32_t level,
+             uint32_t n_ct, uint64_t *d_ct_out, void *stream);
+
+/* ptmul of Table 1: both components of d_ct [2][level][N] times the plaintext d_plain [level][N] (from
+ * ckks_plain_expand).  scale(out) = scale(ct)*scale(plain): follow with ckks_rescale.  out may alias d_ct. */
+int ckks_ptmul(const ckks_params_t *params, const uint64_t *d_ct, uint32_t level, const uint64_t *d_plain,
+               uint64_t *d_ct_out, void *stream);
+
+/* ModSwitchToNext (Sec. 5.4): drops limb level_in-1 WITHOUT dividing: value and scale are unchanged, one level
+ * of budget is given up.  [n_ct][2][level_in][N] -> [n_ct][2][level_in-1][N]; in and out may not overlap.
+ * CKKS_E_LEVEL if level_in < 2. */
+int ckks_mod_switch_to_next(const ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct,
+                            uint64_t *d_ct_out, void *stream);
+
+/* RotFirst_L(x; tau) of App. A.1: cyclic LEFT shift by tau (mod L) inside the first L slots,
+ *   rot(x; tau) (.) a + rot(x; (tau - L) mod n) (.) b,
+ * a = 1{0 <= i < L - tau}, b = 1{L - tau <= i < L} given by the caller as plaintexts d_mask_a, d_mask_b
+ * [level][N] (ckks_plain_expand of their encodings, both at one scale).  Slots L..n-1 come out as zero.  The two
+ * rotations share one hoisted decomposition.  key_tau is the key of step tau mod L, key_wrap of step
+ * (tau mod L - L) mod n; either may be NULL when its step is 0 (mod n).  With L = C*m and tau = Delta*m this is the
+ * restricted segment shift Phi_C^Delta used when fewer than N_seg segments are active.  scale(out) =
+ * scale(x)*scale(mask): follow with ckks_rescale.  d_ct_out [2][level][N], may not alias d_ct_in. */
+int ckks_rot_first(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level, uint32_t L_slots, uint32_t tau,
+                   const ckks_gkey_t *key_tau, const ckks_gkey_t *key_wrap, const uint64_t *d_mask_a,
+                   const uint64_t *d_mask_b, uint64_t *d_ct_out, void *stream);
+
 /* rescale (Sec. 2.2): drops limb level_in-1 and divides by its prime with
  * centred rounding.  d_ct_in [n_ct][2][level_in][N] -> d_ct_out
  * [n_ct][2][level_in-1][N].  CKKS_E_LEVEL if level_in < 2 or > L. */

@@ -57,6 +57,10 @@ def _lib():
                                     _u64p, C.c_int, C.c_int, C.c_int]
     lib.orc_rescale.argtypes = [C.c_void_p, _u64p, C.c_int, C.c_int, _u64p]
     lib.orc_galois_keygen.argtypes = [C.c_void_p, _i8p, C.c_uint64, _u64p, _i64p, _u64p]
+    lib.orc_add.argtypes = [C.c_void_p, _u64p, _u64p, C.c_int, C.c_int, _u64p]
+    lib.orc_ptmul.argtypes = [C.c_void_p, _u64p, C.c_int, _u64p, _u64p]
+    lib.orc_mod_switch.argtypes = [C.c_void_p, _u64p, C.c_int, C.c_int, _u64p]
+    lib.orc_rot_first.argtypes = [C.c_void_p, _u64p, C.c_int, _u64p, C.POINTER(_u64p), _u64p, _u64p, _u64p]
     lib.orc_relin_keygen.argtypes = [C.c_void_p, _i8p, _u64p, _i64p, _u64p]
     lib.orc_ctmul.argtypes = [C.c_void_p, _u64p, _u64p, C.c_int, _u64p, _u64p]
     lib.orc_encrypt.argtypes = [C.c_void_p, C.c_int, _i64p, _i8p, _u64p, _i64p, _u64p]
@@ -264,6 +268,47 @@ class Oracle:
         key = np.zeros((self.dnum, 2, W, self.N), dtype=np.uint64)
         LIB.orc_galois_keygen(self._h, sp, g, ap, ep, key.ctypes.data_as(_u64p))
         return key
+
+    def add(self, a, b, level):
+        a_, ap = _u64(a)
+        b_, bp = _u64(b)
+        n_ct = a_.size // (2 * level * self.N)
+        out = np.zeros_like(a_)
+        LIB.orc_add(self._h, ap, bp, level, n_ct, out.ctypes.data_as(_u64p))
+        return out
+
+    def ptmul(self, ct, level, pt):
+        c_, cp = _u64(ct)
+        p_, pp = _u64(pt)
+        assert c_.shape == (2, level, self.N) and p_.shape == (level, self.N)
+        out = np.zeros_like(c_)
+        LIB.orc_ptmul(self._h, cp, level, pp, out.ctypes.data_as(_u64p))
+        return out
+
+    def mod_switch(self, ct, level):
+        c_, cp = _u64(ct)
+        n_ct = c_.shape[0]
+        assert c_.shape == (n_ct, 2, level, self.N)
+        out = np.zeros((n_ct, 2, level - 1, self.N), dtype=np.uint64)
+        LIB.orc_mod_switch(self._h, cp, level, n_ct, out.ctypes.data_as(_u64p))
+        return out
+
+    def rot_first(self, ct, level, gelts, keys, mask_a, mask_b):
+        c_, cp = _u64(ct)
+        g_, gp = _u64(np.array(gelts, dtype=np.uint64))
+        keep, kp = [], (_u64p * 2)()
+        for i, k in enumerate(keys):
+            if k is None:
+                kp[i] = None
+            else:
+                ka, kptr = _u64(k)
+                keep.append(ka)
+                kp[i] = kptr
+        a_, ap = _u64(mask_a)
+        b_, bp = _u64(mask_b)
+        out = np.zeros_like(c_)
+        LIB.orc_rot_first(self._h, cp, level, gp, kp, ap, bp, out.ctypes.data_as(_u64p))
+        return out
 
     def relin_keygen(self, s, a, e):
         s_, sp = _i8(s)

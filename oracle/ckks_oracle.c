@@ -615,6 +615,55 @@ void orc_rescale(const orc_ctx *c, const u64 *ct_in, int level, int n_ct, u64 *c
 }
 
 /* ------------------------------------------------------------------ */
+/* add / ptmul / ModSwitchToNext / RotFirst                            */
+/* ------------------------------------------------------------------ */
+/* add of Table 1: limb-wise sum of n_ct pairs of ciphertexts, [n_ct][2][level][N]. */
+void orc_add(const orc_ctx *c, const u64 *a, const u64 *b, int level, int n_ct, u64 *out) {
+    u64 N = c->N;
+    for (u64 row = 0; row < (u64)n_ct * 2 * level; row++) {
+        u64 q = c->mod[row % level];
+        for (u64 x = 0; x < N; x++) out[row * N + x] = addmod(a[row * N + x], b[row * N + x], q);
+    }
+}
+
+/* ptmul of Table 1: both components times a plaintext given as NTT-domain residues pt [level][N]. */
+void orc_ptmul(const orc_ctx *c, const u64 *ct, int level, const u64 *pt, u64 *out) {
+    u64 N = c->N;
+    for (int comp = 0; comp < 2; comp++)
+        for (int i = 0; i < level; i++) {
+            u64 q = c->mod[i];
+            u64 off = ((u64)comp * level + i) * N;
+            for (u64 x = 0; x < N; x++) out[off + x] = mulmod(ct[off + x], pt[(u64)i * N + x], q);
+        }
+}
+
+/* ModSwitchToNext (Sec. 5.4): drop the last RNS prime without rescaling; the plaintext and its scale stay.
+ * [n_ct][2][level][N] -> [n_ct][2][level-1][N]. */
+void orc_mod_switch(const orc_ctx *c, const u64 *in, int level, int n_ct, u64 *out) {
+    u64 N = c->N;
+    for (int pc = 0; pc < 2 * n_ct; pc++)
+        memcpy(out + (u64)pc * (level - 1) * N, in + (u64)pc * level * N, sizeof(u64) * (level - 1) * N);
+}
+
+/* RotFirst_L(x; tau) of App. A.1: cyclic left shift by tau inside the first L slots,
+ *   rot(x; tau) (.) a  +  rot(x; (tau - L) mod n) (.) b,
+ * with the masks a = 1{0 <= i < L - tau}, b = 1{L - tau <= i < L} handed over as expanded plaintexts
+ * mask_a, mask_b [level][N].  The two rotations share their input (one hoisted decomposition).
+ * gelts: the two Galois elements, keys: their keys (NULL where an element is 1). */
+void orc_rot_first(const orc_ctx *c, const u64 *ct, int level, const u64 *gelts, const u64 *const *keys,
+                   const u64 *mask_a, const u64 *mask_b, u64 *out) {
+    u64 N = c->N;
+    u64 ctw = (u64)2 * level * N;
+    u64 *rot = (u64 *)malloc(sizeof(u64) * 2 * ctw);
+    u64 *tmp = (u64 *)malloc(sizeof(u64) * ctw);
+    orc_rotate_hoisted(c, ct, level, gelts, 2, keys, rot);
+    orc_ptmul(c, rot, level, mask_a, out);
+    orc_ptmul(c, rot + ctw, level, mask_b, tmp);
+    orc_add(c, out, tmp, level, 1, out);
+    free(tmp); free(rot);
+}
+
+/* ------------------------------------------------------------------ */
 /* client side used by the tests: keys, encryption, decryption         */
 /* ------------------------------------------------------------------ */
 /* s: ternary secret in {-1,0,1}^N.  Returns NTT(s) on every limb, [L+K][N]. */

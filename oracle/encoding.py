@@ -230,3 +230,16 @@ def score_friendly_permutation(H, d_h):
         for u in range(d_h):
             perm[h * d_h + u] = u * H + h
     return perm
+
+
+# ---------------------------------------------------------------------------
+# restricted rotations (App. A.1)
+# ---------------------------------------------------------------------------
+def rot_first_masks(n, L, tau):
+    """a_{L,tau} = 1{0 <= i < L - tau}, b_{L,tau} = 1{L - tau <= i < L} and the two rotation steps
+    (tau, (tau - L) mod n) of RotFirst_L(.; tau)."""
+    tau %= L
+    i = np.arange(n)
+    a = ((i >= 0) & (i < L - tau)).astype(np.float64)
+    b = ((i >= L - tau) & (i < L)).astype(np.float64)
+    return a, b, (tau, (tau - L) % n)

@@ -49,6 +49,11 @@ _SIGS = {
     "ckks_rescale": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
     "ckks_relin_key_load": [_vp, _vp, _vp, C.POINTER(_vp)],
     "ckks_ctmul": [_vp, _vp, _vp, C.c_uint32, _vp, _vp, _vp],
+    "ckks_plain_expand": [_vp, C.c_uint32, _vp, C.c_uint32, _vp, _vp],
+    "ckks_add": [_vp, _vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
+    "ckks_ptmul": [_vp, _vp, C.c_uint32, _vp, _vp, _vp],
+    "ckks_mod_switch_to_next": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
+    "ckks_rot_first": [_vp, _vp, C.c_uint32, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp, _vp],
 }
 for _n, _a in _SIGS.items():
     getattr(lib, _n).argtypes = _a
@@ -248,6 +253,54 @@ def ckks_rescale(P, d_ct_in, level_in, n_ct, d_ct_out=None):
     if d_ct_out is None:
         d_ct_out = torch.empty((n_ct, 2, max(level_in - 1, 1), P.N), dtype=torch.int64, device=d_ct_in.device)
     _check(lib.ckks_rescale(P.h, _dev(d_ct_in), level_in, n_ct, _dev(d_ct_out), _stream()))
+    return d_ct_out
+
+
+def ckks_plain_expand(P, level, d_coeffs, d_out=None):
+    count = d_coeffs.numel() // P.N
+    if d_coeffs.numel() != count * P.N:
+        raise ValueError("coefficients must be [count][N]")
+    if d_out is None:
+        d_out = torch.empty((count, level, P.N), dtype=torch.int64, device=d_coeffs.device)
+    _check(lib.ckks_plain_expand(P.h, level, _dev(d_coeffs), count, _dev(d_out), _stream()))
+    return d_out
+
+
+def ckks_add(P, d_ct_a, d_ct_b, level, n_ct, d_ct_out=None):
+    if d_ct_a.numel() != n_ct * 2 * level * P.N or d_ct_b.numel() != d_ct_a.numel():
+        raise ValueError("ciphertexts must be [n_ct][2][level][N]")
+    if d_ct_out is None:
+        d_ct_out = torch.empty_like(d_ct_a)
+    _check(lib.ckks_add(P.h, _dev(d_ct_a), _dev(d_ct_b), level, n_ct, _dev(d_ct_out), _stream()))
+    return d_ct_out
+
+
+def ckks_ptmul(P, d_ct, level, d_plain, d_ct_out=None):
+    if d_ct.numel() != 2 * level * P.N or d_plain.numel() != level * P.N:
+        raise ValueError("ciphertext must be [2][level][N], plaintext [level][N]")
+    if d_ct_out is None:
+        d_ct_out = torch.empty_like(d_ct)
+    _check(lib.ckks_ptmul(P.h, _dev(d_ct), level, _dev(d_plain), _dev(d_ct_out), _stream()))
+    return d_ct_out
+
+
+def ckks_mod_switch_to_next(P, d_ct_in, level_in, n_ct, d_ct_out=None):
+    if d_ct_in.numel() != n_ct * 2 * level_in * P.N:
+        raise ValueError("input must be [n_ct][2][level][N]")
+    if d_ct_out is None:
+        d_ct_out = torch.empty((n_ct, 2, max(level_in - 1, 1), P.N), dtype=torch.int64, device=d_ct_in.device)
+    _check(lib.ckks_mod_switch_to_next(P.h, _dev(d_ct_in), level_in, n_ct, _dev(d_ct_out), _stream()))
+    return d_ct_out
+
+
+def ckks_rot_first(P, d_ct_in, level, L_slots, tau, key_tau, key_wrap, d_mask_a, d_mask_b, d_ct_out=None):
+    if d_ct_in.numel() != 2 * level * P.N or d_mask_a.numel() != level * P.N or d_mask_b.numel() != level * P.N:
+        raise ValueError("ciphertext must be [2][level][N], masks [level][N]")
+    if d_ct_out is None:
+        d_ct_out = torch.empty((2, level, P.N), dtype=torch.int64, device=d_ct_in.device)
+    _check(lib.ckks_rot_first(P.h, _dev(d_ct_in), level, L_slots, tau, key_tau.h if key_tau is not None else None,
+                              key_wrap.h if key_wrap is not None else None, _dev(d_mask_a), _dev(d_mask_b),
+                              _dev(d_ct_out), _stream()))
     return d_ct_out
 
 

@@ -116,6 +116,14 @@ def diagonal_slots_complex(Wm, m, n, C, N1, b, p, half=True):
     return 0.5 * z if half else z
 
 
+def rot_first_masks(n, L, tau):
+    """Masks and rotation steps of RotFirst_L(.; tau) (App. A.1): first L - tau slots from the plain rotation,
+    the next tau from the wrapped one.  -> (a [n], b [n], (step_tau, step_wrap))."""
+    t = tau % L
+    i = np.arange(n)
+    return (i < L - t).astype(np.float64), ((i >= L - t) & (i < L)).astype(np.float64), (t, (t - L) % n)
+
+
 class Client:
     """Secret-key holder bound to one parameter set."""
 

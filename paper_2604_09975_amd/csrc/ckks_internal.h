@@ -130,5 +130,14 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
 int switch_accumulate(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_u, bool accumulate,
                       hipStream_t stream);
 int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64 *d_w, hipStream_t stream);
+// hoisted rotations of one ciphertext; the first reserve_words of the scratch arena are left to the caller
+size_t rotate_hoisted_scratch_words(const ckks_params *p, u32 level, u32 n_steps);
+int rotate_hoisted(ckks_params *p, const u64 *d_ct_in, u32 level, const int32_t *steps, u32 n_steps,
+                   const ckks_gkey *const *keys, u64 *d_ct_out, size_t reserve_words, hipStream_t stream);
+
+// matmul.hip
+// int64 coefficients [count][N] -> NTT-domain residues [count][level][N]; weight_form: doubles / Montgomery per limb
+int expand_plain(const ckks_params *p, u32 level, const int64_t *d_coeffs, u32 count, u64 *d_out, bool weight_form,
+                 hipStream_t stream);
 
 }  // namespace ckks

@@ -508,6 +508,80 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
 
 }  // namespace ckks
 
+namespace ckks {
+
+size_t rotate_hoisted_scratch_words(const ckks_params *P, u32 level, u32 n_steps) {
+    const u32 batch = std::max<u32>(1, std::min<u32>(ROT_BATCH, n_steps));
+    return digits_words(P, level) + (size_t)level * P->N + switch_scratch_words(P, level, batch);
+}
+
+int rotate_hoisted(ckks_params *P, const u64 *d_ct_in, u32 level, const int32_t *steps, u32 n_steps,
+                   const ckks_gkey *const *keys, u64 *d_ct_out, size_t reserve_words, hipStream_t stream) {
+    if (!P || !d_ct_in || (n_steps && (!steps || !d_ct_out))) {
+        set_error("ckks_rotate_hoisted: null argument");
+        return CKKS_E_INVAL;
+    }
+    if (level == 0 || level > P->L) {
+        set_error("ckks_rotate_hoisted: level %u outside [1,%u]", level, P->L);
+        return CKKS_E_LEVEL;
+    }
+    const u32 N = P->N;
+    const size_t ctw = (size_t)2 * level * N;
+    std::vector<SwitchItem> items;
+    std::vector<u32> copies;
+    for (u32 r = 0; r < n_steps; ++r) {
+        u64 g;
+        ckks_galois_elt(P, steps[r], &g);
+        if (g == 1) {
+            copies.push_back(r);
+            continue;
+        }
+        if (P->K == 0) {
+            set_error("ckks_rotate_hoisted: parameter set has no special primes");
+            return CKKS_E_INVAL;
+        }
+        if (!keys || !keys[r]) {
+            set_error("ckks_rotate_hoisted: step %d (index %u) has no key", steps[r], r);
+            return CKKS_E_NOKEY;
+        }
+        if (keys[r]->params != P || keys[r]->galois_elt != g) {
+            set_error("ckks_rotate_hoisted: key %u is for Galois element %llu, step %d needs %llu", r,
+                      (unsigned long long)keys[r]->galois_elt, steps[r], (unsigned long long)g);
+            return CKKS_E_INVAL;
+        }
+        SwitchItem it;
+        it.digits = nullptr;
+        it.c0 = d_ct_in;
+        it.key = keys[r]->d_key;
+        it.dst = d_ct_out + (size_t)r * ctw;
+        it.galois_elt = g;
+        it.accumulate = 0;
+        items.push_back(it);
+    }
+    for (u32 r : copies)
+        CKKS_HIP(hipMemcpyAsync(d_ct_out + (size_t)r * ctw, d_ct_in, ctw * sizeof(u64), hipMemcpyDeviceToDevice,
+                                stream));
+    if (items.empty()) return CKKS_OK;
+    const u32 batch = std::min<u32>(ROT_BATCH, (u32)items.size());
+    const size_t dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
+    int rc = P->ensure_scratch((reserve_words + dig_w + tmp_w + switch_scratch_words(P, level, batch)) * sizeof(u64),
+                               stream);
+    if (rc) return rc;
+    u64 *d_digits = (u64 *)P->d_scratch + reserve_words, *d_tmp = d_digits + dig_w, *d_work = d_tmp + tmp_w;
+    const u64 *c1 = d_ct_in + (size_t)level * N;
+    rc = decompose(P, &c1, 1, level, d_digits, d_tmp, stream);
+    if (rc) return rc;
+    for (auto &it : items) it.digits = d_digits;
+    for (size_t done = 0; done < items.size(); done += batch) {
+        u32 n = (u32)std::min<size_t>(batch, items.size() - done);
+        rc = switch_batch(P, level, items.data() + done, n, d_work, stream);
+        if (rc) return rc;
+    }
+    return CKKS_OK;
+}
+
+}  // namespace ckks
+
 using namespace ckks;
 
 extern "C" {
@@ -631,67 +705,7 @@ void ckks_galois_key_destroy(ckks_gkey_t *key) {
 
 int ckks_rotate_hoisted(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level, const int32_t *steps,
                         uint32_t n_steps, const ckks_gkey_t *const *keys, uint64_t *d_ct_out, void *stream_) {
-    hipStream_t stream = (hipStream_t)stream_;
-    if (!P || !d_ct_in || (n_steps && (!steps || !d_ct_out))) {
-        set_error("ckks_rotate_hoisted: null argument");
-        return CKKS_E_INVAL;
-    }
-    if (level == 0 || level > P->L) {
-        set_error("ckks_rotate_hoisted: level %u outside [1,%u]", level, P->L);
-        return CKKS_E_LEVEL;
-    }
-    const u32 N = P->N;
-    const size_t ctw = (size_t)2 * level * N;
-    std::vector<SwitchItem> items;
-    std::vector<u32> copies;
-    for (u32 r = 0; r < n_steps; ++r) {
-        u64 g;
-        ckks_galois_elt(P, steps[r], &g);
-        if (g == 1) {
-            copies.push_back(r);
-            continue;
-        }
-        if (P->K == 0) {
-            set_error("ckks_rotate_hoisted: parameter set has no special primes");
-            return CKKS_E_INVAL;
-        }
-        if (!keys || !keys[r]) {
-            set_error("ckks_rotate_hoisted: step %d (index %u) has no key", steps[r], r);
-            return CKKS_E_NOKEY;
-        }
-        if (keys[r]->params != P || keys[r]->galois_elt != g) {
-            set_error("ckks_rotate_hoisted: key %u is for Galois element %llu, step %d needs %llu", r,
-                      (unsigned long long)keys[r]->galois_elt, steps[r], (unsigned long long)g);
-            return CKKS_E_INVAL;
-        }
-        SwitchItem it;
-        it.digits = nullptr;
-        it.c0 = d_ct_in;
-        it.key = keys[r]->d_key;
-        it.dst = d_ct_out + (size_t)r * ctw;
-        it.galois_elt = g;
-        it.accumulate = 0;
-        items.push_back(it);
-    }
-    for (u32 r : copies)
-        CKKS_HIP(hipMemcpyAsync(d_ct_out + (size_t)r * ctw, d_ct_in, ctw * sizeof(u64), hipMemcpyDeviceToDevice,
-                                stream));
-    if (items.empty()) return CKKS_OK;
-    const u32 batch = std::min<u32>(ROT_BATCH, (u32)items.size());
-    const size_t dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
-    int rc = P->ensure_scratch((dig_w + tmp_w + switch_scratch_words(P, level, batch)) * sizeof(u64), stream);
-    if (rc) return rc;
-    u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + dig_w, *d_work = d_tmp + tmp_w;
-    const u64 *c1 = d_ct_in + (size_t)level * N;
-    rc = decompose(P, &c1, 1, level, d_digits, d_tmp, stream);
-    if (rc) return rc;
-    for (auto &it : items) it.digits = d_digits;
-    for (size_t done = 0; done < items.size(); done += batch) {
-        u32 n = (u32)std::min<size_t>(batch, items.size() - done);
-        rc = switch_batch(P, level, items.data() + done, n, d_work, stream);
-        if (rc) return rc;
-    }
-    return CKKS_OK;
+    return rotate_hoisted(P, d_ct_in, level, steps, n_steps, keys, d_ct_out, 0, (hipStream_t)stream_);
 }
 
 }  // extern "C"

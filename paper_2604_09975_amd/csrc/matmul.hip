@@ -358,7 +358,7 @@ __global__ __launch_bounds__(EW_THREADS) void take_last_limb_kernel(const u64 *_
     r[(size_t)pc * N + n] = in[((size_t)pc * level + level - 1) * N + n];
 }
 
-static int expand_plain(const ckks_params *P, u32 level, const int64_t *d_coeffs, u32 count, u64 *d_out, bool mont,
+int expand_plain(const ckks_params *P, u32 level, const int64_t *d_coeffs, u32 count, u64 *d_out, bool mont,
                         hipStream_t stream) {
     const u32 N = P->N;
     LimbIds ids;

@@ -1,0 +1,113 @@
+"""GPU parity: add, ptmul, ModSwitchToNext and RotFirst (Table 1, Sec. 5.4, App. A.1) against the oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import encoding as E
+from tests import helpers
+from tests.gpu_util import make_pair, to_dev, to_host
+from paper_2604_09975_amd import workload as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _plain(O, P, B, z, scale, level):
+    coef = E.encode(z + 0j, scale, O.N)
+    got = to_host(B.ckks_plain_expand(P, level, to_dev(coef[None])))[0]
+    want = O.expand_plain(level, coef)
+    assert (got == want).all()
+    return want
+
+
+def _elementwise(O, P, level, seed, scale):
+    from paper_2604_09975_amd import binding as B
+    cl = helpers.Client(O, seed, hamming_weight=16)
+    r = W.rng(seed)
+    cts = np.stack([cl.encrypt_slots(W.unit_disk_slots(r, O.n), scale, level) for _ in range(3)])
+    got = to_host(B.ckks_add(P, to_dev(cts[:2]), to_dev(cts[1:]), level, 2))
+    assert (got == O.add(cts[:2], cts[1:], level)).all()
+    pt = _plain(O, P, B, r.uniform(-1, 1, O.n), scale, level)
+    got = to_host(B.ckks_ptmul(P, to_dev(cts[0]), level, to_dev(pt)))
+    assert (got == O.ptmul(cts[0], level, pt)).all()
+    if level > 1:
+        got = to_host(B.ckks_mod_switch_to_next(P, to_dev(cts), level, 3))
+        assert (got == O.mod_switch(cts, level)).all()
+
+
+@pytest.mark.parametrize("level", [3, 1])
+def test_elementwise_toy(level):
+    O, P = make_pair(W.TOY_RING)
+    _elementwise(O, P, level, 30 + level, 2.0**30)
+
+
+def test_elementwise_wide_primes():
+    O = helpers.small_oracle(10, L=6, K=3, dnum=2, qbits=52, pbits=55)
+    _, P = make_pair(O)
+    _elementwise(O, P, 5, 35, 2.0**40)
+
+
+def test_elementwise_full_ring():
+    O, P = make_pair(W.BIG_RING)
+    _elementwise(O, P, 24, 36, 2.0**40)
+
+
+def _rot_first(O, P, level, L, tau, seed, scale, hw=16, check=True):
+    from paper_2604_09975_amd import binding as B
+    from paper_2604_09975_amd import client as CL
+    cl = helpers.Client(O, seed, hamming_weight=hw)
+    r = W.rng(seed)
+    z = np.zeros(O.n)
+    z[:L] = r.uniform(-1, 1, L)
+    ct = cl.encrypt_slots(z + 0j, scale, level)
+    a, b, steps = E.rot_first_masks(O.n, L, tau)
+    a2, b2, steps2 = CL.rot_first_masks(O.n, L, tau)
+    assert (a == a2).all() and (b == b2).all() and steps == steps2
+    gel = [O.galois_elt(s) for s in steps]
+    keys = [None if g == 1 else cl.galois_key(g) for g in gel]
+    ma, mb = _plain(O, P, B, a, scale, level), _plain(O, P, B, b, scale, level)
+    want = O.rot_first(ct, level, gel, keys, ma, mb)
+    hk = [None if k is None else B.ckks_galois_key_load(P, g, to_dev(k)) for g, k in zip(gel, keys)]
+    got = to_host(B.ckks_rot_first(P, to_dev(ct), level, L, tau, hk[0], hk[1], to_dev(ma), to_dev(mb)))
+    assert (got == want).all()
+    if check and level > 1:
+        out = to_host(B.ckks_rescale(P, to_dev(got[None]), level, 1))[0]
+        zz = cl.decrypt_slots(out, level - 1, scale * scale / O.q[level - 1], nlimbs=min(level - 1, 2))
+        ref = np.zeros(O.n)
+        ref[:L] = np.roll(z[:L], -(tau % L))
+        assert np.abs(zz - ref).max() < 2e-3
+
+
+@pytest.mark.parametrize("L,tau", [(1024, 16), (1024, 0), (2048, 7), (96, 95), (1024, 1024 + 48)])
+def test_rot_first_toy(L, tau):
+    O, P = make_pair(W.TOY_RING)
+    _rot_first(O, P, 3, L, tau, 40 + tau % 7, 2.0**30, hw=64)
+
+
+def test_rot_first_generic_path():
+    O = helpers.small_oracle(10, L=4, K=2, dnum=2, qbits=40, pbits=45)
+    _, P = make_pair(O)
+    _rot_first(O, P, 3, 320, 64, 47, 2.0**30)
+
+
+def test_rot_first_full_ring_restricted_segment_shift():
+    """Phi_C^Delta on the BERT layout: m = 128, C = 192 of N_seg = 256 segments active, shift by 5 segments."""
+    O, P = make_pair(W.BIG_RING)
+    _rot_first(O, P, 24, 192 * 128, 5 * 128, 48, 2.0**40, hw=64)
+
+
+def test_error_paths():
+    from paper_2604_09975_amd import binding as B
+    O, P = make_pair(W.TOY_RING)
+    ct = torch.zeros((2, 3, O.N), dtype=torch.int64, device="cuda")
+    pt = torch.zeros((3, O.N), dtype=torch.int64, device="cuda")
+    out = torch.zeros_like(ct)
+    p = lambda t: t.data_ptr()
+    assert B.lib.ckks_add(P.h, p(ct), p(ct), 4, 1, p(out), None) == -2
+    assert B.lib.ckks_add(P.h, None, p(ct), 3, 1, p(out), None) == -1
+    assert B.lib.ckks_add(P.h, None, None, 3, 0, None, None) == 0
+    assert B.lib.ckks_ptmul(P.h, p(ct), 0, p(pt), p(out), None) == -2
+    assert B.lib.ckks_mod_switch_to_next(P.h, p(ct), 1, 1, p(out), None) == -2
+    assert B.lib.ckks_rot_first(P.h, p(ct), 3, 0, 1, None, None, p(pt), p(pt), p(out), None) == -1
+    assert B.lib.ckks_rot_first(P.h, p(ct), 3, O.n + 1, 1, None, None, p(pt), p(pt), p(out), None) == -1
+    assert B.lib.ckks_rot_first(P.h, p(ct), 3, 64, 1, None, None, p(pt), p(pt), p(out), None) == -3
+    assert B.lib.ckks_plain_expand(P.h, 4, p(ct), 1, p(out), None) == -2
