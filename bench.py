@@ -267,6 +267,63 @@ def run_hoisted(args, B, CL, W, P, cl):
                      "traffic": None, "bytes_per_launch": 188.7e6 * len(steps), "ms_per_launch": ms}}), flush=True)
 
 
+def run_primitives(args, B, CL, W, P, cl):
+    """Latency of the homomorphic primitives of Table 1 on one ciphertext (the set Table 6 times): rot, conj,
+    ptmul, add, ctmul, each with the rescale that follows it in the protocols where one does.  N = 2^16, at the
+    top level (24 limbs) and at 17 limbs (multiplicative depth 16)."""
+    import torch
+    n = P.N // 2
+    r = W.rng(W.HOISTED_SEED)
+    za, zb = W.unit_disk_slots(r, n), W.unit_disk_slots(r, n)
+    k_rot, k_conj, k_relin = cl.galois_key(1), cl.galois_key("conj"), cl.relin_key()
+    res = {}
+    for level in (P.L, 17):
+        ca, cb = cl.encrypt_slots(za, 2.0 ** 40, level), cl.encrypt_slots(zb, 2.0 ** 40, level)
+        pt = B.ckks_plain_expand(P, level, cl._dev(cl.enc.encode(zb, 2.0 ** 40))[None])[0]
+        o1 = torch.empty((1, 2, level, P.N), dtype=torch.int64, device="cuda")
+        o2 = torch.empty((2, level, P.N), dtype=torch.int64, device="cuda")
+        lo = torch.empty((1, 2, level - 1, P.N), dtype=torch.int64, device="cuda")
+        ops = {
+            "rot": lambda: B.ckks_rotate_hoisted(P, ca, level, [1], [k_rot], o1),
+            "conj": lambda: B.ckks_rotate_hoisted(P, ca, level, ["conj"], [k_conj], o1),
+            "ptmul": lambda: B.ckks_ptmul(P, ca, level, pt, o2),
+            "ptmul+rescale": lambda: (B.ckks_ptmul(P, ca, level, pt, o2), B.ckks_rescale(P, o2, level, 1, lo)),
+            "add": lambda: B.ckks_add(P, ca, cb, level, 1, o2),
+            "ctmul": lambda: B.ckks_ctmul(P, ca, cb, level, k_relin, o2),
+            "ctmul+rescale": lambda: (B.ckks_ctmul(P, ca, cb, level, k_relin, o2), B.ckks_rescale(P, o2, level, 1, lo)),
+            "rescale": lambda: B.ckks_rescale(P, o2, level, 1, lo),
+        }
+        out = {}
+        reps = max(args.steps, 1) * 20
+        for name, f in ops.items():
+            for _ in range(3):
+                f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            out[name] = e0.elapsed_time(e1) / reps
+        # end-to-end checks of what was timed
+        B.ckks_ctmul(P, ca, cb, level, k_relin, o2)
+        B.ckks_rescale(P, o2, level, 1, lo)
+        err = float(np.abs(cl.decrypt_slots(lo[0], level - 1, 2.0 ** 80 / P.q[level - 1]) - za * zb).max())
+        assert err < 1e-5, err
+        B.ckks_rotate_hoisted(P, ca, level, [1], [k_rot], o1)
+        err = float(np.abs(cl.decrypt_slots(o1[0], level, 2.0 ** 40) - np.roll(za, -1)).max())
+        assert err < 585 * P.N / 2.0 ** 40, err
+        res["limbs_%d" % level] = out
+    top = res["limbs_%d" % P.L]
+    print(json.dumps({
+        "metric": "ctmul latency ms at N=2^16 L=24 (tensor + relinearisation)", "value": top["ctmul"], "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": top["ctmul"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "primitive_latencies", "N": P.N, "q_limbs": P.L, "special_limbs": P.K, "dnum": P.dnum},
+        "latency_ms": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -275,7 +332,7 @@ def main():
     ap.add_argument("--n1", type=int, default=0, help="baby steps (0 = the configuration's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
-    ap.add_argument("--workload", default="bert_qkv", choices=["bert_qkv", "gpt2_block", "hoisted", "ntt"],
+    ap.add_argument("--workload", default="bert_qkv", choices=["bert_qkv", "gpt2_block", "hoisted", "ntt", "primitives"],
                     help="bert_qkv (default, the headline configuration), the four GPT-2-small block layers, the "
                          "hoisted rotation batch alone, or the NTT microbenchmark")
     ap.add_argument("--no-hoisted", action="store_true", help="skip the hoisted-rotation batch")
@@ -318,6 +375,9 @@ def main():
         return
     if args.workload == "hoisted":
         run_hoisted(args, B, CL, W, P, cl)
+        return
+    if args.workload == "primitives":
+        run_primitives(args, B, CL, W, P, cl)
         return
     S = setup_matmul(B, CL, W, P, cl, spec, n1, fused_qk=args.fused_qk)
     N, level, B_out, G, N2 = P.N, S["level"], S["B_out"], S["G"], S["N2"]

@@ -150,6 +150,15 @@ class Client:
         torch.cuda.synchronize()
         return h
 
+    def relin_key(self):
+        """Library handle of the relinearisation key."""
+        P = self.P
+        a = W.uniform_residues(self.r, self.moduli, P.N, lead=(P.dnum,))
+        e = W.gaussian_error(self.r, (P.dnum, P.N))
+        h = B.ckks_relin_key_load(P, B.ckks_client_relin_keygen(P, self.S, self._dev(a), self._dev(e)))
+        torch.cuda.synchronize()
+        return h
+
     def encrypt_slots(self, z, scale, level):
         P = self.P
         m = self.enc.encode(z, scale)
