@@ -98,9 +98,17 @@ struct ckks_gkey {
 struct ckks_weights {
     const ckks_params *params = nullptr;
     ckks::u32 level = 0, m = 0, C = 0, G = 0, B_out = 0, N1 = 0, N2 = 0;
-    ckks::u64 *d_w = nullptr;          // [B_out][N2][G][N1][level][N], NTT domain; per limb a double (q < 2^50) or Montgomery form
+    // Diagonals, NTT domain, index ((b*N2 + p)*G + g)*N1 + q.  Two stores, each allocated when first needed:
+    // d_w  [diagonal][level][N] words: per limb a double (q < 2^50) or Montgomery form;
+    // d_wp [diagonal][level] packed half-limb records of 50-bit residues, for output blocks whose diagonals all
+    //      encode real slot vectors when every active prime is below 2^50 (block_packed).
+    ckks::u64 *d_w = nullptr;
+    unsigned char *d_wp = nullptr;
+    ckks::u64 *d_stage = nullptr;      // expansion buffer of the packed store (STAGE_DIAGS diagonals)
+    bool packable = false;             // every active prime below 2^50 and N large enough for the palindrome kernel
     ckks::u64 *d_bias = nullptr;       // [B_out][level][N], NTT domain, canonical, times bias_mul; or null
     std::vector<uint8_t> block_real;   // per output block: every diagonal loaded so far encodes a real slot vector
+    std::vector<uint8_t> block_packed; // per output block: its diagonals live in d_wp (implies block_real)
     ckks::u32 *d_flag = nullptr;       // per-diagonal check results of the chunk being loaded
     ckks::u32 flag_cap = 0;
 };

@@ -138,12 +138,18 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
 // Workgroups go to the XCDs round-robin and each XCD has its own L2, so when the run count allows it the
 // linear workgroup id is unfolded to let one XCD walk all (b,p) tiles of a run of coefficients back to
 // back: the bank lines of that run are then fetched into one L2 once.
-template <u32 TB>
+// PACKED: the half limb is stored in 50 bits per residue instead of 64 (packed_record_bytes): three planes,
+// the low 32 bits, bits 32..47, and bits 48..49 four residues to a byte.  The double is rebuilt as
+// (2^52 + x) - 2^52 from the bit pattern, one addition per weight.
+__host__ __device__ inline size_t packed_record_bytes(u32 N) { return (size_t)3 * N + N / 8; }
+
+template <u32 TB, bool PACKED>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__restrict__ bank,
                                                                   const u64 *__restrict__ w, u64 *__restrict__ acc,
                                                                   const ModFp *__restrict__ modf, LimbIds limbs,
                                                                   u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle) {
     typedef u64 vec_t __attribute__((ext_vector_type(2)));
+    typedef u32 wvec_t __attribute__((ext_vector_type(4)));      // one (b,p) pair's two weights as loaded
     u32 tile = blockIdx.x, run = blockIdx.y;
     if (swizzle) {
         const u32 lin = blockIdx.y * gridDim.x + blockIdx.x;
@@ -165,7 +171,11 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
 #pragma unroll
         for (u32 e = 0; e < 4; ++e) a[t][0][e] = a[t][1][e] = 0.0;
     // loads of step gq+1 are issued before the arithmetic of step gq
-    vec_t xb[2][2], wb[TB];
+    vec_t xb[2][2];
+    wvec_t wb[TB];
+    const size_t rec = packed_record_bytes(N);
+    const unsigned char *wbytes = reinterpret_cast<const unsigned char *>(w);
+    const u32 off_lo = 4 * k, off_hi = 2 * N + 2 * k, off_top = 3 * N + (k >> 2);
     auto fetch = [&](u32 gq) {
 #pragma unroll
         for (u32 c = 0; c < 2; ++c) {
@@ -175,9 +185,25 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
         }
 #pragma unroll
         for (u32 t = 0; t < TB; ++t)
-            if (bp0 + t < BP)
-                wb[t] = *reinterpret_cast<const vec_t *>(w + ((size_t)(bp0 + t) * GQ + gq) * w_stride + row + k);
+            if (bp0 + t < BP) {
+                if (PACKED) {
+                    // buffer loads: the record's address is workgroup-uniform (scalar registers) and the lanes
+                    // add 32-bit offsets, which keeps the 24 addresses of a step out of the vector registers
+                    const unsigned char *r = wbytes + (((size_t)(bp0 + t) * GQ + gq) * level + i) * rec;
+                    const __amdgpu_buffer_rsrc_t rs =
+                        __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(r), 0, (int)rec, 0x00020000);
+                    typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 lo = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)off_lo, 0, 0);
+                    wb[t][0] = lo[0];
+                    wb[t][1] = lo[1];
+                    wb[t][2] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)off_hi, 0, 0);
+                    wb[t][3] = __builtin_amdgcn_raw_buffer_load_b8(rs, (int)off_top, 0, 0);
+                } else {
+                    wb[t] = *reinterpret_cast<const wvec_t *>(w + ((size_t)(bp0 + t) * GQ + gq) * w_stride + row + k);
+                }
+            }
     };
+    const u32 top_shift = (k & 2) * 2;                           // k is even: bits 0..3 or 4..7 of the byte
     fetch(0);
     for (u32 gq = 0; gq < GQ; ++gq) {
         double x[2][4];
@@ -188,7 +214,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
             for (u32 e = 0; e < 4; ++e)
                 x[c][e] = __longlong_as_double((long long)(r[e] | 0x4330000000000000ull)) - 4503599627370496.0;
         }
-        vec_t wc[TB];
+        wvec_t wc[TB];
 #pragma unroll
         for (u32 t = 0; t < TB; ++t) wc[t] = wb[t];
         if (gq + 1 < GQ) fetch(gq + 1);
@@ -196,8 +222,17 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
         for (u32 t = 0; t < TB; ++t) {
             if (bp0 + t < BP) {
                 // weight of k serves k and N-1-k; weight of k+1 serves k+1 and N-2-k
-                const double w0 = __longlong_as_double((long long)wc[t][0]);
-                const double w1 = __longlong_as_double((long long)wc[t][1]);
+                double w0, w1;
+                if (PACKED) {
+                    const u32 top = wc[t][3] >> top_shift;
+                    const u32 h0 = 0x43300000u | ((top & 3u) << 16) | (wc[t][2] & 0xffffu);
+                    const u32 h1 = 0x43300000u | ((top & 12u) << 14) | (wc[t][2] >> 16);
+                    w0 = __hiloint2double((int)h0, (int)wc[t][0]) - 4503599627370496.0;
+                    w1 = __hiloint2double((int)h1, (int)wc[t][1]) - 4503599627370496.0;
+                } else {
+                    w0 = __hiloint2double((int)wc[t][1], (int)wc[t][0]);
+                    w1 = __hiloint2double((int)wc[t][3], (int)wc[t][2]);
+                }
                 const double wv[4] = {w0, w1, w1, w0};
 #pragma unroll
                 for (u32 c = 0; c < 2; ++c)
@@ -250,6 +285,44 @@ __global__ __launch_bounds__(EW_THREADS) void check_real_kernel(const int64_t *_
     const int64_t *c = coef + (size_t)blockIdx.y * N;
     if (n == 0) return;
     if (c[N - n] != -c[n]) sym[blockIdx.y] = 0;
+}
+
+// rows [rows][N] of canonical residues below 2^50 -> packed half-limb records (first N/2 residues of each row);
+// a thread packs four residues
+__global__ __launch_bounds__(EW_THREADS) void pack_half_kernel(const u64 *__restrict__ in,
+                                                               unsigned char *__restrict__ out, u32 N) {
+    const u32 k = (blockIdx.x * EW_THREADS + threadIdx.x) * 4;
+    if (k >= N / 2) return;
+    const u64 *src = in + (size_t)blockIdx.y * N + k;
+    unsigned char *r = out + (size_t)blockIdx.y * packed_record_bytes(N);
+    uint4 lo;
+    uint2 hi;
+    const u64 x0 = src[0], x1 = src[1], x2 = src[2], x3 = src[3];
+    lo.x = (u32)x0;
+    lo.y = (u32)x1;
+    lo.z = (u32)x2;
+    lo.w = (u32)x3;
+    hi.x = (u32)((x0 >> 32) & 0xffff) | ((u32)((x1 >> 32) & 0xffff) << 16);
+    hi.y = (u32)((x2 >> 32) & 0xffff) | ((u32)((x3 >> 32) & 0xffff) << 16);
+    *reinterpret_cast<uint4 *>(r + (size_t)4 * k) = lo;
+    *reinterpret_cast<uint2 *>(r + (size_t)2 * N + (size_t)2 * k) = hi;
+    r[(size_t)3 * N + (k >> 2)] =
+        (unsigned char)(((x0 >> 48) & 3) | (((x1 >> 48) & 3) << 2) | (((x2 >> 48) & 3) << 4) | (((x3 >> 48) & 3) << 6));
+}
+
+// packed records [rows] -> full rows [rows][N] of doubles (the general kernels' weight form), second half mirrored
+__global__ __launch_bounds__(EW_THREADS) void unpack_half_kernel(const unsigned char *__restrict__ in,
+                                                                 u64 *__restrict__ out, u32 N) {
+    const u32 k = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (k >= N / 2) return;
+    const unsigned char *r = in + (size_t)blockIdx.y * packed_record_bytes(N);
+    const u64 lo = *reinterpret_cast<const u32 *>(r + (size_t)4 * k);
+    const u64 hi = *reinterpret_cast<const unsigned short *>(r + (size_t)2 * N + (size_t)2 * k);
+    const u64 top = (r[(size_t)3 * N + (k >> 2)] >> ((k & 3) * 2)) & 3;
+    const u64 x = lo | (hi << 32) | (top << 48);
+    const u64 d = (u64)__double_as_longlong((double)x);
+    out[(size_t)blockIdx.y * N + k] = d;
+    out[(size_t)blockIdx.y * N + (N - 1 - k)] = d;
 }
 
 __global__ __launch_bounds__(EW_THREADS) void fill_u32_kernel(u32 *p, u32 v, u32 n) {
@@ -418,15 +491,53 @@ int ckks_weights_create(const ckks_params_t *P, uint32_t level, uint32_t m, uint
     w->N1 = N1;
     w->N2 = C / N1;
     w->block_real.assign(B_out, 1);
-    size_t words = (size_t)B_out * w->N2 * G * N1 * level * P->N;
-    hipError_t e = hipMalloc((void **)&w->d_w, words * sizeof(u64));
-    if (e != hipSuccess) {
-        delete w;
-        return hip_fail(e, "hipMalloc(weights)");
-    }
+    w->block_packed.assign(B_out, 0);
+    w->packable = P->N >= 4 * MM_THREADS;
+    for (u32 i = 0; i < level; ++i)
+        if (P->mod[i] >> 50) w->packable = false;
     *out = w;
     return CKKS_OK;
 }
+
+namespace {
+
+constexpr u32 STAGE_DIAGS = 32;
+
+int ensure_full_store(ckks_weights *w) {
+    if (w->d_w) return CKKS_OK;
+    const size_t words = (size_t)w->B_out * w->N2 * w->G * w->N1 * w->level * w->params->N;
+    CKKS_HIP(hipMalloc((void **)&w->d_w, words * sizeof(u64)));
+    return CKKS_OK;
+}
+
+int ensure_packed_store(ckks_weights *w) {
+    const u32 N = w->params->N;
+    if (!w->d_wp) {
+        const size_t recs = (size_t)w->B_out * w->N2 * w->G * w->N1 * w->level;
+        CKKS_HIP(hipMalloc((void **)&w->d_wp, recs * packed_record_bytes(N)));
+    }
+    if (!w->d_stage) CKKS_HIP(hipMalloc((void **)&w->d_stage, (size_t)STAGE_DIAGS * w->level * N * sizeof(u64)));
+    return CKKS_OK;
+}
+
+// A packed block receives a diagonal that is not real: its diagonals move to the full store.
+int unpack_block(ckks_weights *w, u32 b, hipStream_t stream) {
+    int rc = ensure_full_store(w);
+    if (rc) return rc;
+    const u32 N = w->params->N;
+    const size_t rows = (size_t)w->N2 * w->G * w->N1 * w->level, first = (size_t)b * rows;
+    for (size_t done = 0; done < rows;) {
+        const u32 c = (u32)std::min<size_t>(rows - done, 32768);
+        hipLaunchKernelGGL(unpack_half_kernel, dim3((N / 2 + EW_THREADS - 1) / EW_THREADS, c), dim3(EW_THREADS), 0,
+                           stream, w->d_wp + (first + done) * packed_record_bytes(N), w->d_w + (first + done) * N, N);
+        CKKS_LAUNCH_CHECK("unpack_half_kernel");
+        done += c;
+    }
+    w->block_packed[b] = 0;
+    return CKKS_OK;
+}
+
+}  // namespace
 
 int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count, const int64_t *d_coeffs,
                                void *stream) {
@@ -460,12 +571,41 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
         CKKS_HIP(hipMemcpyAsync(flags.data(), w->d_flag, count * sizeof(u32), hipMemcpyDeviceToHost,
                                 (hipStream_t)stream));
         CKKS_HIP(hipStreamSynchronize((hipStream_t)stream));
-        const u32 per_block = w->N2 * w->G * w->N1;
-        for (u32 d = 0; d < count; ++d)
-            if (!flags[d]) w->block_real[(first + d) / per_block] = 0;
+        const u32 per_block = w->N2 * w->G * w->N1, N = P->N, level = w->level;
+        // the chunk is stored block by block: packed while the block has seen real diagonals only, else in full
+        for (u32 lo = first; lo < first + count;) {
+            const u32 b = lo / per_block;
+            const u32 hi = std::min<u32>(first + count, (b + 1) * per_block);
+            bool all_real = true;
+            for (u32 d = lo; d < hi; ++d) all_real = all_real && flags[d - first];
+            if (!all_real) w->block_real[b] = 0;
+            // a block that is still real has either nothing loaded yet or everything so far in the packed store
+            const bool packed = w->packable && w->block_real[b];
+            int rc;
+            if (packed) {
+                if ((rc = ensure_packed_store(w))) return rc;
+                w->block_packed[b] = 1;
+                for (u32 d = lo; d < hi; d += STAGE_DIAGS) {
+                    const u32 c = std::min(STAGE_DIAGS, hi - d);
+                    rc = expand_plain(P, level, d_coeffs + (size_t)(d - first) * N, c, w->d_stage, false,
+                                      (hipStream_t)stream);
+                    if (rc) return rc;
+                    hipLaunchKernelGGL(pack_half_kernel, dim3((N / 8 + EW_THREADS - 1) / EW_THREADS, c * level),
+                                       dim3(EW_THREADS), 0, (hipStream_t)stream, w->d_stage,
+                                       w->d_wp + (size_t)d * level * packed_record_bytes(N), N);
+                    CKKS_LAUNCH_CHECK("pack_half_kernel");
+                }
+            } else {
+                if (w->block_packed[b] && (rc = unpack_block(w, b, (hipStream_t)stream))) return rc;
+                if ((rc = ensure_full_store(w))) return rc;
+                rc = expand_plain(P, level, d_coeffs + (size_t)(lo - first) * N, hi - lo,
+                                  w->d_w + (size_t)lo * level * N, true, (hipStream_t)stream);
+                if (rc) return rc;
+            }
+            lo = hi;
+        }
     }
-    return expand_plain(P, w->level, d_coeffs, count, w->d_w + (size_t)first * w->level * P->N, true,
-                        (hipStream_t)stream);
+    return CKKS_OK;
 }
 
 int ckks_weights_set_bias(ckks_weights_t *w, const int64_t *d_bias_coeffs, uint64_t bias_mul, void *stream) {
@@ -486,6 +626,8 @@ int ckks_weights_set_bias(ckks_weights_t *w, const int64_t *d_bias_coeffs, uint6
 void ckks_weights_destroy(ckks_weights_t *w) {
     if (!w) return;
     hipFree(w->d_w);
+    hipFree(w->d_wp);
+    hipFree(w->d_stage);
     hipFree(w->d_bias);
     hipFree(w->d_flag);
     delete w;
@@ -615,16 +757,22 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         // or general ones
         for (u32 b0 = 0; n_fp && b0 < B;) {
             u32 b1 = b0 + 1;
-            while (b1 < B && w->block_real[b1] == w->block_real[b0]) ++b1;
+            while (b1 < B && w->block_real[b1] == w->block_real[b0] && w->block_packed[b1] == w->block_packed[b0])
+                ++b1;
             const u32 bp_first = b0 * N2, bp_count = (b1 - b0) * N2;
             const u64 *wp = w->d_w + (size_t)bp_first * GQ * level * N;
             u64 *ap = d_acc + (size_t)bp_first * ctw;
-            if (w->block_real[b0] && N >= 4 * MM_THREADS) {
-                const u32 runs = N / (4 * MM_THREADS);
-                // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
-                hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB>), dim3((bp_count + MM_TB - 1) / MM_TB, runs, n_fp),
-                                   dim3(MM_THREADS), 0, stream, d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ,
-                                   bp_count, runs % 8 == 0 ? 1u : 0u);
+            const u32 runs = N / (4 * MM_THREADS);
+            const dim3 sym_grid((bp_count + MM_TB - 1) / MM_TB, runs, n_fp);
+            // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
+            if (w->block_packed[b0]) {
+                const u64 *pp = reinterpret_cast<const u64 *>(w->d_wp + (size_t)bp_first * GQ * level *
+                                                                            packed_record_bytes(N));
+                hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, true>), sym_grid, dim3(MM_THREADS), 0, stream, d_bank,
+                                   pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count, runs % 8 == 0 ? 1u : 0u);
+            } else if (w->block_real[b0] && N >= 4 * MM_THREADS) {
+                hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, false>), sym_grid, dim3(MM_THREADS), 0, stream, d_bank,
+                                   wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count, runs % 8 == 0 ? 1u : 0u);
             } else {   // 8 accumulators x 2 coefficients per thread (16-byte loads)
                 hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2>),
                                    dim3((bp_count + MM_TB - 1) / MM_TB, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS), 0,

@@ -39,7 +39,10 @@ def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_
     mx = E.encode(E.pack_columns(X, n, C) + 0j, sx, N)
     ct_x = np.stack([cl.encrypt_coeffs(mx[g], level) for g in range(G)])
     diag = E.encode_diagonals(Wm, m, N, C, N1, sw)
-    if real:
+    if real == "first_upload":                     # real diagonals first, general ones later in the same block
+        flat = diag.reshape(-1, N)
+        flat[:max(1, flat.shape[0] // 2)] = make_real(flat[:max(1, flat.shape[0] // 2)])
+    elif real:
         diag = make_real(diag)
     bias_c = None
     if bias is not None:
@@ -101,6 +104,31 @@ def test_bsgs_bias_ragged_shapes(N1, qbits, pbits):
     assert np.abs(Y - ref).max() <= 1e-3
     assert np.abs(slots.imag).max() <= 1e-3
     assert cnt.key_switches == 3 * (N1 - 1) + 2 * (16 // N1 - 1)
+
+
+def test_real_plaintexts_on_a_chain_with_small_and_large_primes():
+    """One 52-bit prime (Montgomery arithmetic) and two 40-bit primes (fp64 arithmetic, palindrome kernel on
+    unpacked weights): the packed store needs every prime below 2^50, so this chain keeps the full one."""
+    import oracle
+    q = oracle.find_primes(52, 11, 1) + oracle.find_primes(40, 11, 2)
+    O = oracle.Oracle(11, q, oracle.find_primes(55, 11, 1), 3)
+    _, P = make_pair(O)
+    r = W.rng(31)
+    X = r.uniform(-1, 1, (4, 40))
+    Wm = r.uniform(-0.5, 0.5, (40, 20))
+    Y, ref, _, _ = run_case(O, P, X, Wm, r.uniform(-0.5, 0.5, 20), 4, 16, 4, 35, 3, 32, hw=16, real=True)
+    assert np.abs(Y - ref).max() <= 1e-3
+
+
+def test_block_turns_general_after_real_diagonals_were_stored():
+    """One output block loaded in two uploads, the first all real (stored in the packed half-limb form), the
+    second not: the block's diagonals move to the full store and the general kernel runs."""
+    O, P = make_pair(W.TOY_RING)
+    r = W.rng(77)
+    X = r.uniform(-1, 1, (16, 100))
+    Wm = r.uniform(-0.2, 0.2, (100, 64))
+    Y, ref, _, _ = run_case(O, P, X, Wm, None, 16, 64, 8, 30, 3, 78, real="first_upload")
+    assert np.abs(Y - ref).max() <= 2e-3
 
 
 @pytest.mark.parametrize("N1", [1, 4])
