@@ -19,6 +19,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+FP64_ISSUE_PEAK = 256 * 64 * 2.4e9      # fp64 vector instructions per second per lane-op: 256 CUs x 64 lanes x 2.4 GHz (78.6 TFLOP/s / 2)
 HBM_PEAK_GBS = 8000.0
 
 
@@ -437,13 +438,19 @@ def main():
     rot_ms = e0.elapsed_time(e1) / reps
     ks_per_s = len(steps) / rot_ms * 1e3 if steps else None
 
-    # algorithmic bytes of one diagonal multiply-accumulate launch: the bank once, the accumulators once, and
-    # of every weight limb the half that is not determined by the other half (the diagonals encode real slot
-    # vectors, whose transforms are palindromes), 8 bytes per residue
+    # algorithmic bytes of one diagonal multiply-accumulate launch: the bank once, the accumulators once (8 bytes
+    # per residue), and of every weight limb the half that is not determined by the other half (the diagonals
+    # encode real slot vectors, whose transforms are palindromes) in the packed store's 50 bits per residue
     limb_poly = 8 * N
-    mac_bytes = (G * n1 * B_out * N2 * level // 2 + G * n1 * 2 * level + B_out * N2 * 2 * level) * limb_poly
-    if args.fused_qk:   # the complex Q+iK blocks (half of the blocks) are read in full
-        mac_bytes += G * n1 * (B_out // 2) * N2 * level // 2 * limb_poly
+    half_limb_packed = 3 * N + N // 8
+    n_diag = G * n1 * B_out * N2
+    mac_bytes = n_diag * level * half_limb_packed + (G * n1 * 2 * level + B_out * N2 * 2 * level) * limb_poly
+    if args.fused_qk:   # the complex Q+iK blocks (half of the blocks) are read in full, 8 bytes per residue
+        n_cplx = G * n1 * (B_out // 2) * N2
+        mac_bytes += n_cplx * level * (limb_poly - half_limb_packed)
+    # the same launch in double-precision operations: 7 per residue product (exact product split, quotient,
+    # remainder, two additions), 4 products per stored weight residue
+    mac_ops = 7.0 * 4.0 * n_diag * level * (N // 2)
     achieved = mac_bytes / (mac_ms * 1e-3) / 1e9
     ks_bytes = 188.7e6
     traffic = read_traffic(spec.name, n1)
@@ -474,7 +481,8 @@ def main():
         "wall_s_timed_region": wall,
         "roofline": {"bound": "hbm", "kernel": "diag_mac_sym_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "bytes_per_launch": mac_bytes, "ms_per_launch": mac_ms},
+                     "bytes_per_launch": mac_bytes, "ms_per_launch": mac_ms,
+                     "fp64_issue_frac": mac_ops / (mac_ms * 1e-3) / FP64_ISSUE_PEAK},
     }
     if not args.no_cpu_baseline:
         t0 = time.time()
