@@ -135,9 +135,21 @@ size_t digits_words(const ckks_params *p, u32 level);
 size_t switch_scratch_words(const ckks_params *p, u32 level, u32 n_items);
 int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_digits, u64 *d_tmp, hipStream_t stream);
 int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream);
-int switch_accumulate(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_u, bool accumulate,
-                      hipStream_t stream);
 int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64 *d_w, hipStream_t stream);
+// Several rotations of n ciphertexts each, summed over the extended basis in one pass:
+//   u_r (+)= sum_i sum_j sigma_{g_i}(digits_{i,r,j}) * key_{i,j},   dst_r.c0 += sum_i sigma_{g_i}(c0_{i,r}),
+// r < n <= ROT_BATCH, i < n_rot <= MERGE_GROUP.  digits of (i, r) at d_digits + (i*n + r)*digits_words;
+// c0 of (i, r) at c0_base + r*c0_stride_r + c0_off[i]; dst_r at dst_base + r*dst_stride.
+constexpr u32 MERGE_GROUP = 8;
+struct MergedRot {
+    const u64 *key[MERGE_GROUP];
+    u64 galois_elt[MERGE_GROUP];
+    size_t c0_off[MERGE_GROUP];
+    u32 n_rot;
+};
+int switch_accumulate_merged(ckks_params *p, u32 level, const MergedRot &rots, u32 n, const u64 *d_digits,
+                             const u64 *c0_base, size_t c0_stride_r, u64 *dst_base, size_t dst_stride, u64 *d_u,
+                             bool accumulate, hipStream_t stream);
 // hoisted rotations of one ciphertext; the first reserve_words of the scratch arena are left to the caller
 size_t rotate_hoisted_scratch_words(const ckks_params *p, u32 level, u32 n_steps);
 int rotate_hoisted(ckks_params *p, const u64 *d_ct_in, u32 level, const int32_t *steps, u32 n_steps,

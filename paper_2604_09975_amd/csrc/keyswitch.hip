@@ -127,8 +127,7 @@ struct ItemPack {
 // no key), so that nothing but ModDown(u) is left to add later.
 __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack, u64 *__restrict__ u,
                                                                    const ModConst *__restrict__ mods, u32 level,
-                                                                   u32 K, u32 L, u32 beta, u32 logN, u32 accumulate,
-                                                                   u32 fold_c0) {
+                                                                   u32 K, u32 L, u32 beta, u32 logN) {
     const u32 N = 1u << logN;
     const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
     const u32 t = blockIdx.y;
@@ -161,18 +160,8 @@ __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack
         if (r < cnt) {
             u64 *u0 = u + (((size_t)(first + r) * 2 + 0) * Wl + t) * N + k;
             u64 *u1 = u + (((size_t)(first + r) * 2 + 1) * Wl + t) * N + k;
-            u64 v0 = redc_wide(a0[r], m), v1 = redc_wide(a1[r], m);
-            if (accumulate) {
-                v0 = add_mod(v0, *u0, m.q);
-                v1 = add_mod(v1, *u1, m.q);
-            }
-            *u0 = v0;
-            *u1 = v1;
-            if (fold_c0 && t < level) {
-                const SwitchItem &it = pack.it[first + r];
-                u64 *d = it.dst + (size_t)t * N + k;
-                *d = add_mod(*d, it.c0[(size_t)t * N + kp], m.q);
-            }
+            *u0 = redc_wide(a0[r], m);
+            *u1 = redc_wide(a1[r], m);
         }
     }
 }
@@ -180,6 +169,85 @@ __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack
 // y holds, per (item, component), the K special-limb rows y_k = INTT(u_{p_k}) * (P/p_k)^-1 in the coefficient
 // domain (the scaling comes out of the inverse transform); row (pc, k) starts at y + (pc*ystride + yoff + k)*N.
 // w_i = sum_k y_k * (P/p_k mod q_i) mod q_i for a chunk of target limbs i.
+// Inner products of several rotations summed in the extended basis (the merged giant step): a thread owns one
+// coefficient of one limb for MR ciphertexts, so that a key residue, read once, serves MR multiply-accumulates.
+// The 128-bit sums are folded before more than 16 products (each below 2^124) have been added.
+constexpr u32 MR = 3;
+__global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, const u64 *__restrict__ digits,
+                                                               size_t dig_w, const u64 *__restrict__ c0_base,
+                                                               size_t c0_stride_r, u64 *__restrict__ dst_base,
+                                                               size_t dst_stride, u64 *__restrict__ u,
+                                                               const ModConst *__restrict__ mods, u32 n, u32 level,
+                                                               u32 K, u32 L, u32 beta, u32 logN, u32 accumulate) {
+    const u32 N = 1u << logN;
+    const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
+    const u32 t = blockIdx.y;
+    const u32 r0 = blockIdx.z * MR;
+    const u32 Wl = level + K, Wt = L + K;
+    const u32 gl = t < level ? t : L + (t - level);
+    const ModConst m = mods[gl];
+    u128 a0[MR], a1[MR];
+    u64 s0[MR], s1[MR], cs[MR];
+#pragma unroll
+    for (u32 r = 0; r < MR; ++r) {
+        a0[r] = {0, 0};
+        a1[r] = {0, 0};
+        s0[r] = s1[r] = cs[r] = 0;
+    }
+    u32 terms = 0;
+    for (u32 i = 0; i < rots.n_rot; ++i) {
+        const u32 kp = galois_index(k, rots.galois_elt[i], logN);
+        const u64 *key = rots.key[i];
+        for (u32 j = 0; j < beta; ++j) {
+            const u64 k0 = __builtin_nontemporal_load(key + (((size_t)j * 2 + 0) * Wt + gl) * N + k);
+            const u64 k1 = __builtin_nontemporal_load(key + (((size_t)j * 2 + 1) * Wt + gl) * N + k);
+#pragma unroll
+            for (u32 r = 0; r < MR; ++r)
+                if (r0 + r < n) {
+                    const u64 d = digits[((size_t)i * n + r0 + r) * dig_w + ((size_t)j * Wl + t) * N + kp];
+                    mac(a0[r], d, k0);
+                    mac(a1[r], d, k1);
+                }
+        }
+        if (t < level) {
+#pragma unroll
+            for (u32 r = 0; r < MR; ++r)
+                if (r0 + r < n)
+                    cs[r] = add_mod(cs[r], c0_base[(size_t)(r0 + r) * c0_stride_r + rots.c0_off[i] + (size_t)t * N + kp],
+                                    m.q);
+        }
+        terms += beta;
+        if (terms + beta > 16 || i + 1 == rots.n_rot) {
+#pragma unroll
+            for (u32 r = 0; r < MR; ++r) {
+                s0[r] = add_mod(s0[r], redc_wide(a0[r], m), m.q);
+                s1[r] = add_mod(s1[r], redc_wide(a1[r], m), m.q);
+                a0[r] = {0, 0};
+                a1[r] = {0, 0};
+            }
+            terms = 0;
+        }
+    }
+#pragma unroll
+    for (u32 r = 0; r < MR; ++r) {
+        if (r0 + r < n) {
+            u64 *u0 = u + (((size_t)(r0 + r) * 2 + 0) * Wl + t) * N + k;
+            u64 *u1 = u + (((size_t)(r0 + r) * 2 + 1) * Wl + t) * N + k;
+            u64 v0 = s0[r], v1 = s1[r];
+            if (accumulate) {
+                v0 = add_mod(v0, *u0, m.q);
+                v1 = add_mod(v1, *u1, m.q);
+            }
+            *u0 = v0;
+            *u1 = v1;
+            if (t < level) {
+                u64 *d = dst_base + (size_t)(r0 + r) * dst_stride + (size_t)t * N + k;
+                *d = add_mod(*d, cs[r], m.q);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__restrict__ y, u64 *__restrict__ w,
                                                                   const ModConst *__restrict__ mods,
                                                                   const u64 *__restrict__ dn_mat, u32 level, u32 K,
@@ -435,22 +503,22 @@ static u32 build_pack(const SwitchItem *items, u32 n, ItemPack &pack) {
     return n_groups;
 }
 
-// Merged giant step, part 1: d_u[r] (+)= key inner product of item r over all level+K limbs (NTT domain),
-// dst_r.c0 += sigma_g(c0_r).  d_u [n][2][level+K][N].
-int switch_accumulate(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_u, bool accumulate,
-                      hipStream_t stream) {
-    if (n == 0) return CKKS_OK;
-    if (n > ROT_BATCH) {
-        set_error("switch_accumulate: %u items exceed one batch", n);
+// Merged giant step, part 1: d_u[r] (+)= the key inner products of rots.n_rot rotations of ciphertext r over all
+// level+K limbs (NTT domain), dst_r.c0 += the rotated c0 parts.  d_u [n][2][level+K][N].
+int switch_accumulate_merged(ckks_params *p, u32 level, const MergedRot &rots, u32 n, const u64 *d_digits,
+                             const u64 *c0_base, size_t c0_stride_r, u64 *dst_base, size_t dst_stride, u64 *d_u,
+                             bool accumulate, hipStream_t stream) {
+    if (n == 0 || rots.n_rot == 0) return CKKS_OK;
+    if (n > ROT_BATCH || rots.n_rot > MERGE_GROUP) {
+        set_error("switch_accumulate_merged: %u ciphertexts x %u rotations exceed one launch", n, rots.n_rot);
         return CKKS_E_INVAL;
     }
     const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
     const u32 beta = (level + p->alpha - 1) / p->alpha;
-    ItemPack pack;
-    const u32 n_groups = build_pack(items, n, pack);
-    hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n_groups), dim3(KS_THREADS), 0, stream, pack,
-                       d_u, p->d_mod, level, K, L, beta, p->logN, accumulate ? 1u : 0u, 1u);
-    CKKS_LAUNCH_CHECK("inner_product_kernel");
+    hipLaunchKernelGGL(merged_ip_kernel, dim3(N / KS_THREADS, Wl, (n + MR - 1) / MR), dim3(KS_THREADS), 0, stream, rots,
+                       d_digits, digits_words(p, level), c0_base, c0_stride_r, dst_base, dst_stride, d_u, p->d_mod, n,
+                       level, K, L, beta, p->logN, accumulate ? 1u : 0u);
+    CKKS_LAUNCH_CHECK("merged_ip_kernel");
     return CKKS_OK;
 }
 
@@ -463,7 +531,7 @@ int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64
     for (u32 r = 0; r < ROT_BATCH; ++r) {
         SwitchItem &it = pack.it[r];
         it.digits = nullptr;
-        it.c0 = nullptr;                       // already folded in by switch_accumulate
+        it.c0 = nullptr;                       // already folded in by switch_accumulate_merged
         it.key = nullptr;
         it.dst = dst[r < n ? r : 0];
         it.galois_elt = 1;
@@ -526,7 +594,7 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
     u64 *u = d_work;
     u64 *w = d_work + (size_t)n * 2 * Wl * N;
     hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n_groups), dim3(KS_THREADS), 0, stream, pack, u,
-                       p->d_mod, level, K, L, beta, p->logN, 0u, 0u);
+                       p->d_mod, level, K, L, beta, p->logN);
     CKKS_LAUNCH_CHECK("inner_product_kernel");
     for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
     int rc = launch_ntt(p, u, ids, Wl, n * 2 * Wl, true, stream, 3, true);

@@ -689,7 +689,10 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     const size_t bank_w = (size_t)GQ * ctw, acc_w = (size_t)BP * ctw;
     const bool merged = (flags & CKKS_MATMUL_MERGED_GIANT) && N2 > 1;
     const size_t u_w = merged ? (size_t)B * 2 * (level + P->K) * N : 0;   // extended-basis sums of the giant step
-    int rc = P->ensure_scratch((ks_w + bank_w + acc_w + u_w) * sizeof(u64), stream);
+    // merged giant step: the digits of up to MERGE_GROUP rotations of one batch of blocks are held together
+    const u32 mg_rots = merged ? std::min<u32>(MERGE_GROUP, N2 - 1) : 0;
+    const size_t mg_w = (size_t)mg_rots * std::min(batch, B) * dig_w;
+    int rc = P->ensure_scratch((ks_w + bank_w + acc_w + u_w + mg_w) * sizeof(u64), stream);
     if (rc) return rc;
     u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + batch * tmp_w;
     u64 *d_bank = (u64 *)P->d_scratch + ks_w, *d_acc = d_bank + bank_w;
@@ -793,9 +796,50 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     for (u32 b = 0; b < B; ++b)
         CKKS_HIP(hipMemcpyAsync(d_ct_y + (size_t)b * ctw, d_acc + (size_t)b * N2 * ctw, ctw * sizeof(u64),
                                 hipMemcpyDeviceToDevice, stream));
-    u64 *d_u = d_acc + acc_w;
-    bool u_started = false;
-    for (u32 p = 1; p < N2; ++p) {
+    u64 *d_u = d_acc + acc_w, *d_mdig = d_u + u_w;
+    if (merged) {
+        // rotations that are a full turn are plain additions; the others are grouped: the accumulators of a
+        // group are decomposed, then one pass sums their switched forms over the extended basis; one ModDown
+        // per block follows
+        std::vector<u32> ps;
+        for (u32 p = 1; p < N2; ++p) {
+            if (giant_g[p] != 1) {
+                ps.push_back(p);
+                continue;
+            }
+            for (u32 b = 0; b < B; ++b) {
+                hipLaunchKernelGGL(add_rows_kernel, dim3(N / EW_THREADS, 2 * level), dim3(EW_THREADS), 0, stream,
+                                   d_ct_y + (size_t)b * ctw, d_acc + ((size_t)b * N2 + p) * ctw, P->d_mod, level, N);
+                CKKS_LAUNCH_CHECK("add_rows_kernel");
+            }
+        }
+        for (u32 b0 = 0; !ps.empty() && b0 < B; b0 += batch) {
+            const u32 nb = std::min(batch, B - b0);
+            u64 *u_b = d_u + (size_t)b0 * 2 * (level + P->K) * N;
+            for (size_t i0 = 0; i0 < ps.size(); i0 += mg_rots) {
+                MergedRot rots;
+                rots.n_rot = (u32)std::min<size_t>(mg_rots, ps.size() - i0);
+                for (u32 i = 0; i < rots.n_rot; ++i) {
+                    const u32 p = ps[i0 + i];
+                    const u64 *c1s[ROT_BATCH];
+                    for (u32 r = 0; r < nb; ++r) c1s[r] = d_acc + ((size_t)(b0 + r) * N2 + p) * ctw + (size_t)level * N;
+                    rc = decompose(P, c1s, nb, level, d_mdig + (size_t)i * nb * dig_w, d_tmp, stream);
+                    if (rc) return rc;
+                    rots.key[i] = giant_keys[p - 1]->d_key;
+                    rots.galois_elt[i] = giant_g[p];
+                    rots.c0_off[i] = (size_t)p * ctw;
+                }
+                rc = switch_accumulate_merged(P, level, rots, nb, d_mdig, d_acc + (size_t)b0 * N2 * ctw,
+                                              (size_t)N2 * ctw, d_ct_y + (size_t)b0 * ctw, ctw, u_b, i0 > 0, stream);
+                if (rc) return rc;
+            }
+            u64 *dsts[ROT_BATCH];
+            for (u32 r = 0; r < nb; ++r) dsts[r] = d_ct_y + (size_t)(b0 + r) * ctw;
+            rc = moddown_add(P, level, u_b, dsts, nb, d_work, stream);
+            if (rc) return rc;
+        }
+    }
+    for (u32 p = 1; !merged && p < N2; ++p) {
         for (u32 b0 = 0; b0 < B; b0 += batch) {
             const u32 nb = std::min(batch, B - b0);
             if (giant_g[p] == 1) {   // a full turn: plain addition
@@ -821,21 +865,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                 items[r].galois_elt = giant_g[p];
                 items[r].accumulate = 1;
             }
-            if (merged)   // keep the switched accumulators in the extended basis; one ModDown per block follows
-                rc = switch_accumulate(P, level, items, nb, d_u + (size_t)b0 * 2 * (level + P->K) * N, u_started,
-                                       stream);
-            else
-                rc = switch_batch(P, level, items, nb, d_work, stream);
-            if (rc) return rc;
-        }
-        if (merged && giant_g[p] != 1) u_started = true;
-    }
-    if (merged && u_started) {
-        for (u32 b0 = 0; b0 < B; b0 += batch) {
-            const u32 nb = std::min(batch, B - b0);
-            u64 *dsts[ROT_BATCH];
-            for (u32 r = 0; r < nb; ++r) dsts[r] = d_ct_y + (size_t)(b0 + r) * ctw;
-            rc = moddown_add(P, level, d_u + (size_t)b0 * 2 * (level + P->K) * N, dsts, nb, d_work, stream);
+            rc = switch_batch(P, level, items, nb, d_work, stream);
             if (rc) return rc;
         }
     }
