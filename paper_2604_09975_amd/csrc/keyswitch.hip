@@ -266,7 +266,7 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__r
 #pragma unroll
         for (u32 k = 0; k < MAX_DIGIT; ++k)
             if (k < K) mac(acc, yk[k], dn_mat[(size_t)k * L + i]);
-        w[((size_t)pc * level + i) * N + n] = redc(acc, mods[i]);
+        w[((size_t)pc * level + i) * N + n] = redc_wide(acc, mods[i]);   // up to 16 products below 2^62 * q each
     }
 }
 

@@ -44,11 +44,31 @@ def test_toy_ring_lower_levels(level):
     _run(O, P, level, [1, "conj", 7], 12 + level, 2.0**30)
 
 
-@pytest.mark.parametrize("L,K,dnum,level", [(4, 2, 2, 4), (4, 2, 2, 3), (6, 3, 2, 5), (6, 2, 3, 2), (6, 3, 1, 6)])
+@pytest.mark.parametrize("L,K,dnum,level", [(4, 2, 2, 4), (4, 2, 2, 3), (6, 3, 2, 5), (6, 2, 3, 2), (6, 3, 1, 6), (12, 4, 1, 12), (12, 12, 1, 11), (16, 16, 1, 16)])
 def test_multi_limb_digits_and_partial_last_digit(L, K, dnum, level):
     O = helpers.small_oracle(10, L=L, K=K, dnum=dnum, qbits=40, pbits=45)
     _, P = make_pair(O)
     _run(O, P, level, [1, 2, "conj", 0, 33], L * 7 + level, 2.0**30, hw=16)
+
+
+def test_largest_primes_and_widest_digits():
+    """16-limb digit and 16 special primes at the largest prime size the library admits for them (16 lazy
+    products must stay below 2^64 times the modulus: primes below 2^60), and the refusal one bit above."""
+    B = _B()
+    O = helpers.small_oracle(10, L=16, K=16, dnum=1, qbits=58, pbits=59)
+    _, P = make_pair(O)
+    _run(O, P, 16, [1, "conj"], 5, 2.0**40, hw=16)
+    O = helpers.small_oracle(10, L=4, K=16, dnum=2, qbits=58, pbits=59)
+    _, P = make_pair(O)
+    _run(O, P, 3, [3], 6, 2.0**40, hw=16)
+    import oracle
+    with pytest.raises(B.CkksError) as err:
+        B.ckks_params_create(10, oracle.find_primes(60, 10, 16), oracle.find_primes(61, 10, 16), 1)
+    assert err.value.code == -1
+    # 61-bit primes are fine with narrow digits
+    O = helpers.small_oracle(10, L=4, K=2, dnum=2, qbits=60, pbits=61)
+    _, P = make_pair(O)
+    _run(O, P, 4, [2], 7, 2.0**40, hw=16)
 
 
 def test_more_steps_than_one_batch():
