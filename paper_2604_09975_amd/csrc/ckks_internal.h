@@ -51,6 +51,7 @@ struct LevelTables {
     u32 level = 0, beta = 0;
     u64 *d_up_inv = nullptr;   // [level]: ((Q_D/q_i)^-1 mod q_i), Montgomery form, D = digit of i
     u64 *d_up_mat = nullptr;   // [level][level+K]: (Q_D/q_i mod t), Montgomery form w.r.t. t; 0 for t in D
+    u64 *d_up_matf = nullptr;  // the same factors as doubles (bit patterns), for the conversions done in fp64
 };
 
 }  // namespace ckks

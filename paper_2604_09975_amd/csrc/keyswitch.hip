@@ -52,8 +52,10 @@ template <u32 AMAX, u32 VEC>
 __global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, const u64 *__restrict__ c1_coeff,
                                                            u64 *__restrict__ digits,
                                                            const ModConst *__restrict__ mods,
+                                                           const ModFp *__restrict__ modf,
                                                            const u64 *__restrict__ up_inv,
-                                                           const u64 *__restrict__ up_mat, u32 level, u32 K, u32 L,
+                                                           const u64 *__restrict__ up_mat,
+                                                           const u64 *__restrict__ up_matf, u32 level, u32 K, u32 L,
                                                            u32 alpha, u32 N, u32 chunks, u32 beta, u32 up_chunk) {
     typedef u64 vec_t __attribute__((ext_vector_type(2)));
     const u32 n = (blockIdx.x * KS_THREADS + threadIdx.x) * VEC;
@@ -79,6 +81,18 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, cons
             }
         }
     }
+    // Targets below 2^50 fed by a digit of primes below 2^50 are converted in fp64 (twice the multiply rate of
+    // the 32-bit integer pipeline): y is exact in a double, every product is split exactly into h + l and
+    // brought below 0.9 q before it is added, and the partial sum is reduced every four terms (below 2^53).
+    bool digit_fp = true;
+#pragma unroll
+    for (u32 a = 0; a < AMAX; ++a)
+        if (lo + a < hi) digit_fp = digit_fp && modf[lo + a].ok;
+    double yd[AMAX][VEC];
+#pragma unroll
+    for (u32 a = 0; a < AMAX; ++a)
+#pragma unroll
+        for (u32 e = 0; e < VEC; ++e) yd[a][e] = digit_fp ? (double)y[a][e] : 0.0;
     const u32 t0 = chunk * up_chunk, t1 = min(t0 + up_chunk, Wl);
     for (u32 t = t0; t < t1; ++t) {
         u64 *dst = dig + ((size_t)j * Wl + t) * N + n;
@@ -89,6 +103,36 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, cons
             continue;
         }
         const u32 gl = t < level ? t : L + (t - level);
+        if (digit_fp && modf[gl].ok) {
+            const double q = modf[gl].q, u = modf[gl].u;
+            double fd[AMAX], acc[VEC];
+#pragma unroll
+            for (u32 a = 0; a < AMAX; ++a)
+                fd[a] = lo + a < hi ? __longlong_as_double((long long)up_matf[(size_t)(lo + a) * Wl + t]) : 0.0;
+#pragma unroll
+            for (u32 e = 0; e < VEC; ++e) acc[e] = 0.0;
+#pragma unroll
+            for (u32 a = 0; a < AMAX; ++a) {
+#pragma unroll
+                for (u32 e = 0; e < VEC; ++e) {
+                    const double h = yd[a][e] * fd[a], l = fma(yd[a][e], fd[a], -h);
+                    acc[e] += fma(-rint(h * u), q, h) + l;
+                    if ((a & 3) == 3) acc[e] = fma(-rint(acc[e] * u), q, acc[e]);
+                }
+            }
+#pragma unroll
+            for (u32 e = 0; e < VEC; e += 2) {
+                vec_t o;
+#pragma unroll
+                for (u32 z = 0; z < 2; ++z) {
+                    double v = fma(-rint(acc[e + z] * u), q, acc[e + z]);
+                    if (v < 0) v += q;
+                    o[z] = (u64)v;
+                }
+                *reinterpret_cast<vec_t *>(dst + e) = o;
+            }
+            continue;
+        }
         u64 f[AMAX];
 #pragma unroll
         for (u32 a = 0; a < AMAX; ++a) f[a] = lo + a < hi ? up_mat[(size_t)(lo + a) * Wl + t] : 0;
@@ -456,8 +500,8 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
     const u32 chunks = (Wl + UP_CHUNK - 1) / UP_CHUNK;
 #define MODUP_LAUNCH(A)                                                                                             \
     hipLaunchKernelGGL((modup_kernel<A, 2>), dim3(N / KS_THREADS / 2, beta, n * chunks), dim3(KS_THREADS), 0, stream, \
-                       src, d_tmp, d_digits, p->d_mod, lt->d_up_inv, lt->d_up_mat, level, K, L, alpha, N, chunks,   \
-                       beta, UP_CHUNK)
+                       src, d_tmp, d_digits, p->d_mod, p->d_modf, lt->d_up_inv, lt->d_up_mat, lt->d_up_matf, level, \
+                       K, L, alpha, N, chunks, beta, UP_CHUNK)
     if (alpha <= 8)
         MODUP_LAUNCH(8);
     else

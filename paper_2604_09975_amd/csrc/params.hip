@@ -1,6 +1,7 @@
 // Host side of a parameter set: validation of the modulus chain, roots of
 // unity, twiddle tables and base-conversion tables (all uploaded in Montgomery
 // form), and the private scratch arena.
+#include <cstring>
 #include <stdarg.h>
 #include <stdio.h>
 
@@ -141,7 +142,7 @@ int ckks_params::level_tables(u32 level, const LevelTables **out) {
     t.level = level;
     t.beta = (level + alpha - 1) / alpha;
     u32 Wl = level + K;
-    std::vector<u64> inv(level), mat((size_t)level * Wl, 0);
+    std::vector<u64> inv(level), mat((size_t)level * Wl, 0), matf((size_t)level * Wl, 0);
     for (u32 i = 0; i < level; ++i) {
         u32 lo = (i / alpha) * alpha, hi = std::min(lo + alpha, level);
         u64 qi = mod[i], prod = 1;
@@ -155,11 +156,15 @@ int ckks_params::level_tables(u32 level, const LevelTables **out) {
             for (u32 b = lo; b < hi; ++b)
                 if (b != i) f = hmul(f, mod[b] % mt, mt);
             mat[(size_t)i * Wl + t2] = to_mont(f, hmod[gl]);
+            const double fd = (double)f;      // exact below 2^53; read only for targets below 2^50
+            std::memcpy(&matf[(size_t)i * Wl + t2], &fd, sizeof fd);
         }
     }
     int rc = upload(&t.d_up_inv, inv);
     if (rc) return rc;
     rc = upload(&t.d_up_mat, mat);
+    if (rc) return rc;
+    rc = upload(&t.d_up_matf, matf);
     if (rc) return rc;
     auto ins = levels.emplace(level, t);
     *out = &ins.first->second;
@@ -365,6 +370,7 @@ void ckks_params_destroy(ckks_params_t *P) {
     for (auto &kv : P->levels) {
         hipFree(kv.second.d_up_inv);
         hipFree(kv.second.d_up_mat);
+        hipFree(kv.second.d_up_matf);
     }
     hipFree(P->d_scratch);
     for (hipEvent_t ev : P->prof_ev) hipEventDestroy(ev);
