@@ -42,6 +42,28 @@ __global__ __launch_bounds__(KS_THREADS) void gather_c1_kernel(PtrPack src, u64 
     tmp[((size_t)r * level + i) * N + n] = src.p[r][(size_t)i * N + n];
 }
 
+// The same collection fused with the first pass of the inverse transform (rings with the two-pass kernels):
+// reads the c1 halves where they are, writes tmp[r][i] half transformed.  grid: x = 4096-residue tiles,
+// y = r * level + i.
+__global__ __launch_bounds__(NTT_THREADS) void gather_intt_kernel(PtrPack src, u64 *__restrict__ tmp,
+                                                                  const ModConst *__restrict__ mods,
+                                                                  const ModFp *__restrict__ modf,
+                                                                  const u64 *__restrict__ tw,
+                                                                  const double *__restrict__ twf,
+                                                                  const u64 *__restrict__ ninv, u32 level, u32 logN) {
+    __shared__ u64 lds[FAST_LDS_WORDS];
+    const u32 r = blockIdx.y / level, i = blockIdx.y % level;
+    const u64 *in = src.p[r] + ((size_t)i << logN);
+    u64 *out = tmp + ((size_t)blockIdx.y << logN);
+    auto load = [&](u32 idx) { return in[idx]; };
+    auto store = [&](u32 idx, u64 v) { out[idx] = v; };
+    const ModFp mf = modf[i];
+    if (mf.ok)
+        pass_b_body<true>(make_field_fp(mf, twf, i, logN), logN, lds, load, store);
+    else
+        pass_b_body<true>(make_field_int(mods, tw, ninv, i, logN), logN, lds, load, store);
+}
+
 // Per ciphertext r and digit j: y_i = c_i * (Q_D/q_i)^-1 mod q_i for the limbs of the digit, then for
 // every target t outside the digit out_t = sum_i y_i * (Q_D/q_i mod t) mod t (coefficient domain).
 // Targets inside the digit are copied from the NTT-domain input (they need no transform).
@@ -490,12 +512,20 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
     const u32 beta = lt->beta;
     PtrPack src;
     for (u32 r = 0; r < ROT_BATCH; ++r) src.p[r] = c1[r < n ? r : 0];
-    hipLaunchKernelGGL(gather_c1_kernel, dim3(N / KS_THREADS, level, n), dim3(KS_THREADS), 0, stream, src, d_tmp,
-                       level, N);
-    CKKS_LAUNCH_CHECK("gather_c1_kernel");
     LimbIds ids;
     for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
-    rc = launch_ntt(p, d_tmp, ids, level, n * level, true, stream);
+    if (fast_ring(p)) {
+        hipLaunchKernelGGL(gather_intt_kernel, dim3(N >> 12, n * level), dim3(NTT_THREADS), 0, stream, src, d_tmp,
+                           p->d_mod, p->d_modf, p->d_tw_inv, p->d_twf_inv, p->d_ninv, level, p->logN);
+        CKKS_LAUNCH_CHECK("gather_intt_kernel");
+        p->limb_ntts += (u64)n * level;
+        rc = launch_ntt(p, d_tmp, ids, level, n * level, true, stream, 2);
+    } else {
+        hipLaunchKernelGGL(gather_c1_kernel, dim3(N / KS_THREADS, level, n), dim3(KS_THREADS), 0, stream, src, d_tmp,
+                           level, N);
+        CKKS_LAUNCH_CHECK("gather_c1_kernel");
+        rc = launch_ntt(p, d_tmp, ids, level, n * level, true, stream);
+    }
     if (rc) return rc;
     const u32 chunks = (Wl + UP_CHUNK - 1) / UP_CHUNK;
 #define MODUP_LAUNCH(A)                                                                                             \
