@@ -479,6 +479,9 @@ def main():
     half_limb_packed = 3 * N + N // 8
     n_diag = G * n1 * B_out * N2
     mac_bytes = n_diag * level * half_limb_packed + (G * n1 * 2 * level + B_out * N2 * 2 * level) * limb_poly
+    # the same count with unpacked half limbs (8 bytes per residue), the unit the byte budget of the method is
+    # usually stated in
+    mac_bytes_8 = (n_diag * level // 2 + G * n1 * 2 * level + B_out * N2 * 2 * level) * limb_poly
     if args.fused_qk:   # the complex Q+iK blocks (half of the blocks) are read in full, 8 bytes per residue
         n_cplx = G * n1 * (B_out // 2) * N2
         mac_bytes += n_cplx * level * (limb_poly - half_limb_packed)
@@ -517,7 +520,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "diag_mac_sym_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": mac_bytes, "ms_per_launch": mac_ms,
-                     "fp64_issue_frac": mac_ops / (mac_ms * 1e-3) / FP64_ISSUE_PEAK},
+                     "fp64_issue_frac": mac_ops / (mac_ms * 1e-3) / FP64_ISSUE_PEAK,
+                     "frac_at_8_bytes_per_residue": mac_bytes_8 / (mac_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
     if not args.no_cpu_baseline:
         t0 = time.time()
