@@ -485,6 +485,7 @@ def main():
     if args.fused_qk:   # the complex Q+iK blocks (half of the blocks) are read in full, 8 bytes per residue
         n_cplx = G * n1 * (B_out // 2) * N2
         mac_bytes += n_cplx * level * (limb_poly - half_limb_packed)
+        mac_bytes_8 += n_cplx * level * limb_poly // 2
     # the same launch in double-precision operations: 7 per residue product (exact product split, quotient,
     # remainder, two additions), 4 products per stored weight residue
     mac_ops = 7.0 * 4.0 * n_diag * level * (N // 2)
