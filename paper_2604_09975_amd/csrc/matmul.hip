@@ -138,10 +138,16 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
 // Workgroups go to the XCDs round-robin and each XCD has its own L2, so when the run count allows it the
 // linear workgroup id is unfolded to let one XCD walk all (b,p) tiles of a run of coefficients back to
 // back: the bank lines of that run are then fetched into one L2 once.
-// PACKED: the half limb is stored in 50 bits per residue instead of 64 (packed_record_bytes): three planes,
+// PACKED: the half limb is stored in 50 bits per residue instead of 64 (packed_record_bytes) in three parts,
 // the low 32 bits, bits 32..47, and bits 48..49 four residues to a byte.  The double is rebuilt as
 // (2^52 + x) - 2^52 from the bit pattern, one addition per weight.
 __host__ __device__ inline size_t packed_record_bytes(u32 N) { return (size_t)3 * N + N / 8; }
+// A record is a sequence of 800-byte chunks of 128 residues (what one wavefront reads per weight limb and step):
+// 512 bytes of low words, 256 of middle halves, 32 of top bits, so that the three loads of a wavefront fall into
+// one contiguous piece of memory.  Byte offsets of residue k's parts within the record:
+__host__ __device__ inline u32 packed_lo(u32 k) { return (k >> 7) * 800u + 4u * (k & 127u); }
+__host__ __device__ inline u32 packed_hi(u32 k) { return (k >> 7) * 800u + 512u + 2u * (k & 127u); }
+__host__ __device__ inline u32 packed_top(u32 k) { return (k >> 7) * 800u + 768u + ((k & 127u) >> 2); }
 
 template <u32 TB, bool PACKED>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__restrict__ bank,
@@ -175,7 +181,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
     wvec_t wb[TB];
     const size_t rec = packed_record_bytes(N);
     const unsigned char *wbytes = reinterpret_cast<const unsigned char *>(w);
-    const u32 off_lo = 4 * k, off_hi = 2 * N + 2 * k, off_top = 3 * N + (k >> 2);
+    const u32 off_lo = packed_lo(k), off_hi = packed_hi(k), off_top = packed_top(k);
     auto fetch = [&](u32 gq) {
 #pragma unroll
         for (u32 c = 0; c < 2; ++c) {
@@ -304,9 +310,9 @@ __global__ __launch_bounds__(EW_THREADS) void pack_half_kernel(const u64 *__rest
     lo.w = (u32)x3;
     hi.x = (u32)((x0 >> 32) & 0xffff) | ((u32)((x1 >> 32) & 0xffff) << 16);
     hi.y = (u32)((x2 >> 32) & 0xffff) | ((u32)((x3 >> 32) & 0xffff) << 16);
-    *reinterpret_cast<uint4 *>(r + (size_t)4 * k) = lo;
-    *reinterpret_cast<uint2 *>(r + (size_t)2 * N + (size_t)2 * k) = hi;
-    r[(size_t)3 * N + (k >> 2)] =
+    *reinterpret_cast<uint4 *>(r + packed_lo(k)) = lo;
+    *reinterpret_cast<uint2 *>(r + packed_hi(k)) = hi;
+    r[packed_top(k)] =
         (unsigned char)(((x0 >> 48) & 3) | (((x1 >> 48) & 3) << 2) | (((x2 >> 48) & 3) << 4) | (((x3 >> 48) & 3) << 6));
 }
 
@@ -316,9 +322,9 @@ __global__ __launch_bounds__(EW_THREADS) void unpack_half_kernel(const unsigned 
     const u32 k = blockIdx.x * EW_THREADS + threadIdx.x;
     if (k >= N / 2) return;
     const unsigned char *r = in + (size_t)blockIdx.y * packed_record_bytes(N);
-    const u64 lo = *reinterpret_cast<const u32 *>(r + (size_t)4 * k);
-    const u64 hi = *reinterpret_cast<const unsigned short *>(r + (size_t)2 * N + (size_t)2 * k);
-    const u64 top = (r[(size_t)3 * N + (k >> 2)] >> ((k & 3) * 2)) & 3;
+    const u64 lo = *reinterpret_cast<const u32 *>(r + packed_lo(k));
+    const u64 hi = *reinterpret_cast<const unsigned short *>(r + packed_hi(k));
+    const u64 top = (r[packed_top(k)] >> ((k & 3) * 2)) & 3;
     const u64 x = lo | (hi << 32) | (top << 48);
     const u64 d = (u64)__double_as_longlong((double)x);
     out[(size_t)blockIdx.y * N + k] = d;
