@@ -336,6 +336,33 @@ def run_primitives(args, B, CL, W, P, cl):
         err = float(np.abs(cl.decrypt_slots(o1[0], level, 2.0 ** 40) - np.roll(za, -1)).max())
         assert err < 585 * P.N / 2.0 ** 40, err
         res["limbs_%d" % level] = out
+        if level == P.L:
+            # bank of 16 intra-segment shifts Psi^t (m = 128): 32 rotations from one decomposition + masks
+            m, ts = 128, list(range(1, 17))
+            steps, masks = [], []
+            for t in ts:
+                h, u, st = CL.psi_masks(n, m, t)
+                steps += list(st)
+                masks += [cl.enc.encode(h, 2.0 ** 40), cl.enc.encode(u, 2.0 ** 40)]
+            keymap = {s: cl.galois_key(s) for s in sorted(set(steps))}
+            d_masks = B.ckks_plain_expand(P, level, cl._dev(np.stack(masks))).reshape(len(ts), 2, level, P.N)
+            bank = torch.empty((len(ts), 2, level, P.N), dtype=torch.int64, device="cuda")
+            f = lambda: B.ckks_shift_bank(P, ca, level, steps, [keymap[s] for s in steps], d_masks, bank)
+            f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(max(args.steps, 1)):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            bank_ms = e0.elapsed_time(e1) / max(args.steps, 1)
+            bl = B.ckks_rescale(P, bank, level, len(ts))
+            zz = cl.decrypt_slots(bl[4], level - 1, 2.0 ** 80 / P.q[level - 1])
+            want = np.roll(za.reshape(n // m, m), -ts[4], axis=1).reshape(n)
+            err = float(np.abs(zz - want).max())
+            assert err < 1e-5, err
+            res["psi_bank_16_shifts"] = {"ms": bank_ms, "key_switches": len(steps), "max_abs_err": err}
     top = res["limbs_%d" % P.L]
     print(json.dumps({
         "metric": "ctmul latency ms at N=2^16 L=24 (tensor + relinearisation)", "value": top["ctmul"], "unit": "ms",

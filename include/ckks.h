@@ -189,6 +189,19 @@ int ckks_ptmul(const ckks_params_t *params, const uint64_t *d_ct, uint32_t level
 int ckks_mod_switch_to_next(const ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct,
                             uint64_t *d_ct_out, void *stream);
 
+/* Bank of masked rotation pairs of ONE ciphertext (the rotation banks of Sec. 3.1 / 3.3 with the shift
+ * realisations of App. A.1):
+ *   out_i = rot(x; steps[2i]) (.) mask_{2i} + rot(x; steps[2i+1]) (.) mask_{2i+1},   i < n_out.
+ * The intra-segment shift Psi^t is the instance steps = (t mod m, (t mod m - m) mod n) with the masks
+ * H = 1{r < m - t}, U = 1{r >= m - t} on slot s*m + r; RotFirst_L and Phi_C^Delta are instances too (below).  All
+ * 2*n_out rotations share the input's decomposition (hoisting).  steps (host, as in ckks_galois_elt), keys (host
+ * array of 2*n_out handles; NULL only where the step is the identity), d_masks [n_out][2][level][N] plaintexts from
+ * ckks_plain_expand at one scale; d_ct_out [n_out][2][level][N], may not alias the input.  scale(out) =
+ * scale(x)*scale(mask): follow with ckks_rescale.  Errors as ckks_rotate_hoisted. */
+int ckks_shift_bank(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level, uint32_t n_out,
+                    const int32_t *steps, const ckks_gkey_t *const *keys, const uint64_t *d_masks,
+                    uint64_t *d_ct_out, void *stream);
+
 /* RotFirst_L(x; tau) of App. A.1: cyclic LEFT shift by tau (mod L) inside the first L slots,
  *   rot(x; tau) (.) a + rot(x; (tau - L) mod n) (.) b,
  * a = 1{0 <= i < L - tau}, b = 1{L - tau <= i < L} given by the caller as plaintexts d_mask_a, d_mask_b

@@ -61,6 +61,7 @@ def _lib():
     lib.orc_ptmul.argtypes = [C.c_void_p, _u64p, C.c_int, _u64p, _u64p]
     lib.orc_mod_switch.argtypes = [C.c_void_p, _u64p, C.c_int, C.c_int, _u64p]
     lib.orc_rot_first.argtypes = [C.c_void_p, _u64p, C.c_int, _u64p, C.POINTER(_u64p), _u64p, _u64p, _u64p]
+    lib.orc_shift_bank.argtypes = [C.c_void_p, _u64p, C.c_int, C.c_int, _u64p, C.POINTER(_u64p), _u64p, _u64p]
     lib.orc_relin_keygen.argtypes = [C.c_void_p, _i8p, _u64p, _i64p, _u64p]
     lib.orc_ctmul.argtypes = [C.c_void_p, _u64p, _u64p, C.c_int, _u64p, _u64p]
     lib.orc_encrypt.argtypes = [C.c_void_p, C.c_int, _i64p, _i8p, _u64p, _i64p, _u64p]
@@ -308,6 +309,26 @@ class Oracle:
         b_, bp = _u64(mask_b)
         out = np.zeros_like(c_)
         LIB.orc_rot_first(self._h, cp, level, gp, kp, ap, bp, out.ctypes.data_as(_u64p))
+        return out
+
+    def shift_bank(self, ct, level, gelts, keys, masks):
+        """gelts, keys: n_out pairs; masks [n_out][2][level][N] -> [n_out][2][level][N]."""
+        c_, cp = _u64(ct)
+        n_out = len(gelts)
+        g_, gp = _u64(np.array(gelts, dtype=np.uint64).reshape(-1))
+        keep, kp = [], (_u64p * (2 * n_out))()
+        for i, pair in enumerate(keys):
+            for e, k in enumerate(pair):
+                if k is None:
+                    kp[2 * i + e] = None
+                else:
+                    ka, kptr = _u64(k)
+                    keep.append(ka)
+                    kp[2 * i + e] = kptr
+        m_, mp = _u64(masks)
+        assert m_.shape == (n_out, 2, level, self.N)
+        out = np.zeros((n_out, 2, level, self.N), dtype=np.uint64)
+        LIB.orc_shift_bank(self._h, cp, level, n_out, gp, kp, mp, out.ctypes.data_as(_u64p))
         return out
 
     def relin_keygen(self, s, a, e):

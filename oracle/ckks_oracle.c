@@ -663,6 +663,26 @@ void orc_rot_first(const orc_ctx *c, const u64 *ct, int level, const u64 *gelts,
     free(tmp); free(rot);
 }
 
+/* Bank of masked rotation pairs from ONE input (Sec. 3.1 "rotation banks", App. A.1):
+ *   out_i = rot(x; step_{i,0}) (.) mask_{i,0} + rot(x; step_{i,1}) (.) mask_{i,1},   i < n_out.
+ * Psi^t (intra-segment shift), RotFirst_L and Phi_C^Delta are instances with their own masks and steps.
+ * All 2*n_out rotations share the input's decomposition (hoisting).  gelts, keys: [n_out][2]; masks
+ * [n_out][2][level][N] expanded plaintexts. */
+void orc_shift_bank(const orc_ctx *c, const u64 *ct, int level, int n_out, const u64 *gelts, const u64 *const *keys,
+                    const u64 *masks, u64 *out) {
+    u64 N = c->N;
+    u64 ctw = (u64)2 * level * N, ptw = (u64)level * N;
+    u64 *rot = (u64 *)malloc(sizeof(u64) * 2 * n_out * ctw);
+    u64 *tmp = (u64 *)malloc(sizeof(u64) * ctw);
+    orc_rotate_hoisted(c, ct, level, gelts, 2 * n_out, keys, rot);
+    for (int i = 0; i < n_out; i++) {
+        orc_ptmul(c, rot + (u64)(2 * i) * ctw, level, masks + (u64)(2 * i) * ptw, out + (u64)i * ctw);
+        orc_ptmul(c, rot + (u64)(2 * i + 1) * ctw, level, masks + (u64)(2 * i + 1) * ptw, tmp);
+        orc_add(c, out + (u64)i * ctw, tmp, level, 1, out + (u64)i * ctw);
+    }
+    free(tmp); free(rot);
+}
+
 /* ------------------------------------------------------------------ */
 /* client side used by the tests: keys, encryption, decryption         */
 /* ------------------------------------------------------------------ */

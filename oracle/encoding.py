@@ -243,3 +243,18 @@ def rot_first_masks(n, L, tau):
     a = ((i >= 0) & (i < L - tau)).astype(np.float64)
     b = ((i >= L - tau) & (i < L)).astype(np.float64)
     return a, b, (tau, (tau - L) % n)
+
+
+def psi_masks(n, m, t):
+    """Masks and rotation steps of the intra-segment shift Psi^t (App. A.1): H_{r,s} = 1{0 <= r < m - t},
+    U_{r,s} = 1{m - t <= r < m} on slot s*m + r, steps (t, (t - m) mod n) with t taken mod m."""
+    t %= m
+    r = np.arange(n) % m
+    return (r < m - t).astype(np.float64), (r >= m - t).astype(np.float64), (t, (t - m) % n)
+
+
+def psi_shift(x, m, t):
+    """Psi^t on a slot vector by its definition (Sec. 3.1): slot s*m + r takes the value of slot s*m + (r+t) mod m."""
+    n = len(x)
+    X = np.asarray(x).reshape(n // m, m)          # X[s][r]
+    return np.roll(X, -(t % m), axis=1).reshape(n)

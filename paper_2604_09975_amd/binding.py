@@ -53,6 +53,7 @@ _SIGS = {
     "ckks_add": [_vp, _vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
     "ckks_ptmul": [_vp, _vp, C.c_uint32, _vp, _vp, _vp],
     "ckks_mod_switch_to_next": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
+    "ckks_shift_bank": [_vp, _vp, C.c_uint32, C.c_uint32, C.POINTER(C.c_int32), C.POINTER(_vp), _vp, _vp, _vp],
     "ckks_rot_first": [_vp, _vp, C.c_uint32, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp, _vp],
 }
 for _n, _a in _SIGS.items():
@@ -290,6 +291,21 @@ def ckks_mod_switch_to_next(P, d_ct_in, level_in, n_ct, d_ct_out=None):
     if d_ct_out is None:
         d_ct_out = torch.empty((n_ct, 2, max(level_in - 1, 1), P.N), dtype=torch.int64, device=d_ct_in.device)
     _check(lib.ckks_mod_switch_to_next(P.h, _dev(d_ct_in), level_in, n_ct, _dev(d_ct_out), _stream()))
+    return d_ct_out
+
+
+def ckks_shift_bank(P, d_ct_in, level, steps, keys, d_masks, d_ct_out=None):
+    """steps, keys: flat lists of 2*n_out entries (pair i at 2i, 2i+1); d_masks [n_out][2][level][N]."""
+    n_out = len(steps) // 2
+    if len(steps) != 2 * n_out or len(keys) != len(steps):
+        raise ValueError("steps and keys must hold one pair per output")
+    if d_ct_in.numel() != 2 * level * P.N or d_masks.numel() != n_out * 2 * level * P.N:
+        raise ValueError("ciphertext must be [2][level][N], masks [n_out][2][level][N]")
+    if d_ct_out is None:
+        d_ct_out = torch.empty((n_out, 2, level, P.N), dtype=torch.int64, device=d_ct_in.device)
+    st = (C.c_int32 * max(len(steps), 1))(*[STEP_CONJ if s == "conj" else int(s) for s in steps])
+    _check(lib.ckks_shift_bank(P.h, _dev(d_ct_in), level, n_out, st, _keyarr(keys), _dev(d_masks), _dev(d_ct_out),
+                               _stream()))
     return d_ct_out
 
 

@@ -124,6 +124,14 @@ def rot_first_masks(n, L, tau):
     return (i < L - t).astype(np.float64), ((i >= L - t) & (i < L)).astype(np.float64), (t, (t - L) % n)
 
 
+def psi_masks(n, m, t):
+    """Masks and rotation steps of the intra-segment shift Psi^t (App. A.1) on slots s*m + r:
+    H = 1{r < m - t}, U = 1{r >= m - t}, steps (t, (t - m) mod n), t taken mod m."""
+    t %= m
+    r = np.arange(n) % m
+    return (r < m - t).astype(np.float64), (r >= m - t).astype(np.float64), (t, (t - m) % n)
+
+
 class Client:
     """Secret-key holder bound to one parameter set."""
 

@@ -1,6 +1,7 @@
 // Elementwise homomorphic primitives of Table 1 (add, ptmul), ModSwitchToNext (Sec. 5.4) and the restricted
 // rotation RotFirst of App. A.1.  All of them stream their operands once: HBM-bound.
 #include <algorithm>
+#include <vector>
 
 #include "ckks_internal.h"
 #include "common_kernels.h"
@@ -84,6 +85,76 @@ static int check_level(const ckks_params *P, u32 level, u32 lo, const char *who)
 
 using namespace ckks;
 
+// masks: 2*n_out device pointers, [level][N] each
+static int shift_bank(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level, uint32_t n_out, const int32_t *steps,
+                      const ckks_gkey_t *const *keys, const uint64_t *const *masks, uint64_t *d_ct_out,
+                      hipStream_t stream) {
+    int rc;
+    const u32 N = P->N;
+    const size_t ctw = (size_t)2 * level * N;
+    // every key is checked before any work is enqueued
+    std::vector<u64> gel(2 * (size_t)n_out);
+    bool any = false;
+    for (size_t s = 0; s < gel.size(); ++s) {
+        ckks_galois_elt(P, steps[s], &gel[s]);
+        if (gel[s] == 1) continue;
+        any = true;
+        if (P->K == 0) {
+            set_error("ckks_shift_bank: parameter set has no special primes");
+            return CKKS_E_INVAL;
+        }
+        if (!keys[s]) {
+            set_error("ckks_shift_bank: step %d (output %zu, term %zu) has no key", steps[s], s / 2, s % 2);
+            return CKKS_E_NOKEY;
+        }
+        if (keys[s]->params != P || keys[s]->galois_elt != gel[s]) {
+            set_error("ckks_shift_bank: key of output %zu, term %zu is for another Galois element", s / 2, s % 2);
+            return CKKS_E_INVAL;
+        }
+    }
+    // scratch: rotated copies of one chunk of outputs, then the hoisted digits and the switch workspace
+    const u32 chunk_out = ROT_BATCH / 2;
+    const size_t rot_w = (size_t)ROT_BATCH * ctw, dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
+    rc = P->ensure_scratch((rot_w + dig_w + tmp_w + switch_scratch_words(P, level, ROT_BATCH)) * sizeof(u64), stream);
+    if (rc) return rc;
+    u64 *d_rot = (u64 *)P->d_scratch, *d_digits = d_rot + rot_w, *d_tmp = d_digits + dig_w, *d_work = d_tmp + tmp_w;
+    if (any) {
+        const u64 *c1 = d_ct_in + (size_t)level * N;
+        rc = decompose(P, &c1, 1, level, d_digits, d_tmp, stream);
+        if (rc) return rc;
+    }
+    for (u32 o0 = 0; o0 < n_out; o0 += chunk_out) {
+        const u32 no = std::min(chunk_out, n_out - o0);
+        SwitchItem items[ROT_BATCH];
+        const u64 *term[ROT_BATCH];
+        u32 n_it = 0;
+        for (u32 s = 0; s < 2 * no; ++s) {
+            const size_t gs = (size_t)2 * o0 + s;
+            if (gel[gs] == 1) {       // the input itself
+                term[s] = d_ct_in;
+                continue;
+            }
+            term[s] = d_rot + (size_t)s * ctw;
+            SwitchItem &it = items[n_it++];
+            it.digits = d_digits;
+            it.c0 = d_ct_in;
+            it.key = keys[gs]->d_key;
+            it.dst = d_rot + (size_t)s * ctw;
+            it.galois_elt = gel[gs];
+            it.accumulate = 0;
+        }
+        rc = switch_batch(P, level, items, n_it, d_work, stream);
+        if (rc) return rc;
+        for (u32 o = 0; o < no; ++o) {
+            hipLaunchKernelGGL(masked_sum_kernel, dim3(N / (2 * EW_THREADS), level), dim3(EW_THREADS), 0, stream,
+                               term[2 * o], term[2 * o + 1], masks[2 * (o0 + o)], masks[2 * (o0 + o) + 1],
+                               d_ct_out + (size_t)(o0 + o) * ctw, P->d_mod, level, N);
+            CKKS_LAUNCH_CHECK("masked_sum_kernel");
+        }
+    }
+    return CKKS_OK;
+}
+
 extern "C" {
 
 int ckks_plain_expand(const ckks_params_t *P, uint32_t level, const int64_t *d_coeffs, uint32_t count,
@@ -148,10 +219,22 @@ int ckks_mod_switch_to_next(const ckks_params_t *P, const uint64_t *d_ct_in, uin
     return CKKS_OK;
 }
 
+int ckks_shift_bank(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level, uint32_t n_out, const int32_t *steps,
+                    const ckks_gkey_t *const *keys, const uint64_t *d_masks, uint64_t *d_ct_out, void *stream) {
+    if (!P || !d_ct_in || (n_out && (!steps || !keys || !d_masks || !d_ct_out))) {
+        set_error("ckks_shift_bank: null argument");
+        return CKKS_E_INVAL;
+    }
+    int rc = check_level(P, level, 1, "ckks_shift_bank");
+    if (rc || n_out == 0) return rc;
+    std::vector<const uint64_t *> masks(2 * (size_t)n_out);
+    for (size_t s = 0; s < masks.size(); ++s) masks[s] = d_masks + s * (size_t)level * P->N;
+    return shift_bank(P, d_ct_in, level, n_out, steps, keys, masks.data(), d_ct_out, (hipStream_t)stream);
+}
+
 int ckks_rot_first(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level, uint32_t L_slots, uint32_t tau,
                    const ckks_gkey_t *key_tau, const ckks_gkey_t *key_wrap, const uint64_t *d_mask_a,
                    const uint64_t *d_mask_b, uint64_t *d_ct_out, void *stream_) {
-    hipStream_t stream = (hipStream_t)stream_;
     if (!P || !d_ct_in || !d_mask_a || !d_mask_b || !d_ct_out) {
         set_error("ckks_rot_first: null argument");
         return CKKS_E_INVAL;
@@ -166,17 +249,8 @@ int ckks_rot_first(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level, ui
     const u32 t = tau % L_slots;
     const int32_t steps[2] = {(int32_t)t, (int32_t)((t + n - L_slots) % n)};
     const ckks_gkey_t *keys[2] = {key_tau, key_wrap};
-    const size_t ctw = (size_t)2 * level * N;
-    const size_t reserve = 2 * ctw;
-    rc = P->ensure_scratch((reserve + rotate_hoisted_scratch_words(P, level, 2)) * sizeof(u64), stream);
-    if (rc) return rc;
-    u64 *d_rot = (u64 *)P->d_scratch;
-    rc = rotate_hoisted(P, d_ct_in, level, steps, 2, keys, d_rot, reserve, stream);
-    if (rc) return rc;
-    hipLaunchKernelGGL(masked_sum_kernel, dim3(N / (2 * EW_THREADS), level), dim3(EW_THREADS), 0, stream, d_rot,
-                       d_rot + ctw, d_mask_a, d_mask_b, d_ct_out, P->d_mod, level, N);
-    CKKS_LAUNCH_CHECK("masked_sum_kernel");
-    return CKKS_OK;
+    const uint64_t *masks[2] = {d_mask_a, d_mask_b};
+    return shift_bank(P, d_ct_in, level, 1, steps, keys, masks, d_ct_out, (hipStream_t)stream_);
 }
 
 }  // extern "C"

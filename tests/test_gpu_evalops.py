@@ -111,3 +111,75 @@ def test_error_paths():
     assert B.lib.ckks_rot_first(P.h, p(ct), 3, O.n + 1, 1, None, None, p(pt), p(pt), p(out), None) == -1
     assert B.lib.ckks_rot_first(P.h, p(ct), 3, 64, 1, None, None, p(pt), p(pt), p(out), None) == -3
     assert B.lib.ckks_plain_expand(P.h, 4, p(ct), 1, p(out), None) == -2
+
+
+def _psi_bank(O, P, level, m, ts, seed, scale, hw=16):
+    """Bank of Psi^t, t in ts, against the oracle's bank bit for bit and against the definition of the shift."""
+    from paper_2604_09975_amd import binding as B
+    from paper_2604_09975_amd import client as CL
+    cl = helpers.Client(O, seed, hamming_weight=hw)
+    r = W.rng(seed)
+    z = W.unit_disk_slots(r, O.n)
+    ct = cl.encrypt_slots(z, scale, level)
+    gel, keys, masks, steps_flat, cache = [], [], [], [], {}
+    for t in ts:
+        h, u, steps = E.psi_masks(O.n, m, t)
+        h2, u2, steps2 = CL.psi_masks(O.n, m, t)
+        assert (h == h2).all() and (u == u2).all() and steps == steps2
+        g = [O.galois_elt(s) for s in steps]
+        for x in g:
+            if x != 1 and x not in cache:
+                k = cl.galois_key(x)
+                cache[x] = (k, B.ckks_galois_key_load(P, x, to_dev(k)))
+        gel.append(g)
+        keys.append([cache[x] if x != 1 else (None, None) for x in g])
+        masks.append([_plain(O, P, B, h, scale, level), _plain(O, P, B, u, scale, level)])
+        steps_flat += list(steps)
+    masks = np.array(masks)
+    want = O.shift_bank(ct, level, gel, [[k[0] for k in pair] for pair in keys], masks)
+    got = to_host(B.ckks_shift_bank(P, to_dev(ct), level, steps_flat, [k[1] for pair in keys for k in pair],
+                                    to_dev(masks)))
+    assert (got == want).all()
+    if level > 1:
+        out = to_host(B.ckks_rescale(P, to_dev(got), level, len(ts)))
+        for i, t in enumerate(ts):
+            zz = cl.decrypt_slots(out[i], level - 1, scale * scale / O.q[level - 1], nlimbs=min(level - 1, 2))
+            assert np.abs(zz - E.psi_shift(z, m, t)).max() < 2e-3
+
+
+def test_psi_bank_toy():
+    O, P = make_pair(W.TOY_RING)
+    _psi_bank(O, P, 3, 16, [1, 2, 3, 5, 8, 15], 51, 2.0**30, hw=64)
+
+
+def test_psi_bank_more_outputs_than_one_batch_and_identity_terms():
+    """11 outputs = 22 rotations (two batches of key switches); t = 0 has an identity first term."""
+    O = helpers.small_oracle(10, L=4, K=2, dnum=2, qbits=40, pbits=45)
+    _, P = make_pair(O)
+    _psi_bank(O, P, 4, 32, list(range(0, 11)), 52, 2.0**30)
+
+
+def test_psi_bank_full_ring():
+    """m = 128 (the BERT / GPT-2 sequence length): Psi^1, Psi^64 (the half-segment shift of the value kernel) and
+    Psi^127 from one ciphertext at N = 2^16, level 24."""
+    O, P = make_pair(W.BIG_RING)
+    _psi_bank(O, P, 24, 128, [1, 64, 127], 53, 2.0**40, hw=64)
+
+
+def test_shift_bank_errors():
+    from paper_2604_09975_amd import binding as B
+    O, P = make_pair(W.TOY_RING)
+    ct = torch.zeros((2, 3, O.N), dtype=torch.int64, device="cuda")
+    masks = torch.zeros((1, 2, 3, O.N), dtype=torch.int64, device="cuda")
+    with pytest.raises(B.CkksError) as err:
+        B.ckks_shift_bank(P, ct, 3, [1, 0], [None, None], masks)
+    assert err.value.code == -3
+    cl = helpers.Client(O, 8)
+    k2 = B.ckks_galois_key_load(P, O.galois_elt(2), to_dev(cl.galois_key(O.galois_elt(2))))
+    with pytest.raises(B.CkksError) as err:
+        B.ckks_shift_bank(P, ct, 3, [1, 0], [k2, None], masks)
+    assert err.value.code == -1
+    out = B.ckks_shift_bank(P, ct, 3, [0, 0], [None, None], masks)           # identity terms need no keys
+    assert int(out.abs().sum()) == 0
+    assert B.lib.ckks_shift_bank(P.h, ct.data_ptr(), 4, 0, None, None, None, None, None) == -2
+    assert B.lib.ckks_shift_bank(P.h, ct.data_ptr(), 3, 0, None, None, None, None, None) == 0

@@ -52,3 +52,37 @@ def test_restricted_segment_shift_equals_plain_rot_when_all_segments_are_active(
     a, b, steps = E.rot_first_masks(n, n, 3 * m)
     assert steps == (3 * m, (3 * m - n) % n) and steps[0] == steps[1]
     assert (a + b == 1).all()
+
+
+@pytest.mark.parametrize("m,ts", [(16, [1, 5, 15]), (4, [0, 3]), (128, [64])])
+def test_psi_bank_is_the_intra_segment_shift(m, ts):
+    """Bank of Psi^t from one input (Sec. 3.1, App. A.1): slot s*m + r of Psi^t(x) holds x[s*m + (r+t) mod m];
+    the bank equals the shifts made one by one (hoisting shares only the decomposition)."""
+    O = helpers.small_oracle(8, L=3, K=1, dnum=3, qbits=40, pbits=42)
+    n = O.n
+    cl = helpers.Client(O, 81, hamming_weight=16)
+    r = np.random.default_rng(m)
+    z = r.uniform(-1, 1, n) + 1j * r.uniform(-1, 1, n)
+    ct = cl.encrypt_slots(z, 2.0**30, 3)
+    gel, keys, masks = [], [], []
+    cache = {}
+    for t in ts:
+        h, u, steps = E.psi_masks(n, m, t)
+        assert ((h + u) == 1).all()
+        g = [O.galois_elt(s) for s in steps]
+        for x in g:
+            if x != 1 and x not in cache:
+                cache[x] = cl.galois_key(x)
+        gel.append(g)
+        keys.append([cache.get(x) for x in g])
+        masks.append([O.expand_plain(3, E.encode(h + 0j, 2.0**30, O.N)), O.expand_plain(3, E.encode(u + 0j, 2.0**30, O.N))])
+    masks = np.array(masks)
+    bank = O.shift_bank(ct, 3, gel, keys, masks)
+    for i, t in enumerate(ts):
+        one = O.rot_first(ct, 3, gel[i], keys[i], masks[i, 0], masks[i, 1])
+        assert (bank[i] == one).all()
+        out = O.rescale(bank[i][None], 3)[0]
+        got = cl.decrypt_slots(out, 2, 2.0**60 / O.q[2], nlimbs=2)
+        assert np.abs(got - E.psi_shift(z, m, t)).max() < 1e-3
+    # composing the definition: Psi^t then Psi^(m-t) is the identity
+    assert np.allclose(E.psi_shift(E.psi_shift(z, m, ts[0]), m, m - ts[0]), z)
