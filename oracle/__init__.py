@@ -23,7 +23,9 @@ CONJ = "conj"
 
 
 def _lib():
-    lib = C.CDLL(_build.build())
+    # CKKS_ORACLE_LIB: a library built elsewhere from (a copy of) ckks_oracle.c; the mutation tests point it at
+    # deliberately broken builds to show that the pins catch them
+    lib = C.CDLL(os.environ.get("CKKS_ORACLE_LIB") or _build.build())
     lib.orc_mulmod.restype = C.c_uint64
     lib.orc_mulmod.argtypes = [C.c_uint64] * 3
     lib.orc_powmod.restype = C.c_uint64
