@@ -53,6 +53,14 @@ MUTANTS = [
      ["test_oracle_matmul.py"]),
     ("diagonal_index_transposed", "((((u64)b * N2 + p) * G + g) * N1 + q) * N;",
      "((((u64)b * N2 + p) * N1 + q) * G + g) * N;", ["test_oracle_matmul.py"]),
+    ("merged_c0_dropped", "if (ci < level) v = addmod(v, c0_acc[(u64)ci * N + k], qi);",
+     "if (ci < level) v = addmod(v, 0, qi);", ["test_oracle_matmul.py"]),
+    ("merged_skips_first_rotation", "for (int p = 1; p < N2; p++)\n                orc_switch_accumulate(",
+     "for (int p = 2; p < N2; p++)\n                orc_switch_accumulate(", ["test_oracle_matmul.py"]),
+    ("conj_added_twice", "orc_rotate_hoisted(c, y, level, &g, 1, &conj_key, rot);",
+     "orc_rotate_hoisted(c, y, level, &g, 1, &conj_key, rot); memcpy(y, rot, sizeof(u64) * 2 * level * N);",
+     ["test_oracle_complex.py"]),
+    ("bias_without_scale_factor", "u64 bm = bias_mul % qi;", "u64 bm = 1;", ["test_oracle_matmul.py"]),
     ("ctmul_cross_term_dropped",
      "t1[(u64)i * N + x] = addmod(mulmod(a0[x], b1[x], q), mulmod(a1[x], b0[x], q), q);",
      "t1[(u64)i * N + x] = mulmod(a0[x], b1[x], q);", ["test_oracle_ctmul.py"]),
