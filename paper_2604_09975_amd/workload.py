@@ -52,9 +52,9 @@ BERT_QKV = MatmulSpec(ring=BIG_RING, m=128, d_in=768, d_out=2304, C=256, N1=32, 
                       name="bert_base_qkv_128x768x2304")
 GPT2_LAYERS = (
     MatmulSpec(ring=BIG_RING, m=128, d_in=768, d_out=2304, C=256, N1=32, seed=SEED_BASE + 40, name="gpt2_qkv"),
-    MatmulSpec(ring=BIG_RING, m=128, d_in=768, d_out=768, C=256, N1=32, seed=SEED_BASE + 41, name="gpt2_attn_out"),
+    MatmulSpec(ring=BIG_RING, m=128, d_in=768, d_out=768, C=256, N1=16, seed=SEED_BASE + 41, name="gpt2_attn_out"),
     MatmulSpec(ring=BIG_RING, m=128, d_in=768, d_out=3072, C=256, N1=32, seed=SEED_BASE + 42, name="gpt2_ffn_up"),
-    MatmulSpec(ring=BIG_RING, m=128, d_in=3072, d_out=768, C=256, N1=32, seed=SEED_BASE + 43, name="gpt2_ffn_down"),
+    MatmulSpec(ring=BIG_RING, m=128, d_in=3072, d_out=768, C=256, N1=8, seed=SEED_BASE + 43, name="gpt2_ffn_down"),
 )
 
 # hoisted-rotation batch: the 26 non-trivial listed steps, conjugation, and the

@@ -72,10 +72,11 @@ def test_bert_qkv_sampled_block_bit_exact(merged):
     assert np.abs(slots.imag).max() <= 1e-3
 
 
-def test_gpt2_ffn_down_width_one_block_bit_exact():
+@pytest.mark.parametrize("merged", [False, True], ids=["default", "merged_giant"])
+def test_gpt2_ffn_down_width_one_block_bit_exact(merged):
     """Full ring, the input width of the GPT-2 FFN-down layer (d_in = 3072: twelve input ciphertexts, so the
-    baby-step batches hold one step of all inputs each), one output block of 256 columns, every residue of it
-    against the oracle.  Run at level 9 of 24 (two digits, the second with a single limb) to keep the oracle
+    baby-step batches hold one step of all inputs each; N1 = 8, so the giant step has 31 rotations, four
+    groups of the merged form), one output block of 256 columns, every residue of it against the oracle.  Run at level 9 of 24 (two digits, the second with a single limb) to keep the oracle
     under half a minute and to cover a partial last digit at N = 2^16."""
     from paper_2604_09975_amd import binding as B
     t0 = time.time()
@@ -98,11 +99,13 @@ def test_gpt2_ffn_down_width_one_block_bit_exact():
     B.ckks_weights_set_diagonals(w, 0, to_dev(diag.reshape(-1, N)))
     B.ckks_weights_set_bias(w, to_dev(bias_c), int(scale))
     print(f"[ffn] inputs ready {time.time() - t0:.0f}s", flush=True)
-    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h)
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h,
+                                    flags=B.MATMUL_MERGED_GIANT if merged else 0)
     y_res = B.ckks_rescale(P, y_dev, level, B_out)
     torch.cuda.synchronize()
     assert cnt.key_switches == G * (N1 - 1) + B_out * (N2 - 1)
-    want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(scale), ct_x, baby_np, giant_np)
+    want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(scale), ct_x, baby_np, giant_np,
+                         merged=merged)
     print(f"[ffn] oracle done {time.time() - t0:.0f}s", flush=True)
     assert (to_host(y_dev) == want).all()
     got_res = to_host(y_res)
