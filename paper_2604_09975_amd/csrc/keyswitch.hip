@@ -380,28 +380,37 @@ __global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64
     const u64 g = it.galois_elt;
     u64 *out = y + (((size_t)r * 2 + comp) * K + k) * N;
     auto store = [&](u32 idx, u64 v) { out[idx] = v; };
-    // inner product into LDS, four residues at a time so that their 6*4 loads are in flight together
+    // inner product into LDS on pairs of adjacent residues (16-byte key loads), two pairs at a time so that
+    // their loads are in flight together
+    typedef u64 vec_t __attribute__((ext_vector_type(2)));
     const u32 tid = threadIdx.x, base = blockIdx.x << 12;
-    for (u32 i0 = 0; i0 < 16; i0 += EPI) {
-        u64 dv[EPI][MAX_BETA], kv[EPI][MAX_BETA];
+    constexpr u32 EPP = EPI / 2;
+    for (u32 i0 = 0; i0 < 8; i0 += EPP) {
+        u64 dv[EPP][2][MAX_BETA];
+        vec_t kv[EPP][MAX_BETA];
 #pragma unroll
-        for (u32 e = 0; e < EPI; ++e) {
-            const u32 idx = base + tid + 256 * (i0 + e);
-            const u32 kp = galois_index(idx, g, logN);
+        for (u32 e = 0; e < EPP; ++e) {
+            const u32 idx = base + 2 * (tid + 256 * (i0 + e));
+            const u32 kp0 = galois_index(idx, g, logN), kp1 = galois_index(idx + 1, g, logN);
 #pragma unroll
             for (u32 j = 0; j < MAX_BETA; ++j)
                 if (j < beta) {
-                    dv[e][j] = dig[(size_t)j * Wl * N + kp];
-                    kv[e][j] = __builtin_nontemporal_load(key + (size_t)j * 2 * Wt * N + idx);
+                    dv[e][0][j] = dig[(size_t)j * Wl * N + kp0];
+                    dv[e][1][j] = dig[(size_t)j * Wl * N + kp1];
+                    kv[e][j] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(key + (size_t)j * 2 * Wt * N + idx));
                 }
         }
 #pragma unroll
-        for (u32 e = 0; e < EPI; ++e) {
-            u128 acc = {0, 0};
+        for (u32 e = 0; e < EPP; ++e) {
+            const u32 loc = 2 * (tid + 256 * (i0 + e));
 #pragma unroll
-            for (u32 j = 0; j < MAX_BETA; ++j)
-                if (j < beta) mac(acc, dv[e][j], kv[e][j]);
-            lds[lds_pad(tid + 256 * (i0 + e))] = redc_wide(acc, m);
+            for (u32 z = 0; z < 2; ++z) {
+                u128 acc = {0, 0};
+#pragma unroll
+                for (u32 j = 0; j < MAX_BETA; ++j)
+                    if (j < beta) mac(acc, dv[e][z][j], kv[e][j][z]);
+                lds[lds_pad(loc + z)] = redc_wide(acc, m);
+            }
         }
     }
     __syncthreads();
@@ -442,36 +451,49 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
         pass_b_fwd_to_lds(make_field_fp(mf, twf_fwd, i, logN), logN, lds, load);
     else
         pass_b_fwd_to_lds(make_field_int(mods, tw_fwd, ninv, i, logN), logN, lds, load);
-    // epilogue, four residues at a time so that their loads are in flight together.  Keys, w and the output
-    // are streamed once: non-temporal, so that they do not push the digit rows (re-read by every item of the
-    // batch) out of L2.
+    // epilogue on pairs of adjacent residues (16-byte accesses to the streamed operands), two pairs at a time so
+    // that their loads are in flight together.  Keys, w and the output are streamed once: non-temporal, so that
+    // they do not push the digit rows (re-read by every item of the batch) out of L2.
+    typedef u64 vec_t __attribute__((ext_vector_type(2)));
     const u32 tid = threadIdx.x, base = blockIdx.x << 12;
-    for (u32 i0 = 0; i0 < 16; i0 += EPI) {
-        u64 dv[EPI][MAX_BETA], kv[EPI][MAX_BETA], cv[EPI], ov[EPI];
+    constexpr u32 EPP = EPI / 2;
+    for (u32 i0 = 0; i0 < 8; i0 += EPP) {
+        u64 dv[EPP][2][MAX_BETA], cv[EPP][2];
+        vec_t kv[EPP][MAX_BETA], ov[EPP];
 #pragma unroll
-        for (u32 e = 0; e < EPI; ++e) {
-            const u32 idx = base + tid + 256 * (i0 + e);
-            const u32 kp = galois_index(idx, g, logN);
+        for (u32 e = 0; e < EPP; ++e) {
+            const u32 idx = base + 2 * (tid + 256 * (i0 + e));
+            const u32 kp0 = galois_index(idx, g, logN), kp1 = galois_index(idx + 1, g, logN);
 #pragma unroll
             for (u32 j = 0; j < MAX_BETA; ++j)
                 if (j < beta) {
-                    dv[e][j] = dig[(size_t)j * Wl * N + kp];
-                    kv[e][j] = __builtin_nontemporal_load(key + (size_t)j * 2 * Wt * N + idx);
+                    dv[e][0][j] = dig[(size_t)j * Wl * N + kp0];
+                    dv[e][1][j] = dig[(size_t)j * Wl * N + kp1];
+                    kv[e][j] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(key + (size_t)j * 2 * Wt * N + idx));
                 }
-            cv[e] = (comp == 0 && it.c0) ? c0[kp] : 0;
-            ov[e] = accumulate ? __builtin_nontemporal_load(dst + idx) : 0;
+            const bool fold = comp == 0 && it.c0;
+            cv[e][0] = fold ? c0[kp0] : 0;
+            cv[e][1] = fold ? c0[kp1] : 0;
+            if (accumulate)
+                ov[e] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(dst + idx));
+            else
+                ov[e] = vec_t{0, 0};
         }
 #pragma unroll
-        for (u32 e = 0; e < EPI; ++e) {
-            const u32 idx = base + tid + 256 * (i0 + e);
-            u128 acc = {0, 0};
+        for (u32 e = 0; e < EPP; ++e) {
+            const u32 loc = 2 * (tid + 256 * (i0 + e));
+            vec_t out;
 #pragma unroll
-            for (u32 j = 0; j < MAX_BETA; ++j)
-                if (j < beta) mac(acc, dv[e][j], kv[e][j]);
-            u64 v = mont_mul(sub_mod(redc_wide(acc, m), lds[lds_pad(tid + 256 * (i0 + e))], m.q), pi, m);
-            v = add_mod(v, cv[e], m.q);
-            v = add_mod(v, ov[e], m.q);
-            __builtin_nontemporal_store(v, dst + idx);
+            for (u32 z = 0; z < 2; ++z) {
+                u128 acc = {0, 0};
+#pragma unroll
+                for (u32 j = 0; j < MAX_BETA; ++j)
+                    if (j < beta) mac(acc, dv[e][z][j], kv[e][j][z]);
+                u64 v = mont_mul(sub_mod(redc_wide(acc, m), lds[lds_pad(loc + z)], m.q), pi, m);
+                v = add_mod(v, cv[e][z], m.q);
+                out[z] = add_mod(v, ov[e][z], m.q);
+            }
+            __builtin_nontemporal_store(out, reinterpret_cast<vec_t *>(dst + base + loc));
         }
     }
 }
