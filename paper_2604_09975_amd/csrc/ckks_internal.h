@@ -73,6 +73,8 @@ struct ckks_params {
     // ModDown tables (independent of the level)
     ckks::u64 *d_dn_inv = nullptr;     // [K]: (P/p_k)^-1 mod p_k
     ckks::u64 *d_dn_mat = nullptr;     // [K][L]: P/p_k mod q_i
+    double *d_dn_matf = nullptr;       // [L][K][3][2]: (2^(20a) * P/p_k) mod q_i as two 25-bit halves (doubles)
+    bool dn_fp = false;                // every special prime below 2^60: the fp64 ModDown conversion applies
     ckks::u64 *d_pinv = nullptr;       // [L]: P^-1 mod q_i
     ckks::u64 *d_qlinv = nullptr;      // [L][L]: q_l^-1 mod q_i (rescale), row l
     std::map<ckks::u32, ckks::LevelTables> levels;

@@ -22,7 +22,7 @@ namespace ckks {
 
 constexpr u32 KS_THREADS = EW_THREADS;
 constexpr u32 UP_CHUNK = 16;   // target limbs per workgroup in ModUp (8, 16, 32 measured: 16 is fastest)
-constexpr u32 DN_CHUNK = 12;   // target limbs per workgroup in ModDown
+constexpr u32 DN_CHUNK = 24;   // target limbs per workgroup in ModDown (2, 3, 4, 6, 12, 24 measured: fewer, larger groups are faster)
 
 __device__ __forceinline__ u32 galois_index(u32 k, u64 g, u32 logN) {
     // entry k holds the value at psi^(2*bitrev(k)+1); sigma_g reads the value at that exponent times g
@@ -314,26 +314,75 @@ __global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, c
     }
 }
 
+template <u32 KMAX>
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__restrict__ y, u64 *__restrict__ w,
                                                                   const ModConst *__restrict__ mods,
-                                                                  const u64 *__restrict__ dn_mat, u32 level, u32 K,
-                                                                  u32 L, u32 N, u32 ystride, u32 yoff) {
+                                                                  const ModFp *__restrict__ modf,
+                                                                  const u64 *__restrict__ dn_mat,
+                                                                  const double *__restrict__ dn_matf, u32 level,
+                                                                  u32 K, u32 L, u32 N, u32 ystride, u32 yoff,
+                                                                  u32 fp_ok) {
     const u32 n = blockIdx.x * KS_THREADS + threadIdx.x;
     const u32 pc = blockIdx.y;   // (item, component)
-    u64 yk[MAX_DIGIT];
+    u64 yk[KMAX];
 #pragma unroll
-    for (u32 k = 0; k < MAX_DIGIT; ++k) {
+    for (u32 k = 0; k < KMAX; ++k) {
         yk[k] = 0;
         if (k < K) yk[k] = y[((size_t)pc * ystride + yoff + k) * N + n];
     }
+    // Targets below 2^50 (special primes below 2^60): every y_k is cut into three 20-bit pieces and every factor
+    // (times 2^0, 2^20, 2^40, reduced) into two 25-bit halves, all held as doubles.  The 45-bit products are
+    // summed exactly by FMAs into a low and a high sum (3*KMAX terms each, below 2^53), and the result is
+    // (high * 2^25 + low) mod q: the 32-bit integer multiplier, four times slower per product, stays out of it.
+    double yp[KMAX][3];
+#pragma unroll
+    for (u32 k = 0; k < KMAX; ++k) {
+        const u64 v = fp_ok ? yk[k] : 0;
+        yp[k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
+        yp[k][1] = __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
+        yp[k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
+    }
     const u32 i0 = blockIdx.z * DN_CHUNK, i1 = min(i0 + DN_CHUNK, level);
     for (u32 i = i0; i < i1; ++i) {
+        if (fp_ok && modf[i].ok) {
+            const double q = modf[i].q, u = modf[i].u;
+            const double *f = dn_matf + (size_t)i * K * 6;
+            double lo = 0.0, hi = 0.0;
+#pragma unroll
+            for (u32 k = 0; k < KMAX; ++k)
+                if (k < K) {
+#pragma unroll
+                    for (u32 a = 0; a < 3; ++a) {
+                        lo = fma(yp[k][a], f[(k * 3 + a) * 2 + 0], lo);
+                        hi = fma(yp[k][a], f[(k * 3 + a) * 2 + 1], hi);
+                    }
+                }
+            const double t = hi * 33554432.0;                       // exact: a power of two
+            double v = fma(-rint(t * u), q, t) + lo;                // |.| < 0.75 q, plus low < 2^51
+            v = fma(-rint(v * u), q, v);
+            if (v < 0) v += q;
+            w[((size_t)pc * level + i) * N + n] = (u64)v;
+            continue;
+        }
         u128 acc = {0, 0};
 #pragma unroll
-        for (u32 k = 0; k < MAX_DIGIT; ++k)
+        for (u32 k = 0; k < KMAX; ++k)
             if (k < K) mac(acc, yk[k], dn_mat[(size_t)k * L + i]);
         w[((size_t)pc * level + i) * N + n] = redc_wide(acc, mods[i]);   // up to 16 products below 2^62 * q each
     }
+}
+
+// base conversion P -> q_i of n*2 polynomials; the rows of polynomial pc start at row pc * ystride + yoff of y
+static void launch_moddown_conv(const ckks_params *p, const u64 *y, u64 *w, u32 n, u32 level, u32 ystride, u32 yoff,
+                                hipStream_t stream) {
+    const dim3 grid(p->N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK);
+    if (p->K <= 8)
+        hipLaunchKernelGGL(moddown_conv_kernel<8>, grid, dim3(KS_THREADS), 0, stream, y, w, p->d_mod, p->d_modf,
+                           p->d_dn_mat, p->d_dn_matf, level, p->K, p->L, p->N, ystride, yoff, p->dn_fp ? 1u : 0u);
+    else
+        hipLaunchKernelGGL(moddown_conv_kernel<MAX_DIGIT>, grid, dim3(KS_THREADS), 0, stream, y, w, p->d_mod,
+                           p->d_modf, p->d_dn_mat, p->d_dn_matf, level, p->K, p->L, p->N, ystride, yoff,
+                           p->dn_fp ? 1u : 0u);
 }
 
 // dst[comp][i][k] (+)= (u_{q_i} - NTT(w_i)) * P^-1  (+ sigma_g(c0)[i][k] for comp 0)
@@ -637,8 +686,7 @@ int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64
     for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
     int rc = launch_ntt(p, d_u, ids, Wl, n * 2 * Wl, true, stream, 3, true);
     if (rc) return rc;
-    hipLaunchKernelGGL(moddown_conv_kernel, dim3(N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK),
-                       dim3(KS_THREADS), 0, stream, d_u, d_w, p->d_mod, p->d_dn_mat, level, K, L, N, Wl, level);
+    launch_moddown_conv(p, d_u, d_w, n, level, Wl, level, stream);
     CKKS_LAUNCH_CHECK("moddown_conv_kernel");
     for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
     rc = launch_ntt(p, d_w, ids, level, n * 2 * level, false, stream);
@@ -675,8 +723,7 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
         if (rc) return rc;
         // (a variant with this base conversion fused into the transform's first pass was measured: its 8 strided
         // reads per residue from L2 made it slower than the two kernels)
-        hipLaunchKernelGGL(moddown_conv_kernel, dim3(N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK),
-                           dim3(KS_THREADS), 0, stream, y, w, p->d_mod, p->d_dn_mat, level, K, L, N, K, 0u);
+        launch_moddown_conv(p, y, w, n, level, K, 0u, stream);
         CKKS_LAUNCH_CHECK("moddown_conv_kernel");
         for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
         rc = launch_ntt(p, w, ids, level, n * 2 * level, false, stream, 1, false);
@@ -695,8 +742,7 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
     for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
     int rc = launch_ntt(p, u, ids, Wl, n * 2 * Wl, true, stream, 3, true);
     if (rc) return rc;
-    hipLaunchKernelGGL(moddown_conv_kernel, dim3(N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK),
-                       dim3(KS_THREADS), 0, stream, u, w, p->d_mod, p->d_dn_mat, level, K, L, N, Wl, level);
+    launch_moddown_conv(p, u, w, n, level, Wl, level, stream);
     CKKS_LAUNCH_CHECK("moddown_conv_kernel");
     for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
     rc = launch_ntt(p, w, ids, level, n * 2 * level, false, stream);

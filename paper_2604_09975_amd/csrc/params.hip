@@ -296,6 +296,7 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
             }
     }
     std::vector<u64> dn_inv(K), dn_mat((size_t)K * L), pinv(L), qlinv((size_t)L * L, 0);
+    std::vector<double> dn_matf((size_t)L * K * 6, 0.0);
     for (u32 k = 0; k < K; ++k) {
         u64 pk = mod[L + k], prod = 1;
         for (u32 b = 0; b < K; ++b)
@@ -306,8 +307,18 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
             for (u32 b = 0; b < K; ++b)
                 if (b != k) f = hmul(f, mod[L + b] % mod[i], mod[i]);
             dn_mat[(size_t)k * L + i] = to_mont(f, P->hmod[i]);
+            // the same factor times 2^0, 2^20, 2^40 mod q_i, each split into 25-bit halves held as doubles: the
+            // conversion onto a prime below 2^50 is then a sum of exact 20-bit x 25-bit products in fp64
+            for (u32 a = 0; a < 3; ++a) {
+                const u64 c = hmul(f, hpow(2, 20 * a, mod[i]), mod[i]);
+                dn_matf[(((size_t)i * K + k) * 3 + a) * 2 + 0] = (double)(c & ((1u << 25) - 1));
+                dn_matf[(((size_t)i * K + k) * 3 + a) * 2 + 1] = (double)(c >> 25);
+            }
         }
     }
+    P->dn_fp = true;          // three 20-bit pieces cover a special prime below 2^60
+    for (u32 k = 0; k < K; ++k)
+        if (mod[L + k] >> 60) P->dn_fp = false;
     for (u32 i = 0; i < L; ++i) {
         u64 pm = 1;
         for (u32 k = 0; k < K; ++k) pm = hmul(pm, mod[L + k] % mod[i], mod[i]);
@@ -342,6 +353,7 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     if (!rc) rc = upload(&P->d_twf_inv, inv_f);
     if (!rc) rc = upload(&P->d_dn_inv, dn_inv);
     if (!rc) rc = upload(&P->d_dn_mat, dn_mat);
+    if (!rc) rc = upload(&P->d_dn_matf, dn_matf);
     if (!rc) rc = upload(&P->d_pinv, pinv);
     if (!rc) rc = upload(&P->d_qlinv, qlinv);
     if (rc) {
@@ -365,6 +377,7 @@ void ckks_params_destroy(ckks_params_t *P) {
     hipFree(P->d_twf_inv);
     hipFree(P->d_dn_inv);
     hipFree(P->d_dn_mat);
+    hipFree(P->d_dn_matf);
     hipFree(P->d_pinv);
     hipFree(P->d_qlinv);
     for (auto &kv : P->levels) {
