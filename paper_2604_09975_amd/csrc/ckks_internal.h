@@ -127,7 +127,9 @@ inline bool fast_ring(const ckks_params *p) { return p->logN == 16 || p->logN ==
 
 // keyswitch.hip
 struct SwitchItem {
-    const u64 *digits;   // [beta][level+K][N] extended digits of the source c1, NTT domain
+    const u64 *digits;   // [beta][level+K][N] extended digits of the source c1, NTT domain; the rows of a digit's own
+                         // limbs are NOT filled: they equal the source's own rows and are read from c1
+    const u64 *c1;       // [level][N] the decomposed polynomial itself (NTT domain); must outlive the switch
     const u64 *c0;       // [level][N] source c0
     const u64 *key;      // Montgomery-form key
     u64 *dst;            // [2][level][N]
@@ -142,7 +144,8 @@ int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64
 // Several rotations of n ciphertexts each, summed over the extended basis in one pass:
 //   u_r (+)= sum_i sum_j sigma_{g_i}(digits_{i,r,j}) * key_{i,j},   dst_r.c0 += sum_i sigma_{g_i}(c0_{i,r}),
 // r < n <= ROT_BATCH, i < n_rot <= MERGE_GROUP.  digits of (i, r) at d_digits + (i*n + r)*digits_words;
-// c0 of (i, r) at c0_base + r*c0_stride_r + c0_off[i]; dst_r at dst_base + r*dst_stride.
+// c0 of (i, r) at c0_base + r*c0_stride_r + c0_off[i], its c1 (the decomposed polynomial) level*N words behind it;
+// dst_r at dst_base + r*dst_stride.
 constexpr u32 MERGE_GROUP = 8;
 struct MergedRot {
     const u64 *key[MERGE_GROUP];

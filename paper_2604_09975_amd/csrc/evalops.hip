@@ -137,6 +137,7 @@ static int shift_bank(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level,
             term[s] = d_rot + (size_t)s * ctw;
             SwitchItem &it = items[n_it++];
             it.digits = d_digits;
+            it.c1 = d_ct_in + (size_t)level * N;
             it.c0 = d_ct_in;
             it.key = keys[gs]->d_key;
             it.dst = d_rot + (size_t)s * ctw;

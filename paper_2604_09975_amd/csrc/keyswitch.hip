@@ -66,12 +66,13 @@ __global__ __launch_bounds__(NTT_THREADS) void gather_intt_kernel(PtrPack src, u
 
 // Per ciphertext r and digit j: y_i = c_i * (Q_D/q_i)^-1 mod q_i for the limbs of the digit, then for
 // every target t outside the digit out_t = sum_i y_i * (Q_D/q_i mod t) mod t (coefficient domain).
-// Targets inside the digit are copied from the NTT-domain input (they need no transform).
+// Targets inside the digit are left out: in the NTT domain they are the input's own rows, which the consumers
+// read in place (no copy, no transform).
 // grid: x = pairs of coefficients, y = digit, z = r * chunks + chunk of UP_CHUNK targets.  A thread owns two
 // adjacent coefficients (16-byte accesses) so that every conversion factor, which is workgroup-uniform and
 // arrives through the scalar cache, serves two multiply-accumulates; AMAX bounds the digit size.
 template <u32 AMAX, u32 VEC>
-__global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, const u64 *__restrict__ c1_coeff,
+__global__ __launch_bounds__(KS_THREADS) void modup_kernel(const u64 *__restrict__ c1_coeff,
                                                            u64 *__restrict__ digits,
                                                            const ModConst *__restrict__ mods,
                                                            const ModFp *__restrict__ modf,
@@ -118,12 +119,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(PtrPack src_ntt, cons
     const u32 t0 = chunk * up_chunk, t1 = min(t0 + up_chunk, Wl);
     for (u32 t = t0; t < t1; ++t) {
         u64 *dst = dig + ((size_t)j * Wl + t) * N + n;
-        if (t >= lo && t < hi) {
-#pragma unroll
-            for (u32 e = 0; e < VEC; e += 2)
-                *reinterpret_cast<vec_t *>(dst + e) = *reinterpret_cast<const vec_t *>(src_ntt.p[r] + (size_t)t * N + n + e);
-            continue;
-        }
+        if (t >= lo && t < hi) continue;      // the digit's own limbs: consumers read them from the source
         const u32 gl = t < level ? t : L + (t - level);
         if (digit_fp && modf[gl].ok) {
             const double q = modf[gl].q, u = modf[gl].u;
@@ -193,7 +189,7 @@ struct ItemPack {
 // no key), so that nothing but ModDown(u) is left to add later.
 __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack, u64 *__restrict__ u,
                                                                    const ModConst *__restrict__ mods, u32 level,
-                                                                   u32 K, u32 L, u32 beta, u32 logN) {
+                                                                   u32 K, u32 L, u32 beta, u32 alpha, u32 logN) {
     const u32 N = 1u << logN;
     const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
     const u32 t = blockIdx.y;
@@ -214,7 +210,9 @@ __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack
 #pragma unroll
         for (u32 r = 0; r < KEY_GROUP; ++r) {
             if (r < cnt) {
-                const u64 d = pack.it[first + r].digits[((size_t)j * Wl + t) * N + kp];
+                const SwitchItem &it = pack.it[first + r];
+                const u64 d = (t < level && t / alpha == j) ? it.c1[(size_t)t * N + kp]
+                                                            : it.digits[((size_t)j * Wl + t) * N + kp];
                 mac(a0[r], d, k0);
                 mac(a1[r], d, k1);
             }
@@ -244,13 +242,15 @@ __global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, c
                                                                size_t c0_stride_r, u64 *__restrict__ dst_base,
                                                                size_t dst_stride, u64 *__restrict__ u,
                                                                const ModConst *__restrict__ mods, u32 n, u32 level,
-                                                               u32 K, u32 L, u32 beta, u32 logN, u32 accumulate) {
+                                                               u32 K, u32 L, u32 beta, u32 alpha, u32 logN,
+                                                               u32 accumulate) {
     const u32 N = 1u << logN;
     const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
     const u32 t = blockIdx.y;
     const u32 r0 = blockIdx.z * MR;
     const u32 Wl = level + K, Wt = L + K;
     const u32 gl = t < level ? t : L + (t - level);
+    const u32 own = t < level ? t / alpha : ~0u;                 // the digit whose own limb t is: read from c1
     const ModConst m = mods[gl];
     u128 a0[MR], a1[MR];
     u64 s0[MR], s1[MR], cs[MR];
@@ -270,7 +270,9 @@ __global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, c
 #pragma unroll
             for (u32 r = 0; r < MR; ++r)
                 if (r0 + r < n) {
-                    const u64 d = digits[((size_t)i * n + r0 + r) * dig_w + ((size_t)j * Wl + t) * N + kp];
+                    const u64 d = own == j ? c0_base[(size_t)(r0 + r) * c0_stride_r + rots.c0_off[i] +
+                                                     ((size_t)level + t) * N + kp]
+                                           : digits[((size_t)i * n + r0 + r) * dig_w + ((size_t)j * Wl + t) * N + kp];
                     mac(a0[r], d, k0);
                     mac(a1[r], d, k1);
                 }
@@ -480,7 +482,7 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
                                                                   const double *__restrict__ twf_fwd,
                                                                   const u64 *__restrict__ ninv,
                                                                   const u64 *__restrict__ pinv, u32 n, u32 level,
-                                                                  u32 K, u32 L, u32 beta, u32 logN) {
+                                                                  u32 K, u32 L, u32 beta, u32 alpha, u32 logN) {
     __shared__ u64 lds[FAST_LDS_WORDS];
     const u32 N = 1u << logN;
     const u32 comp = blockIdx.y & 1, r = (blockIdx.y >> 1) % n, i = (blockIdx.y >> 1) / n;
@@ -488,7 +490,11 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
     const SwitchItem &it = pack.it[r];
     const ModConst m = mods[i];
     const u64 *wrow = w + (((size_t)r * 2 + comp) * level + i) * N;
-    const u64 *dig = it.digits + (size_t)i * N;
+    // row of limb i in digit j; the digit that owns limb i is not stored: its row is the source's own
+    const u64 *drow[MAX_BETA];
+#pragma unroll
+    for (u32 j = 0; j < MAX_BETA; ++j)
+        drow[j] = j == i / alpha ? it.c1 + (size_t)i * N : it.digits + ((size_t)j * Wl + i) * N;
     const u64 *key = it.key + ((size_t)comp * Wt + i) * N;
     const u64 *c0 = it.c0 + (size_t)i * N;
     u64 *dst = it.dst + ((size_t)comp * level + i) * N;
@@ -516,8 +522,8 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
 #pragma unroll
             for (u32 j = 0; j < MAX_BETA; ++j)
                 if (j < beta) {
-                    dv[e][0][j] = dig[(size_t)j * Wl * N + kp0];
-                    dv[e][1][j] = dig[(size_t)j * Wl * N + kp1];
+                    dv[e][0][j] = drow[j][kp0];
+                    dv[e][1][j] = drow[j][kp1];
                     kv[e][j] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(key + (size_t)j * 2 * Wt * N + idx));
                 }
             const bool fold = comp == 0 && it.c0;
@@ -601,7 +607,7 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
     const u32 chunks = (Wl + UP_CHUNK - 1) / UP_CHUNK;
 #define MODUP_LAUNCH(A)                                                                                             \
     hipLaunchKernelGGL((modup_kernel<A, 2>), dim3(N / KS_THREADS / 2, beta, n * chunks), dim3(KS_THREADS), 0, stream, \
-                       src, d_tmp, d_digits, p->d_mod, p->d_modf, lt->d_up_inv, lt->d_up_mat, lt->d_up_matf, level, \
+                       d_tmp, d_digits, p->d_mod, p->d_modf, lt->d_up_inv, lt->d_up_mat, lt->d_up_matf, level,      \
                        K, L, alpha, N, chunks, beta, UP_CHUNK)
     if (alpha <= 8)
         MODUP_LAUNCH(8);
@@ -662,7 +668,7 @@ int switch_accumulate_merged(ckks_params *p, u32 level, const MergedRot &rots, u
     const u32 beta = (level + p->alpha - 1) / p->alpha;
     hipLaunchKernelGGL(merged_ip_kernel, dim3(N / KS_THREADS, Wl, (n + MR - 1) / MR), dim3(KS_THREADS), 0, stream, rots,
                        d_digits, digits_words(p, level), c0_base, c0_stride_r, dst_base, dst_stride, d_u, p->d_mod, n,
-                       level, K, L, beta, p->logN, accumulate ? 1u : 0u);
+                       level, K, L, beta, p->alpha, p->logN, accumulate ? 1u : 0u);
     CKKS_LAUNCH_CHECK("merged_ip_kernel");
     return CKKS_OK;
 }
@@ -676,6 +682,7 @@ int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64
     for (u32 r = 0; r < ROT_BATCH; ++r) {
         SwitchItem &it = pack.it[r];
         it.digits = nullptr;
+        it.c1 = nullptr;
         it.c0 = nullptr;                       // already folded in by switch_accumulate_merged
         it.key = nullptr;
         it.dst = dst[r < n ? r : 0];
@@ -730,14 +737,14 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
         if (rc) return rc;
         hipLaunchKernelGGL(passb_final_kernel, dim3(tiles, n * 2 * level), dim3(NTT_THREADS), 0, stream, pack, w,
                            p->d_mod, p->d_modf, p->d_tw_fwd, p->d_twf_fwd, p->d_ninv, p->d_pinv, n, level, K, L, beta,
-                           p->logN);
+                           p->alpha, p->logN);
         CKKS_LAUNCH_CHECK("passb_final_kernel");
         return CKKS_OK;
     }
     u64 *u = d_work;
     u64 *w = d_work + (size_t)n * 2 * Wl * N;
     hipLaunchKernelGGL(inner_product_kernel, dim3(N / KS_THREADS, Wl, n_groups), dim3(KS_THREADS), 0, stream, pack, u,
-                       p->d_mod, level, K, L, beta, p->logN);
+                       p->d_mod, level, K, L, beta, p->alpha, p->logN);
     CKKS_LAUNCH_CHECK("inner_product_kernel");
     for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
     int rc = launch_ntt(p, u, ids, Wl, n * 2 * Wl, true, stream, 3, true);
@@ -798,6 +805,7 @@ int rotate_hoisted(ckks_params *P, const u64 *d_ct_in, u32 level, const int32_t 
         }
         SwitchItem it;
         it.digits = nullptr;
+        it.c1 = d_ct_in + (size_t)level * N;
         it.c0 = d_ct_in;
         it.key = keys[r]->d_key;
         it.dst = d_ct_out + (size_t)r * ctw;
@@ -936,6 +944,7 @@ int ckks_ctmul(ckks_params_t *P, const uint64_t *d_ct_a, const uint64_t *d_ct_b,
     if (rc) return rc;
     SwitchItem it;
     it.digits = d_digits;
+    it.c1 = d_t2;
     it.c0 = nullptr;            // (t0, t1) are already in the output: the switch only adds ModDown(...)
     it.key = relin_key->d_key;
     it.dst = d_ct_out;

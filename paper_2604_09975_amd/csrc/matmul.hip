@@ -730,6 +730,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                 }
                 SwitchItem &it = items[n_it++];
                 it.digits = d_digits + (size_t)r * dig_w;
+                it.c1 = src + (size_t)level * N;
                 it.c0 = src;
                 it.key = bk[q]->d_key;
                 it.dst = dst;
@@ -865,6 +866,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             for (u32 r = 0; r < nb; ++r) {
                 const u64 *src = d_acc + ((size_t)(b0 + r) * N2 + p) * ctw;
                 items[r].digits = d_digits + (size_t)r * dig_w;
+                items[r].c1 = src + (size_t)level * N;
                 items[r].c0 = src;
                 items[r].key = giant_keys[p - 1]->d_key;
                 items[r].dst = d_ct_y + (size_t)(b0 + r) * ctw;   // distinct b within a batch: no two items share dst
@@ -887,6 +889,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             if (rc) return rc;
             for (u32 r = 0; r < nb; ++r) {
                 items[r].digits = d_digits + (size_t)r * dig_w;
+                items[r].c1 = d_ct_y + (size_t)(b0 + r) * ctw + (size_t)level * N;
                 items[r].c0 = d_ct_y + (size_t)(b0 + r) * ctw;
                 items[r].key = conj_key->d_key;
                 items[r].dst = d_acc + (size_t)r * ctw;
