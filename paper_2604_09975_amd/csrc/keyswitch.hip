@@ -21,7 +21,6 @@
 namespace ckks {
 
 constexpr u32 KS_THREADS = EW_THREADS;
-constexpr u32 UP_CHUNK = 16;   // target limbs per workgroup in ModUp (8, 16, 32 measured: 16 is fastest)
 constexpr u32 DN_CHUNK = 24;   // target limbs per workgroup in ModDown (2, 3, 4, 6, 12, 24 measured: fewer, larger groups are faster)
 
 __device__ __forceinline__ u32 galois_index(u32 k, u64 g, u32 logN) {
@@ -68,10 +67,10 @@ __global__ __launch_bounds__(NTT_THREADS) void gather_intt_kernel(PtrPack src, u
 // every target t outside the digit out_t = sum_i y_i * (Q_D/q_i mod t) mod t (coefficient domain).
 // Targets inside the digit are left out: in the NTT domain they are the input's own rows, which the consumers
 // read in place (no copy, no transform).
-// grid: x = pairs of coefficients, y = digit, z = r * chunks + chunk of UP_CHUNK targets.  A thread owns two
+// grid: x = pairs of coefficients, y = digit, z = ciphertext; targets t0 .. t1-1.  A thread owns two
 // adjacent coefficients (16-byte accesses) so that every conversion factor, which is workgroup-uniform and
 // arrives through the scalar cache, serves two multiply-accumulates; AMAX bounds the digit size.
-template <u32 AMAX, u32 VEC>
+template <u32 AMAX, u32 VEC, bool FP>
 __global__ __launch_bounds__(KS_THREADS) void modup_kernel(const u64 *__restrict__ c1_coeff,
                                                            u64 *__restrict__ digits,
                                                            const ModConst *__restrict__ mods,
@@ -79,11 +78,11 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(const u64 *__restrict
                                                            const u64 *__restrict__ up_inv,
                                                            const u64 *__restrict__ up_mat,
                                                            const u64 *__restrict__ up_matf, u32 level, u32 K, u32 L,
-                                                           u32 alpha, u32 N, u32 chunks, u32 beta, u32 up_chunk) {
+                                                           u32 alpha, u32 N, u32 beta, u32 t0, u32 t1) {
     typedef u64 vec_t __attribute__((ext_vector_type(2)));
     const u32 n = (blockIdx.x * KS_THREADS + threadIdx.x) * VEC;
     const u32 j = blockIdx.y;
-    const u32 r = blockIdx.z / chunks, chunk = blockIdx.z % chunks;
+    const u32 r = blockIdx.z;
     const u32 Wl = level + K;
     const u32 lo = j * alpha, hi = min(lo + alpha, level);
     const u64 *coef = c1_coeff + (size_t)r * level * N;
@@ -104,25 +103,19 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(const u64 *__restrict
             }
         }
     }
-    // Targets below 2^50 fed by a digit of primes below 2^50 are converted in fp64 (twice the multiply rate of
-    // the 32-bit integer pipeline): y is exact in a double, every product is split exactly into h + l and
-    // brought below 0.9 q before it is added, and the partial sum is reduced every four terms (below 2^53).
-    bool digit_fp = true;
+    if (FP) {
+        // Every prime involved is below 2^50 (the launcher checks): y is exact in a double, every product is
+        // split exactly into h + l and brought below 0.9 q before it is added, and the partial sum is reduced
+        // every four terms (below 2^53).  Twice the multiply rate of the 32-bit integer pipeline.
+        double yd[AMAX][VEC];
 #pragma unroll
-    for (u32 a = 0; a < AMAX; ++a)
-        if (lo + a < hi) digit_fp = digit_fp && modf[lo + a].ok;
-    double yd[AMAX][VEC];
+        for (u32 a = 0; a < AMAX; ++a)
 #pragma unroll
-    for (u32 a = 0; a < AMAX; ++a)
-#pragma unroll
-        for (u32 e = 0; e < VEC; ++e) yd[a][e] = digit_fp ? (double)y[a][e] : 0.0;
-    const u32 t0 = chunk * up_chunk, t1 = min(t0 + up_chunk, Wl);
-    for (u32 t = t0; t < t1; ++t) {
-        u64 *dst = dig + ((size_t)j * Wl + t) * N + n;
-        if (t >= lo && t < hi) continue;      // the digit's own limbs: consumers read them from the source
-        const u32 gl = t < level ? t : L + (t - level);
-        if (digit_fp && modf[gl].ok) {
-            const double q = modf[gl].q, u = modf[gl].u;
+            for (u32 e = 0; e < VEC; ++e) yd[a][e] = (double)y[a][e];
+        for (u32 t = t0; t < t1; ++t) {
+            if (t >= lo && t < hi) continue;      // the digit's own limbs: consumers read them from the source
+            u64 *dst = dig + ((size_t)j * Wl + t) * N + n;
+            const double q = modf[t].q, u = modf[t].u;
             double fd[AMAX], acc[VEC];
 #pragma unroll
             for (u32 a = 0; a < AMAX; ++a)
@@ -149,25 +142,30 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(const u64 *__restrict
                 }
                 *reinterpret_cast<vec_t *>(dst + e) = o;
             }
-            continue;
         }
-        u64 f[AMAX];
+    } else {
+        for (u32 t = t0; t < t1; ++t) {
+            if (t >= lo && t < hi) continue;
+            u64 *dst = dig + ((size_t)j * Wl + t) * N + n;
+            const u32 gl = t < level ? t : L + (t - level);
+            u64 f[AMAX];
 #pragma unroll
-        for (u32 a = 0; a < AMAX; ++a) f[a] = lo + a < hi ? up_mat[(size_t)(lo + a) * Wl + t] : 0;
-        u128 acc[VEC];
+            for (u32 a = 0; a < AMAX; ++a) f[a] = lo + a < hi ? up_mat[(size_t)(lo + a) * Wl + t] : 0;
+            u128 acc[VEC];
 #pragma unroll
-        for (u32 e = 0; e < VEC; ++e) acc[e] = {0, 0};
+            for (u32 e = 0; e < VEC; ++e) acc[e] = {0, 0};
 #pragma unroll
-        for (u32 a = 0; a < AMAX; ++a)        // a factor of 0 pads digits shorter than AMAX
+            for (u32 a = 0; a < AMAX; ++a)        // a factor of 0 pads digits shorter than AMAX
 #pragma unroll
-            for (u32 e = 0; e < VEC; ++e) mac(acc[e], y[a][e], f[a]);
-        const ModConst mt = mods[gl];
+                for (u32 e = 0; e < VEC; ++e) mac(acc[e], y[a][e], f[a]);
+            const ModConst mt = mods[gl];
 #pragma unroll
-        for (u32 e = 0; e < VEC; e += 2) {
-            vec_t o;
-            o[0] = redc_wide(acc[e], mt);     // up to AMAX products below 2^62 * q each
-            o[1] = redc_wide(acc[e + 1], mt);
-            *reinterpret_cast<vec_t *>(dst + e) = o;
+            for (u32 e = 0; e < VEC; e += 2) {
+                vec_t o;
+                o[0] = redc_wide(acc[e], mt);     // up to AMAX products below 2^62 * q each
+                o[1] = redc_wide(acc[e + 1], mt);
+                *reinterpret_cast<vec_t *>(dst + e) = o;
+            }
         }
     }
 }
@@ -604,15 +602,27 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
         rc = launch_ntt(p, d_tmp, ids, level, n * level, true, stream);
     }
     if (rc) return rc;
-    const u32 chunks = (Wl + UP_CHUNK - 1) / UP_CHUNK;
-#define MODUP_LAUNCH(A)                                                                                             \
-    hipLaunchKernelGGL((modup_kernel<A, 2>), dim3(N / KS_THREADS / 2, beta, n * chunks), dim3(KS_THREADS), 0, stream, \
-                       d_tmp, d_digits, p->d_mod, p->d_modf, lt->d_up_inv, lt->d_up_mat, lt->d_up_matf, level,      \
-                       K, L, alpha, N, chunks, beta, UP_CHUNK)
-    if (alpha <= 8)
-        MODUP_LAUNCH(8);
-    else
-        MODUP_LAUNCH(MAX_DIGIT);
+    // two launches: the ciphertext-prime targets (fp64 arithmetic when every active prime is below 2^50) and the
+    // special-prime targets (integer arithmetic); each keeps only its own form of y in registers
+    bool all_fp = true;
+    for (u32 i = 0; i < level; ++i) all_fp = all_fp && (p->mod[i] >> 50) == 0;
+#define MODUP_LAUNCH(A, FPK, T0, T1)                                                                               \
+    hipLaunchKernelGGL((modup_kernel<A, 2, FPK>), dim3(N / KS_THREADS / 2, beta, n), dim3(KS_THREADS), 0, stream,   \
+                       d_tmp, d_digits, p->d_mod, p->d_modf, lt->d_up_inv, lt->d_up_mat, lt->d_up_matf, level, K,   \
+                       L, alpha, N, beta, T0, T1)
+    if (alpha <= 8) {
+        if (all_fp)
+            MODUP_LAUNCH(8, true, 0u, level);
+        else
+            MODUP_LAUNCH(8, false, 0u, level);
+        MODUP_LAUNCH(8, false, level, Wl);
+    } else {
+        if (all_fp)
+            MODUP_LAUNCH(MAX_DIGIT, true, 0u, level);
+        else
+            MODUP_LAUNCH(MAX_DIGIT, false, 0u, level);
+        MODUP_LAUNCH(MAX_DIGIT, false, level, Wl);
+    }
 #undef MODUP_LAUNCH
     CKKS_LAUNCH_CHECK("modup_kernel");
     // forward NTT of the converted rows; the digit's own limbs were copied and are skipped
