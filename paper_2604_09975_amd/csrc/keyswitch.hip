@@ -314,14 +314,13 @@ __global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, c
     }
 }
 
-template <u32 KMAX>
+template <u32 KMAX, bool FP>
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__restrict__ y, u64 *__restrict__ w,
                                                                   const ModConst *__restrict__ mods,
                                                                   const ModFp *__restrict__ modf,
                                                                   const u64 *__restrict__ dn_mat,
                                                                   const double *__restrict__ dn_matf, u32 level,
-                                                                  u32 K, u32 L, u32 N, u32 ystride, u32 yoff,
-                                                                  u32 fp_ok) {
+                                                                  u32 K, u32 L, u32 N, u32 ystride, u32 yoff) {
     const u32 n = blockIdx.x * KS_THREADS + threadIdx.x;
     const u32 pc = blockIdx.y;   // (item, component)
     u64 yk[KMAX];
@@ -330,21 +329,23 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__r
         yk[k] = 0;
         if (k < K) yk[k] = y[((size_t)pc * ystride + yoff + k) * N + n];
     }
-    // Targets below 2^50 (special primes below 2^60): every y_k is cut into three 20-bit pieces and every factor
-    // (times 2^0, 2^20, 2^40, reduced) into two 25-bit halves, all held as doubles.  The 45-bit products are
-    // summed exactly by FMAs into a low and a high sum (3*KMAX terms each, below 2^53), and the result is
-    // (high * 2^25 + low) mod q: the 32-bit integer multiplier, four times slower per product, stays out of it.
-    double yp[KMAX][3];
-#pragma unroll
-    for (u32 k = 0; k < KMAX; ++k) {
-        const u64 v = fp_ok ? yk[k] : 0;
-        yp[k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
-        yp[k][1] = __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
-        yp[k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
-    }
     const u32 i0 = blockIdx.z * DN_CHUNK, i1 = min(i0 + DN_CHUNK, level);
-    for (u32 i = i0; i < i1; ++i) {
-        if (fp_ok && modf[i].ok) {
+    if (FP) {
+        // Every target below 2^50 and every special prime below 2^60 (the launcher checks): each y_k is cut into
+        // three 20-bit pieces and each factor (times 2^0, 2^20, 2^40, reduced) into two 25-bit halves, all held
+        // as doubles.  The 45-bit products are summed exactly by FMAs into a low and a high sum (3*KMAX terms
+        // each, below 2^53), and the result is (high * 2^25 + low) mod q: the 32-bit integer multiplier, four
+        // times slower per product, stays out of it.
+        double yp[KMAX][3];
+#pragma unroll
+        for (u32 k = 0; k < KMAX; ++k) {
+            const u64 v = yk[k];
+            yp[k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
+            yp[k][1] =
+                __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
+            yp[k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
+        }
+        for (u32 i = i0; i < i1; ++i) {
             const double q = modf[i].q, u = modf[i].u;
             const double *f = dn_matf + (size_t)i * K * 6;
             double lo = 0.0, hi = 0.0;
@@ -362,13 +363,15 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__r
             v = fma(-rint(v * u), q, v);
             if (v < 0) v += q;
             w[((size_t)pc * level + i) * N + n] = (u64)v;
-            continue;
         }
-        u128 acc = {0, 0};
+    } else {
+        for (u32 i = i0; i < i1; ++i) {
+            u128 acc = {0, 0};
 #pragma unroll
-        for (u32 k = 0; k < KMAX; ++k)
-            if (k < K) mac(acc, yk[k], dn_mat[(size_t)k * L + i]);
-        w[((size_t)pc * level + i) * N + n] = redc_wide(acc, mods[i]);   // up to 16 products below 2^62 * q each
+            for (u32 k = 0; k < KMAX; ++k)
+                if (k < K) mac(acc, yk[k], dn_mat[(size_t)k * L + i]);
+            w[((size_t)pc * level + i) * N + n] = redc_wide(acc, mods[i]);   // up to 16 products below 2^62 * q each
+        }
     }
 }
 
@@ -376,13 +379,17 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__r
 static void launch_moddown_conv(const ckks_params *p, const u64 *y, u64 *w, u32 n, u32 level, u32 ystride, u32 yoff,
                                 hipStream_t stream) {
     const dim3 grid(p->N / KS_THREADS, n * 2, (level + DN_CHUNK - 1) / DN_CHUNK);
-    if (p->K <= 8)
-        hipLaunchKernelGGL(moddown_conv_kernel<8>, grid, dim3(KS_THREADS), 0, stream, y, w, p->d_mod, p->d_modf,
-                           p->d_dn_mat, p->d_dn_matf, level, p->K, p->L, p->N, ystride, yoff, p->dn_fp ? 1u : 0u);
-    else
-        hipLaunchKernelGGL(moddown_conv_kernel<MAX_DIGIT>, grid, dim3(KS_THREADS), 0, stream, y, w, p->d_mod,
-                           p->d_modf, p->d_dn_mat, p->d_dn_matf, level, p->K, p->L, p->N, ystride, yoff,
-                           p->dn_fp ? 1u : 0u);
+    bool fp = p->dn_fp;        // fp64 sums need every target below 2^50 and every special prime below 2^60
+    for (u32 i = 0; i < level; ++i) fp = fp && (p->mod[i] >> 50) == 0;
+#define CONV_LAUNCH(KM, FPK)                                                                                      \
+    hipLaunchKernelGGL((moddown_conv_kernel<KM, FPK>), grid, dim3(KS_THREADS), 0, stream, y, w, p->d_mod, p->d_modf, \
+                       p->d_dn_mat, p->d_dn_matf, level, p->K, p->L, p->N, ystride, yoff)
+    if (p->K <= 8) {
+        if (fp) CONV_LAUNCH(8, true); else CONV_LAUNCH(8, false);
+    } else {
+        if (fp) CONV_LAUNCH(MAX_DIGIT, true); else CONV_LAUNCH(MAX_DIGIT, false);
+    }
+#undef CONV_LAUNCH
 }
 
 // dst[comp][i][k] (+)= (u_{q_i} - NTT(w_i)) * P^-1  (+ sigma_g(c0)[i][k] for comp 0)
