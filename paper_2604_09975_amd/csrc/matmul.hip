@@ -220,26 +220,27 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
             for (u32 e = 0; e < 4; ++e)
                 x[c][e] = __longlong_as_double((long long)(r[e] | 0x4330000000000000ull)) - 4503599627370496.0;
         }
-        wvec_t wc[TB];
+        // the weights leave their load registers as doubles before the next step's loads are issued into them
+        double wd[TB][2];
 #pragma unroll
-        for (u32 t = 0; t < TB; ++t) wc[t] = wb[t];
+        for (u32 t = 0; t < TB; ++t) {
+            if (PACKED) {
+                const u32 top = wb[t][3] >> top_shift;
+                const u32 h0 = 0x43300000u | ((top & 3u) << 16) | (wb[t][2] & 0xffffu);
+                const u32 h1 = 0x43300000u | ((top & 12u) << 14) | (wb[t][2] >> 16);
+                wd[t][0] = __hiloint2double((int)h0, (int)wb[t][0]) - 4503599627370496.0;
+                wd[t][1] = __hiloint2double((int)h1, (int)wb[t][1]) - 4503599627370496.0;
+            } else {
+                wd[t][0] = __hiloint2double((int)wb[t][1], (int)wb[t][0]);
+                wd[t][1] = __hiloint2double((int)wb[t][3], (int)wb[t][2]);
+            }
+        }
         if (gq + 1 < GQ) fetch(gq + 1);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t) {
             if (bp0 + t < BP) {
                 // weight of k serves k and N-1-k; weight of k+1 serves k+1 and N-2-k
-                double w0, w1;
-                if (PACKED) {
-                    const u32 top = wc[t][3] >> top_shift;
-                    const u32 h0 = 0x43300000u | ((top & 3u) << 16) | (wc[t][2] & 0xffffu);
-                    const u32 h1 = 0x43300000u | ((top & 12u) << 14) | (wc[t][2] >> 16);
-                    w0 = __hiloint2double((int)h0, (int)wc[t][0]) - 4503599627370496.0;
-                    w1 = __hiloint2double((int)h1, (int)wc[t][1]) - 4503599627370496.0;
-                } else {
-                    w0 = __hiloint2double((int)wc[t][1], (int)wc[t][0]);
-                    w1 = __hiloint2double((int)wc[t][3], (int)wc[t][2]);
-                }
-                const double wv[4] = {w0, w1, w1, w0};
+                const double wv[4] = {wd[t][0], wd[t][1], wd[t][1], wd[t][0]};
 #pragma unroll
                 for (u32 c = 0; c < 2; ++c)
 #pragma unroll
