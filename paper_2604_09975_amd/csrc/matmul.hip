@@ -48,14 +48,35 @@ __global__ __launch_bounds__(EW_THREADS) void scale_rows_kernel(u64 *data, const
 // blockIdx.z indexes `limbs`, the list of limbs this launch covers (fp64 limbs and Montgomery limbs
 // go to separate launches so that each kernel keeps its own register budget).
 // Each thread owns VEC adjacent coefficients (16-byte loads for VEC = 2) and TB (b,p) accumulators.
-template <u32 TB, u32 VEC>
+// Packed weight records: 50 bits per residue instead of 64, in three parts: the low 32 bits, bits 32..47, and
+// bits 48..49 four residues to a byte.  A half record holds the first N/2 residues of a limb (real diagonals,
+// the rest is the mirror image), a whole-limb record all N.
+__host__ __device__ inline size_t packed_record_bytes(u32 N) { return (size_t)3 * N + N / 8; }
+// A record is a sequence of 800-byte chunks of 128 residues (what one wavefront reads per weight limb and step):
+// 512 bytes of low words, 256 of middle halves, 32 of top bits, so that the three loads of a wavefront fall into
+// one contiguous piece of memory.  Byte offsets of residue k's parts within the record:
+__host__ __device__ inline u32 packed_lo(u32 k) { return (k >> 7) * 800u + 4u * (k & 127u); }
+__host__ __device__ inline u32 packed_hi(u32 k) { return (k >> 7) * 800u + 512u + 2u * (k & 127u); }
+__host__ __device__ inline u32 packed_top(u32 k) { return (k >> 7) * 800u + 768u + ((k & 127u) >> 2); }
+
+// PACKED (VEC = 2): the weight limbs are whole-limb packed records.
+template <u32 TB, u32 VEC, bool PACKED>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restrict__ bank,
                                                               const u64 *__restrict__ w, u64 *__restrict__ acc,
                                                               const ModFp *__restrict__ modf, LimbIds limbs,
-                                                              u32 level, u32 N, u32 GQ, u32 BP) {
+                                                              u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle) {
+    static_assert(!PACKED || VEC == 2, "packed weights are read in pairs");
     typedef u64 vec_t __attribute__((ext_vector_type(VEC)));
-    const u32 bp0 = blockIdx.x * TB;
-    const u32 k = (blockIdx.y * MM_THREADS + threadIdx.x) * VEC;
+    // swizzle: one XCD walks all (b,p) tiles of a run of coefficients back to back (see diag_mac_sym_kernel)
+    u32 tile = blockIdx.x, run = blockIdx.y;
+    if (swizzle) {
+        const u32 lin = blockIdx.y * gridDim.x + blockIdx.x;
+        const u32 xcd = lin & 7, slot = lin >> 3;
+        tile = slot % gridDim.x;
+        run = (slot / gridDim.x) * 8 + xcd;
+    }
+    const u32 bp0 = tile * TB;
+    const u32 k = (run * MM_THREADS + threadIdx.x) * VEC;
     const u32 i = limbs.id[blockIdx.z];
     const size_t limb_off = (size_t)i * N + k;
     const size_t w_stride = (size_t)level * N;         // between consecutive gq of one (b,p)
@@ -67,14 +88,38 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
 #pragma unroll
         for (u32 e = 0; e < VEC; ++e) a0[t][e] = a1[t][e] = 0.0;
     // loads of step gq+1 are issued before the arithmetic of step gq
-    vec_t xb0, xb1, wb[TB];
+    typedef u32 wvec_t __attribute__((ext_vector_type(4)));
+    vec_t xb0, xb1;
+    wvec_t wb[TB];
+    const size_t rec = 2 * packed_record_bytes(N);
+    const unsigned char *wbytes = reinterpret_cast<const unsigned char *>(w);
+    const u32 off_lo = packed_lo(k), off_hi = packed_hi(k), off_top = packed_top(k);
+    const u32 top_shift = (k & 2) * 2;
     auto fetch = [&](u32 gq) {
         xb0 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 0) * w_stride + limb_off);
         xb1 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 1) * w_stride + limb_off);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t)
-            if (bp0 + t < BP)
-                wb[t] = *reinterpret_cast<const vec_t *>(w + ((size_t)(bp0 + t) * GQ + gq) * w_stride + limb_off);
+            if (bp0 + t < BP) {
+                if (PACKED) {
+                    const unsigned char *r = wbytes + (((size_t)(bp0 + t) * GQ + gq) * level + i) * rec;
+                    const __amdgpu_buffer_rsrc_t rs =
+                        __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(r), 0, (int)rec, 0x00020000);
+                    typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 lo = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)off_lo, 0, 0);
+                    wb[t][0] = lo[0];
+                    wb[t][1] = lo[1];
+                    wb[t][2] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)off_hi, 0, 0);
+                    wb[t][3] = __builtin_amdgcn_raw_buffer_load_b8(rs, (int)off_top, 0, 0);
+                } else {
+                    const vec_t v = *reinterpret_cast<const vec_t *>(w + ((size_t)(bp0 + t) * GQ + gq) * w_stride + limb_off);
+#pragma unroll
+                    for (u32 e = 0; e < VEC; ++e) {
+                        wb[t][2 * e] = (u32)v[e];
+                        wb[t][2 * e + 1] = (u32)(v[e] >> 32);
+                    }
+                }
+            }
     };
     fetch(0);
     for (u32 gq = 0; gq < GQ; ++gq) {
@@ -84,16 +129,27 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
             x0[e] = __longlong_as_double((long long)(xb0[e] | 0x4330000000000000ull)) - 4503599627370496.0;
             x1[e] = __longlong_as_double((long long)(xb1[e] | 0x4330000000000000ull)) - 4503599627370496.0;
         }
-        vec_t wc[TB];
+        double wd[TB][VEC];
 #pragma unroll
-        for (u32 t = 0; t < TB; ++t) wc[t] = wb[t];
+        for (u32 t = 0; t < TB; ++t) {
+            if (PACKED) {
+                const u32 top = wb[t][3] >> top_shift;
+                const u32 h0 = 0x43300000u | ((top & 3u) << 16) | (wb[t][2] & 0xffffu);
+                const u32 h1 = 0x43300000u | ((top & 12u) << 14) | (wb[t][2] >> 16);
+                wd[t][0] = __hiloint2double((int)h0, (int)wb[t][0]) - 4503599627370496.0;
+                wd[t][VEC - 1] = __hiloint2double((int)h1, (int)wb[t][1]) - 4503599627370496.0;
+            } else {
+#pragma unroll
+                for (u32 e = 0; e < VEC; ++e) wd[t][e] = __hiloint2double((int)wb[t][2 * e + 1], (int)wb[t][2 * e]);
+            }
+        }
         if (gq + 1 < GQ) fetch(gq + 1);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t) {
             if (bp0 + t < BP) {
 #pragma unroll
                 for (u32 e = 0; e < VEC; ++e) {
-                    const double wv = __longlong_as_double((long long)wc[t][e]);
+                    const double wv = wd[t][e];
                     // x*w = h + l exactly; subtract the nearest multiple of q: |r| < 0.9 q
                     const double h0 = x0[e] * wv, h1 = x1[e] * wv;
                     const double l0 = fma(x0[e], wv, -h0), l1 = fma(x1[e], wv, -h1);
@@ -141,14 +197,6 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
 // PACKED: the half limb is stored in 50 bits per residue instead of 64 (packed_record_bytes) in three parts,
 // the low 32 bits, bits 32..47, and bits 48..49 four residues to a byte.  The double is rebuilt as
 // (2^52 + x) - 2^52 from the bit pattern, one addition per weight.
-__host__ __device__ inline size_t packed_record_bytes(u32 N) { return (size_t)3 * N + N / 8; }
-// A record is a sequence of 800-byte chunks of 128 residues (what one wavefront reads per weight limb and step):
-// 512 bytes of low words, 256 of middle halves, 32 of top bits, so that the three loads of a wavefront fall into
-// one contiguous piece of memory.  Byte offsets of residue k's parts within the record:
-__host__ __device__ inline u32 packed_lo(u32 k) { return (k >> 7) * 800u + 4u * (k & 127u); }
-__host__ __device__ inline u32 packed_hi(u32 k) { return (k >> 7) * 800u + 512u + 2u * (k & 127u); }
-__host__ __device__ inline u32 packed_top(u32 k) { return (k >> 7) * 800u + 768u + ((k & 127u) >> 2); }
-
 template <u32 TB, bool PACKED>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__restrict__ bank,
                                                                   const u64 *__restrict__ w, u64 *__restrict__ acc,
@@ -297,11 +345,12 @@ __global__ __launch_bounds__(EW_THREADS) void check_real_kernel(const int64_t *_
 // rows [rows][N] of canonical residues below 2^50 -> packed half-limb records (first N/2 residues of each row);
 // a thread packs four residues
 __global__ __launch_bounds__(EW_THREADS) void pack_half_kernel(const u64 *__restrict__ in,
-                                                               unsigned char *__restrict__ out, u32 N) {
+                                                               unsigned char *__restrict__ out, u32 N, u32 cnt) {
+    // cnt = N/2 (half records of real diagonals) or N (whole limbs of general ones)
     const u32 k = (blockIdx.x * EW_THREADS + threadIdx.x) * 4;
-    if (k >= N / 2) return;
+    if (k >= cnt) return;
     const u64 *src = in + (size_t)blockIdx.y * N + k;
-    unsigned char *r = out + (size_t)blockIdx.y * packed_record_bytes(N);
+    unsigned char *r = out + (size_t)blockIdx.y * (cnt == N ? 2 : 1) * packed_record_bytes(N);
     uint4 lo;
     uint2 hi;
     const u64 x0 = src[0], x1 = src[1], x2 = src[2], x3 = src[3];
@@ -317,19 +366,24 @@ __global__ __launch_bounds__(EW_THREADS) void pack_half_kernel(const u64 *__rest
         (unsigned char)(((x0 >> 48) & 3) | (((x1 >> 48) & 3) << 2) | (((x2 >> 48) & 3) << 4) | (((x3 >> 48) & 3) << 6));
 }
 
-// packed records [rows] -> full rows [rows][N] of doubles (the general kernels' weight form), second half mirrored
-__global__ __launch_bounds__(EW_THREADS) void unpack_half_kernel(const unsigned char *__restrict__ in,
-                                                                 u64 *__restrict__ out, u32 N) {
-    const u32 k = blockIdx.x * EW_THREADS + threadIdx.x;
-    if (k >= N / 2) return;
+// half records [rows] -> whole-limb records [rows]: residue k of the second half is residue N-1-k of the first
+__global__ __launch_bounds__(EW_THREADS) void widen_half_kernel(const unsigned char *__restrict__ in,
+                                                                unsigned char *__restrict__ out, u32 N) {
+    const u32 k = (blockIdx.x * EW_THREADS + threadIdx.x) * 4;
+    if (k >= N) return;
     const unsigned char *r = in + (size_t)blockIdx.y * packed_record_bytes(N);
-    const u64 lo = *reinterpret_cast<const u32 *>(r + packed_lo(k));
-    const u64 hi = *reinterpret_cast<const unsigned short *>(r + packed_hi(k));
-    const u64 top = (r[packed_top(k)] >> ((k & 3) * 2)) & 3;
-    const u64 x = lo | (hi << 32) | (top << 48);
-    const u64 d = (u64)__double_as_longlong((double)x);
-    out[(size_t)blockIdx.y * N + k] = d;
-    out[(size_t)blockIdx.y * N + (N - 1 - k)] = d;
+    unsigned char *o = out + (size_t)blockIdx.y * 2 * packed_record_bytes(N);
+    u32 lo[4], hi[4], top = 0;
+#pragma unroll
+    for (u32 e = 0; e < 4; ++e) {
+        const u32 s = k + e < N / 2 ? k + e : N - 1 - (k + e);
+        lo[e] = *reinterpret_cast<const u32 *>(r + packed_lo(s));
+        hi[e] = *reinterpret_cast<const unsigned short *>(r + packed_hi(s));
+        top |= ((r[packed_top(s)] >> ((s & 3) * 2)) & 3u) << (2 * e);
+    }
+    *reinterpret_cast<uint4 *>(o + packed_lo(k)) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    *reinterpret_cast<uint2 *>(o + packed_hi(k)) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+    o[packed_top(k)] = (unsigned char)top;
 }
 
 __global__ __launch_bounds__(EW_THREADS) void fill_u32_kernel(u32 *p, u32 v, u32 n) {
@@ -517,30 +571,31 @@ int ensure_full_store(ckks_weights *w) {
     return CKKS_OK;
 }
 
-int ensure_packed_store(ckks_weights *w) {
+// whole: the store of whole-limb records (general diagonals) instead of the store of half records (real ones)
+int ensure_packed_store(ckks_weights *w, bool whole) {
     const u32 N = w->params->N;
-    if (!w->d_wp) {
-        const size_t recs = (size_t)w->B_out * w->N2 * w->G * w->N1 * w->level;
-        CKKS_HIP(hipMalloc((void **)&w->d_wp, recs * packed_record_bytes(N)));
-    }
+    const size_t recs = (size_t)w->B_out * w->N2 * w->G * w->N1 * w->level;
+    if (!whole && !w->d_wp) CKKS_HIP(hipMalloc((void **)&w->d_wp, recs * packed_record_bytes(N)));
+    if (whole && !w->d_wpf) CKKS_HIP(hipMalloc((void **)&w->d_wpf, recs * 2 * packed_record_bytes(N)));
     if (!w->d_stage) CKKS_HIP(hipMalloc((void **)&w->d_stage, (size_t)STAGE_DIAGS * w->level * N * sizeof(u64)));
     return CKKS_OK;
 }
 
-// A packed block receives a diagonal that is not real: its diagonals move to the full store.
-int unpack_block(ckks_weights *w, u32 b, hipStream_t stream) {
-    int rc = ensure_full_store(w);
+// A block of half records receives a diagonal that is not real: its diagonals move to the whole-limb store.
+int widen_block(ckks_weights *w, u32 b, hipStream_t stream) {
+    int rc = ensure_packed_store(w, true);
     if (rc) return rc;
     const u32 N = w->params->N;
     const size_t rows = (size_t)w->N2 * w->G * w->N1 * w->level, first = (size_t)b * rows;
     for (size_t done = 0; done < rows;) {
         const u32 c = (u32)std::min<size_t>(rows - done, 32768);
-        hipLaunchKernelGGL(unpack_half_kernel, dim3((N / 2 + EW_THREADS - 1) / EW_THREADS, c), dim3(EW_THREADS), 0,
-                           stream, w->d_wp + (first + done) * packed_record_bytes(N), w->d_w + (first + done) * N, N);
-        CKKS_LAUNCH_CHECK("unpack_half_kernel");
+        hipLaunchKernelGGL(widen_half_kernel, dim3((N / 4 + EW_THREADS - 1) / EW_THREADS, c), dim3(EW_THREADS), 0,
+                           stream, w->d_wp + (first + done) * packed_record_bytes(N),
+                           w->d_wpf + (first + done) * 2 * packed_record_bytes(N), N);
+        CKKS_LAUNCH_CHECK("widen_half_kernel");
         done += c;
     }
-    w->block_packed[b] = 0;
+    w->block_packed[b] = 2;
     return CKKS_OK;
 }
 
@@ -586,24 +641,28 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
             bool all_real = true;
             for (u32 d = lo; d < hi; ++d) all_real = all_real && flags[d - first];
             if (!all_real) w->block_real[b] = 0;
-            // a block that is still real has either nothing loaded yet or everything so far in the packed store
-            const bool packed = w->packable && w->block_real[b];
             int rc;
-            if (packed) {
-                if ((rc = ensure_packed_store(w))) return rc;
-                w->block_packed[b] = 1;
+            if (w->packable) {
+                // a block that is still real has either nothing loaded yet or half records only; a general block
+                // keeps whole-limb records (half records stored before the first general diagonal are widened)
+                const bool whole = !w->block_real[b];
+                if (whole && w->block_packed[b] == 1 && (rc = widen_block(w, b, (hipStream_t)stream))) return rc;
+                if ((rc = ensure_packed_store(w, whole))) return rc;
+                w->block_packed[b] = whole ? 2 : 1;
+                const size_t recb = (whole ? 2 : 1) * packed_record_bytes(N);
+                unsigned char *store = whole ? w->d_wpf : w->d_wp;
+                const u32 cnt = whole ? N : N / 2;
                 for (u32 d = lo; d < hi; d += STAGE_DIAGS) {
                     const u32 c = std::min(STAGE_DIAGS, hi - d);
                     rc = expand_plain(P, level, d_coeffs + (size_t)(d - first) * N, c, w->d_stage, false,
                                       (hipStream_t)stream);
                     if (rc) return rc;
-                    hipLaunchKernelGGL(pack_half_kernel, dim3((N / 8 + EW_THREADS - 1) / EW_THREADS, c * level),
+                    hipLaunchKernelGGL(pack_half_kernel, dim3((cnt / 4 + EW_THREADS - 1) / EW_THREADS, c * level),
                                        dim3(EW_THREADS), 0, (hipStream_t)stream, w->d_stage,
-                                       w->d_wp + (size_t)d * level * packed_record_bytes(N), N);
+                                       store + (size_t)d * level * recb, N, cnt);
                     CKKS_LAUNCH_CHECK("pack_half_kernel");
                 }
             } else {
-                if (w->block_packed[b] && (rc = unpack_block(w, b, (hipStream_t)stream))) return rc;
                 if ((rc = ensure_full_store(w))) return rc;
                 rc = expand_plain(P, level, d_coeffs + (size_t)(lo - first) * N, hi - lo,
                                   w->d_w + (size_t)lo * level * N, true, (hipStream_t)stream);
@@ -634,6 +693,7 @@ void ckks_weights_destroy(ckks_weights_t *w) {
     if (!w) return;
     hipFree(w->d_w);
     hipFree(w->d_wp);
+    hipFree(w->d_wpf);
     hipFree(w->d_stage);
     hipFree(w->d_bias);
     hipFree(w->d_flag);
@@ -771,23 +831,31 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             while (b1 < B && w->block_real[b1] == w->block_real[b0] && w->block_packed[b1] == w->block_packed[b0])
                 ++b1;
             const u32 bp_first = b0 * N2, bp_count = (b1 - b0) * N2;
-            const u64 *wp = w->d_w + (size_t)bp_first * GQ * level * N;
+            const u64 *wp = w->d_w ? w->d_w + (size_t)bp_first * GQ * level * N : nullptr;
             u64 *ap = d_acc + (size_t)bp_first * ctw;
             const u32 runs = N / (4 * MM_THREADS);
             const dim3 sym_grid((bp_count + MM_TB - 1) / MM_TB, runs, n_fp);
             // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
-            if (w->block_packed[b0]) {
+            if (w->block_packed[b0] == 1) {
                 const u64 *pp = reinterpret_cast<const u64 *>(w->d_wp + (size_t)bp_first * GQ * level *
                                                                             packed_record_bytes(N));
                 hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, true>), sym_grid, dim3(MM_THREADS), 0, stream, d_bank,
                                    pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count, runs % 8 == 0 ? 1u : 0u);
+            } else if (w->block_packed[b0] == 2) {
+                const u64 *pp = reinterpret_cast<const u64 *>(w->d_wpf + (size_t)bp_first * GQ * level * 2 *
+                                                                             packed_record_bytes(N));
+                hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2, true>),
+                                   dim3((bp_count + MM_TB - 1) / MM_TB, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS), 0,
+                                   stream, d_bank, pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
+                                   (N / MM_THREADS / 2) % 8 == 0 ? 1u : 0u);
             } else if (w->block_real[b0] && N >= 4 * MM_THREADS) {
                 hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, false>), sym_grid, dim3(MM_THREADS), 0, stream, d_bank,
                                    wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count, runs % 8 == 0 ? 1u : 0u);
             } else {   // 8 accumulators x 2 coefficients per thread (16-byte loads)
-                hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2>),
+                hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2, false>),
                                    dim3((bp_count + MM_TB - 1) / MM_TB, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS), 0,
-                                   stream, d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count);
+                                   stream, d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
+                                   (N / MM_THREADS / 2) % 8 == 0 ? 1u : 0u);
             }
             b0 = b1;
         }
