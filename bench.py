@@ -29,9 +29,11 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False):
+def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False, pairs=False):
     """fused_qk: the d_out columns are [Q | K | V]; Q and K go through ONE projection with the complex weights
-    W_Q + i*W_K (App. A.2.3), V through real weights: 2/3 of the output blocks and giant steps."""
+    W_Q + i*W_K (App. A.2.3), V through real weights: 2/3 of the output blocks and giant steps.
+    pairs: complex-pair compression of Sec. 3.2: inputs x^(2u) + i*x^(2u+1), weights (W_even - i*W_odd)/2, one
+    conjugation per output block brings back the real result: half the bank and half the products."""
     import torch
     N, n = P.N, P.N // 2
     level = P.L
@@ -42,6 +44,8 @@ def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False):
         parts = [(Wm[:, :third] + 1j * Wm[:, third:2 * third], 0), (Wm[:, 2 * third:], -(-third // spec.C))]
         bias = None
     G = -(-spec.d_in // spec.C)
+    if pairs:
+        G = -(-G // 2)                                       # complexified inputs
     B_out = sum(-(-M.shape[1] // spec.C) for M, _ in parts)
     N2 = spec.C // n1
     scale = 2.0 ** spec.ring.log_scale
@@ -56,14 +60,18 @@ def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False):
     baby = [key(q * spec.m) for q in range(1, n1)]
     giant = [key(p * n1 * spec.m) for p in range(1, N2)]
     log(f"[bench] {len(baby) + len(giant)} Galois keys ready in {time.time() - t0:.1f}s")
-    xs = CL.pack_columns(X, n, spec.C)
+    xs = CL.pack_columns_complex(X, n, spec.C) if pairs else CL.pack_columns(X, n, spec.C)
     ct_x = torch.stack([cl.encrypt_slots(xs[g], scale, level) for g in range(G)])
+    conj = key("conj") if pairs else None
     w = B.ckks_weights_create(P, level, spec.m, spec.C, G, B_out, n1)
     t0 = time.time()
     for M, b_first in parts:
         for b in range(-(-M.shape[1] // spec.C)):
             for p in range(N2):
-                z = CL.diagonal_slots(M, spec.m, n, spec.C, n1, b, p).reshape(G * n1, n)
+                if pairs:
+                    z = CL.diagonal_slots_complex(M, spec.m, n, spec.C, n1, b, p).reshape(G * n1, n)
+                else:
+                    z = CL.diagonal_slots(M, spec.m, n, spec.C, n1, b, p).reshape(G * n1, n)
                 coeffs = cl.enc.encode(z, scale)
                 B.ckks_weights_set_diagonals(w, ((b_first + b) * N2 + p) * G * n1, torch.from_numpy(coeffs).cuda())
     if bias is not None:
@@ -79,7 +87,8 @@ def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False):
     ref = X @ Wm + (bias if bias is not None else 0.0)
     if fused_qk:
         ref = np.concatenate([X @ parts[0][0], X @ parts[1][0] + 0j], axis=1)       # [Q + iK | V]
-    return dict(ct_x=ct_x, w=w, baby=baby, giant=giant, ref=ref, G=G, B_out=B_out, N2=N2, scale=scale, level=level)
+    return dict(ct_x=ct_x, w=w, baby=baby, giant=giant, conj=conj, ref=ref, G=G, B_out=B_out, N2=N2, scale=scale,
+                level=level)
 
 
 def read_traffic(workload, n1):
@@ -151,16 +160,19 @@ def run_gpt2_block(args, B, CL, W, P, cl):
     length 128, one after the other; weights of one layer resident at a time; inputs freshly encrypted per
     layer (the MPC boundary between layers is simulated by fresh synthetic activations)."""
     import torch
+    from paper_2604_09975_amd import plan
     keys, layers, total = {}, [], 0.0
     for spec in W.GPT2_LAYERS:
         n1 = args.n1 or spec.N1
-        S = setup_matmul(B, CL, W, P, cl, spec, n1, keys)
+        if args.pair_compression and not args.n1:
+            n1 = plan.choose_n1(-(-(-(-spec.d_in // spec.C)) // 2), -(-spec.d_out // spec.C), spec.C)
+        S = setup_matmul(B, CL, W, P, cl, spec, n1, keys, pairs=args.pair_compression)
         level, B_out = S["level"], S["B_out"]
         y = torch.empty((B_out, 2, level, P.N), dtype=torch.int64, device="cuda")
         yr = torch.empty((B_out, 2, level - 1, P.N), dtype=torch.int64, device="cuda")
 
         def step():
-            _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y,
+            _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y, conj_key=S["conj"],
                                         flags=0 if args.separate_giant else B.MATMUL_MERGED_GIANT)
             B.ckks_rescale(P, y, level, B_out, yr)
             return cnt
@@ -194,7 +206,9 @@ def run_gpt2_block(args, B, CL, W, P, cl):
         "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
         "config": {"workload": "gpt2_small_block_linear_set", "N": P.N, "q_limbs": P.L, "special_limbs": P.K,
-                   "dnum": P.dnum, "giant_step": GIANT_NAMES[not args.separate_giant], "layers": layers}}), flush=True)
+                   "dnum": P.dnum, "giant_step": GIANT_NAMES[not args.separate_giant],
+                   "input_packing": "complex pairs (Sec. 3.2)" if args.pair_compression else "real", "layers": layers}}),
+          flush=True)
 
 
 def run_ntt(args, B, W):
@@ -390,6 +404,9 @@ def main():
                     help="giant step with one ModDown per output block (CKKS_MATMUL_MERGED_GIANT); the default")
     ap.add_argument("--fused-qk", action="store_true",
                     help="bert_qkv only: Q and K through one projection with weights W_Q + i*W_K (no bias)")
+    ap.add_argument("--pair-compression", action="store_true",
+                    help="complex-pair compression of the inputs (Sec. 3.2): half the bank, one conjugation per "
+                         "output block; N1 re-planned unless --n1 is given")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only a plain 4 GiB device-to-device copy, 10 times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -409,7 +426,7 @@ def main():
         print(json.dumps({"probe": "copy", "bytes_read_per_launch": src.numel() * 8,
                           "bytes_written_per_launch": src.numel() * 8, "launches": 10}))
         return
-    from paper_2604_09975_amd import binding as B, client as CL, workload as W
+    from paper_2604_09975_amd import binding as B, client as CL, plan, workload as W
     if args.workload == "ntt":
         run_ntt(args, B, W)
         return
@@ -429,7 +446,13 @@ def main():
     if args.workload == "primitives":
         run_primitives(args, B, CL, W, P, cl)
         return
-    S = setup_matmul(B, CL, W, P, cl, spec, n1, fused_qk=args.fused_qk)
+    if args.pair_compression and args.fused_qk:
+        print("bench.py: --pair-compression and --fused-qk are different packings of the same layer; pick one.",
+              file=sys.stderr)
+        sys.exit(2)
+    if args.pair_compression and not args.n1:
+        n1 = plan.choose_n1(-(-(-(-spec.d_in // spec.C)) // 2), -(-spec.d_out // spec.C), spec.C)
+    S = setup_matmul(B, CL, W, P, cl, spec, n1, fused_qk=args.fused_qk, pairs=args.pair_compression)
     N, level, B_out, G, N2 = P.N, S["level"], S["B_out"], S["G"], S["N2"]
     y = torch.empty((B_out, 2, level, N), dtype=torch.int64, device="cuda")
     yr = torch.empty((B_out, 2, level - 1, N), dtype=torch.int64, device="cuda")
@@ -437,7 +460,7 @@ def main():
     merged = not args.separate_giant
 
     def step(merged_giant=merged):
-        _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y,
+        _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y, conj_key=S["conj"],
                                     flags=B.MATMUL_MERGED_GIANT if merged_giant else 0)
         B.ckks_rescale(P, y, level, B_out, yr)
         return cnt
@@ -536,6 +559,7 @@ def main():
                    "log_scale": ring.log_scale, "m": spec.m, "d_in": spec.d_in, "d_out": spec.d_out,
                    "C": spec.C, "G": G, "B_out": B_out, "N1": n1, "N2": N2,
                    "giant_step": GIANT_NAMES[merged],
+                   "input_packing": "complex pairs (Sec. 3.2)" if args.pair_compression else "real",
                    "key_switches_per_step": int(cnt.key_switches), "ptmuls_per_step": int(cnt.ptmuls),
                    "limb_ntts_per_step": int(cnt.limb_ntts)},
         "other_giant_step": {"giant_step": GIANT_NAMES[not merged], "ms_per_step": other_ms},
