@@ -114,3 +114,47 @@ def test_gpt2_ffn_down_width_one_block_bit_exact(merged):
     err = np.abs(E.unpack_columns(slots.real, m, C, d_out) - (X @ Wm + bias)).max()
     print(f"[ffn] max abs err {err:.2e}, total {time.time() - t0:.0f}s", flush=True)
     assert err <= 1e-3
+
+
+def test_gpt2_ffn_down_complex_pairs_one_block_bit_exact():
+    """Full ring, complex-pair compression (Sec. 3.2) of the FFN-down layer: the twelve real input groups travel as
+    six complexified ciphertexts, the weights are (W_even - i*W_odd)/2 stored as packed whole limbs, and one
+    conjugation per output block brings back the real result.  One output block, level 9, merged giant step,
+    every residue against the oracle."""
+    from paper_2604_09975_amd import binding as B
+    t0 = time.time()
+    spec = W.GPT2_LAYERS[3]
+    O, P = make_pair(spec.ring)
+    N, n, m, C, N1 = O.N, O.n, spec.m, spec.C, 16
+    U, N2, B_out, d_out = 6, C // N1, 1, 256
+    level = 9
+    scale = 2.0 ** spec.ring.log_scale
+    X, Wm, bias = W.matmul_inputs(spec)
+    Wm, bias = Wm[:, :d_out], bias[:d_out]
+    cl = helpers.Client(O, spec.seed + 1)
+    mx = E.encode(E.pack_columns_complex(X, n, C), scale, N)
+    ct_x = np.stack([cl.encrypt_coeffs(mx[u], level) for u in range(U)])
+    baby_np, baby_h = load_keys(P, O, cl, [q * m for q in range(1, N1)])
+    giant_np, giant_h = load_keys(P, O, cl, [p * N1 * m for p in range(1, N2)])
+    (conj_np,), (conj_h,) = load_keys(P, O, cl, ["conj"])
+    bias_c = np.stack([E.encode(E.bias_slots(bias, m, n, C, 0) + 0j, scale, N)])
+    diag = E.encode_diagonals_complex(Wm, m, N, C, N1, scale, half=True)
+    w = B.ckks_weights_create(P, level, m, C, U, B_out, N1)
+    B.ckks_weights_set_diagonals(w, 0, to_dev(diag.reshape(-1, N)))
+    B.ckks_weights_set_bias(w, to_dev(bias_c), int(scale))
+    print(f"[pairs] inputs ready {time.time() - t0:.0f}s", flush=True)
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, conj_key=conj_h,
+                                    flags=B.MATMUL_MERGED_GIANT)
+    y_res = B.ckks_rescale(P, y_dev, level, B_out)
+    torch.cuda.synchronize()
+    assert cnt.key_switches == U * (N1 - 1) + B_out * (N2 - 1) + B_out
+    want = O.ctpt_matmul(level, m, U, B_out, N1, N2, diag, bias_c, int(scale), ct_x, baby_np, giant_np,
+                         conj_key=conj_np, merged=True)
+    print(f"[pairs] oracle done {time.time() - t0:.0f}s", flush=True)
+    assert (to_host(y_dev) == want).all()
+    got_res = to_host(y_res)
+    assert (got_res == O.rescale(want, level)).all()
+    slots = cl.decrypt_slots(got_res[0], level - 1, scale * scale / O.q[level - 1], nlimbs=2)[None]
+    err = np.abs(E.unpack_columns(slots.real, m, C, d_out) - (X @ Wm + bias)).max()
+    print(f"[pairs] max abs err {err:.2e}, imag {np.abs(slots.imag).max():.2e}, total {time.time() - t0:.0f}s", flush=True)
+    assert err <= 1e-3 and np.abs(slots.imag).max() <= 1e-3
