@@ -7,8 +7,11 @@ namespace ckks {
 
 constexpr u32 NTT_THREADS = 256;
 
-__device__ __forceinline__ u32 lds_pad(u32 i) { return i + (i >> 4); }
-constexpr u32 FAST_LDS_WORDS = 4096 + 256;
+// LDS slot of tile element i: bits 4..8 of the index are folded into its low five bits, which spreads both the
+// stride-16 and the contiguous 16-element accesses of the radix-16 passes over all bank pairs without padding
+// words (a bijection on every aligned block of 512), so a tile takes exactly 32 KiB and five fit a CU.
+__device__ __forceinline__ u32 lds_pad(u32 i) { return i ^ ((i >> 4) & 31u); }
+constexpr u32 FAST_LDS_WORDS = 4096;
 
 struct FieldInt {
     typedef u64 T;
