@@ -37,12 +37,20 @@ class Encoder:
         v[..., self.neg] = np.conj(z)
         m = (np.fft.fft(v, axis=-1) * self.twist).real * (scale / self.N)
         m = np.rint(m).astype(np.int64)
+        # a real slot vector is fixed by conjugation, so m(X) = m(1/X): m[N-j] = -m[j] exactly.  The FFT only
+        # gives that up to rounding; enforcing it (for every vector whose imaginary parts are all zero, also
+        # inside a complex batch) lets the library read half of every such weight limb.
+        h = self.N // 2
         if np.isrealobj(z):
-            # a real slot vector is fixed by conjugation, so m(X) = m(1/X): m[N-j] = -m[j] exactly.  The FFT
-            # only gives that up to rounding; enforcing it lets the library read half of every weight limb.
-            h = self.N // 2
             m[..., h + 1:] = -m[..., 1:h][..., ::-1]
             m[..., h] = 0
+        else:
+            real_rows = ~np.any(z.imag != 0, axis=-1)
+            if np.any(real_rows):
+                sub = m[real_rows]
+                sub[..., h + 1:] = -sub[..., 1:h][..., ::-1]
+                sub[..., h] = 0
+                m[real_rows] = sub
         return m
 
     def decode(self, m, scale):

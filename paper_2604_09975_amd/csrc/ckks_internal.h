@@ -111,8 +111,10 @@ struct ckks_weights {
     ckks::u64 *d_stage = nullptr;      // expansion buffer of the packed store (STAGE_DIAGS diagonals)
     bool packable = false;             // every active prime below 2^50 and N large enough for the palindrome kernel
     ckks::u64 *d_bias = nullptr;       // [B_out][level][N], NTT domain, canonical, times bias_mul; or null
-    std::vector<uint8_t> block_real;   // per output block: every diagonal loaded so far encodes a real slot vector
-    std::vector<uint8_t> block_packed; // per output block: 0 = d_w, 1 = half records in d_wp (real), 2 = whole-limb records in d_wpf
+    // per (output block b, input group g), index b*G + g: every diagonal loaded so far encodes a real slot vector;
+    // and where the group's diagonals live: 0 = d_w, 1 = half records in d_wp (real), 2 = whole-limb records in d_wpf
+    std::vector<uint8_t> block_real;
+    std::vector<uint8_t> block_packed;
     ckks::u32 *d_flag = nullptr;       // per-diagonal check results of the chunk being loaded
     ckks::u32 flag_cap = 0;
 };

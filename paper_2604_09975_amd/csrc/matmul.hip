@@ -64,7 +64,9 @@ template <u32 TB, u32 VEC, bool PACKED>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restrict__ bank,
                                                               const u64 *__restrict__ w, u64 *__restrict__ acc,
                                                               const ModFp *__restrict__ modf, LimbIds limbs,
-                                                              u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle) {
+                                                              u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle,
+                                                              u32 gq0, u32 gq1, u32 accumulate) {
+    // steps gq0 .. gq1-1 of the GQ per pair are summed; accumulate: onto what acc already holds
     static_assert(!PACKED || VEC == 2, "packed weights are read in pairs");
     typedef u64 vec_t __attribute__((ext_vector_type(VEC)));
     // swizzle: one XCD walks all (b,p) tiles of a run of coefficients back to back (see diag_mac_sym_kernel)
@@ -121,8 +123,21 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
                 }
             }
     };
-    fetch(0);
-    for (u32 gq = 0; gq < GQ; ++gq) {
+    if (accumulate) {
+#pragma unroll
+        for (u32 t = 0; t < TB; ++t)
+            if (bp0 + t < BP) {
+                const vec_t p0 = *reinterpret_cast<const vec_t *>(acc + ((size_t)(bp0 + t) * 2 + 0) * w_stride + limb_off);
+                const vec_t p1 = *reinterpret_cast<const vec_t *>(acc + ((size_t)(bp0 + t) * 2 + 1) * w_stride + limb_off);
+#pragma unroll
+                for (u32 e = 0; e < VEC; ++e) {
+                    a0[t][e] = (double)p0[e];
+                    a1[t][e] = (double)p1[e];
+                }
+            }
+    }
+    fetch(gq0);
+    for (u32 gq = gq0; gq < gq1; ++gq) {
         double x0[VEC], x1[VEC];
 #pragma unroll
         for (u32 e = 0; e < VEC; ++e) {
@@ -143,7 +158,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
                 for (u32 e = 0; e < VEC; ++e) wd[t][e] = __hiloint2double((int)wb[t][2 * e + 1], (int)wb[t][2 * e]);
             }
         }
-        if (gq + 1 < GQ) fetch(gq + 1);
+        if (gq + 1 < gq1) fetch(gq + 1);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t) {
             if (bp0 + t < BP) {
@@ -159,7 +174,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
                 }
             }
         }
-        if ((gq & 7) == 7) {   // keep the signed sums far below 2^53
+        if (((gq - gq0) & 7) == 7) {   // keep the signed sums far below 2^53
 #pragma unroll
             for (u32 t = 0; t < TB; ++t)
 #pragma unroll
@@ -201,7 +216,9 @@ template <u32 TB, bool PACKED>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__restrict__ bank,
                                                                   const u64 *__restrict__ w, u64 *__restrict__ acc,
                                                                   const ModFp *__restrict__ modf, LimbIds limbs,
-                                                                  u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle) {
+                                                                  u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle,
+                                                                  u32 gq0, u32 gq1, u32 accumulate) {
+    // steps gq0 .. gq1-1 of the GQ per pair are summed; accumulate: onto what acc already holds
     typedef u64 vec_t __attribute__((ext_vector_type(2)));
     typedef u32 wvec_t __attribute__((ext_vector_type(4)));      // one (b,p) pair's two weights as loaded
     u32 tile = blockIdx.x, run = blockIdx.y;
@@ -258,8 +275,24 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
             }
     };
     const u32 top_shift = (k & 2) * 2;                           // k is even: bits 0..3 or 4..7 of the byte
-    fetch(0);
-    for (u32 gq = 0; gq < GQ; ++gq) {
+    if (accumulate) {
+#pragma unroll
+        for (u32 t = 0; t < TB; ++t)
+            if (bp0 + t < BP) {
+#pragma unroll
+                for (u32 c = 0; c < 2; ++c) {
+                    const u64 *src = acc + ((size_t)(bp0 + t) * 2 + c) * w_stride + row;
+                    const vec_t lo = *reinterpret_cast<const vec_t *>(src + k);
+                    const vec_t hi = *reinterpret_cast<const vec_t *>(src + km);
+                    a[t][c][0] = (double)lo[0];
+                    a[t][c][1] = (double)lo[1];
+                    a[t][c][2] = (double)hi[0];
+                    a[t][c][3] = (double)hi[1];
+                }
+            }
+    }
+    fetch(gq0);
+    for (u32 gq = gq0; gq < gq1; ++gq) {
         double x[2][4];
 #pragma unroll
         for (u32 c = 0; c < 2; ++c) {
@@ -283,7 +316,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
                 wd[t][1] = __hiloint2double((int)wb[t][3], (int)wb[t][2]);
             }
         }
-        if (gq + 1 < GQ) fetch(gq + 1);
+        if (gq + 1 < gq1) fetch(gq + 1);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t) {
             if (bp0 + t < BP) {
@@ -299,7 +332,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
                     }
             }
         }
-        if ((gq & 7) == 7) {
+        if (((gq - gq0) & 7) == 7) {
 #pragma unroll
             for (u32 t = 0; t < TB; ++t)
 #pragma unroll
@@ -551,8 +584,8 @@ int ckks_weights_create(const ckks_params_t *P, uint32_t level, uint32_t m, uint
     w->B_out = B_out;
     w->N1 = N1;
     w->N2 = C / N1;
-    w->block_real.assign(B_out, 1);
-    w->block_packed.assign(B_out, 0);
+    w->block_real.assign((size_t)B_out * G, 1);
+    w->block_packed.assign((size_t)B_out * G, 0);
     w->packable = P->N >= 4 * MM_THREADS;
     for (u32 i = 0; i < level; ++i)
         if (P->mod[i] >> 50) w->packable = false;
@@ -581,21 +614,20 @@ int ensure_packed_store(ckks_weights *w, bool whole) {
     return CKKS_OK;
 }
 
-// A block of half records receives a diagonal that is not real: its diagonals move to the whole-limb store.
-int widen_block(ckks_weights *w, u32 b, hipStream_t stream) {
+// A group (b, g) of half records receives a diagonal that is not real: its diagonals move to the whole-limb store.
+int widen_group(ckks_weights *w, u32 b, u32 g, hipStream_t stream) {
     int rc = ensure_packed_store(w, true);
     if (rc) return rc;
     const u32 N = w->params->N;
-    const size_t rows = (size_t)w->N2 * w->G * w->N1 * w->level, first = (size_t)b * rows;
-    for (size_t done = 0; done < rows;) {
-        const u32 c = (u32)std::min<size_t>(rows - done, 32768);
-        hipLaunchKernelGGL(widen_half_kernel, dim3((N / 4 + EW_THREADS - 1) / EW_THREADS, c), dim3(EW_THREADS), 0,
-                           stream, w->d_wp + (first + done) * packed_record_bytes(N),
-                           w->d_wpf + (first + done) * 2 * packed_record_bytes(N), N);
+    const size_t rows = (size_t)w->N1 * w->level;            // the records of one (b, p, g)
+    for (u32 p = 0; p < w->N2; ++p) {
+        const size_t first = ((((size_t)b * w->N2 + p) * w->G + g) * w->N1) * w->level;
+        hipLaunchKernelGGL(widen_half_kernel, dim3((N / 4 + EW_THREADS - 1) / EW_THREADS, (u32)rows), dim3(EW_THREADS),
+                           0, stream, w->d_wp + first * packed_record_bytes(N),
+                           w->d_wpf + first * 2 * packed_record_bytes(N), N);
         CKKS_LAUNCH_CHECK("widen_half_kernel");
-        done += c;
     }
-    w->block_packed[b] = 2;
+    w->block_packed[(size_t)b * w->G + g] = 2;
     return CKKS_OK;
 }
 
@@ -615,8 +647,8 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
     }
     const ckks_params *P = w->params;
     if (count) {
-        // real slot vectors are recognised by their coefficients (c[N-j] = -c[j]); an output block whose
-        // diagonals all pass is read through the palindrome kernel.  One host read per chunk: this call is
+        // real slot vectors are recognised by their coefficients (c[N-j] = -c[j]); an (output block, input group)
+        // pair whose diagonals all pass is read through the palindrome kernel.  One host read per chunk: this call is
         // the offline weight-loading step.
         if (w->flag_cap < count) {
             hipFree(w->d_flag);
@@ -633,22 +665,28 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
         CKKS_HIP(hipMemcpyAsync(flags.data(), w->d_flag, count * sizeof(u32), hipMemcpyDeviceToHost,
                                 (hipStream_t)stream));
         CKKS_HIP(hipStreamSynchronize((hipStream_t)stream));
-        const u32 per_block = w->N2 * w->G * w->N1, N = P->N, level = w->level;
-        // the chunk is stored block by block: packed while the block has seen real diagonals only, else in full
+        const u32 N = P->N, level = w->level, N1 = w->N1, G = w->G;
+        // the chunk is stored one (b, p, g) run of baby steps at a time; the kind of store is a property of the
+        // (output block, input group) pair: packed half records while the pair has seen real diagonals only,
+        // packed whole limbs otherwise (chains with a prime of 50 bits or more keep 8-byte words)
         for (u32 lo = first; lo < first + count;) {
-            const u32 b = lo / per_block;
-            const u32 hi = std::min<u32>(first + count, (b + 1) * per_block);
+            const u32 run = lo / N1;                                   // (b*N2 + p)*G + g
+            const u32 g = run % G, b = run / G / w->N2;
+            const u32 hi = std::min<u32>(first + count, (run + 1) * N1);
+            const size_t grp = (size_t)b * G + g;
+            if (w->N1 > 65535 / level) {
+                set_error("ckks_weights_set_diagonals: N1 * level = %u exceeds one launch", w->N1 * level);
+                return CKKS_E_INVAL;
+            }
             bool all_real = true;
             for (u32 d = lo; d < hi; ++d) all_real = all_real && flags[d - first];
-            if (!all_real) w->block_real[b] = 0;
+            if (!all_real) w->block_real[grp] = 0;
             int rc;
             if (w->packable) {
-                // a block that is still real has either nothing loaded yet or half records only; a general block
-                // keeps whole-limb records (half records stored before the first general diagonal are widened)
-                const bool whole = !w->block_real[b];
-                if (whole && w->block_packed[b] == 1 && (rc = widen_block(w, b, (hipStream_t)stream))) return rc;
+                const bool whole = !w->block_real[grp];
+                if (whole && w->block_packed[grp] == 1 && (rc = widen_group(w, b, g, (hipStream_t)stream))) return rc;
                 if ((rc = ensure_packed_store(w, whole))) return rc;
-                w->block_packed[b] = whole ? 2 : 1;
+                w->block_packed[grp] = whole ? 2 : 1;
                 const size_t recb = (whole ? 2 : 1) * packed_record_bytes(N);
                 unsigned char *store = whole ? w->d_wpf : w->d_wp;
                 const u32 cnt = whole ? N : N / 2;
@@ -824,38 +862,56 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                 int_limbs.id[n_int++] = (uint8_t)i;
         }
         const dim3 tiles((BP + MM_TB - 1) / MM_TB, N / MM_THREADS);
-        // runs of output blocks of one kind: real diagonals (palindrome kernel, half of each weight limb read)
-        // or general ones
+        // Runs of output blocks whose input groups have the same kinds of store; within a run, one launch per
+        // range of input groups of one kind (real diagonals: palindrome kernel on half records; general ones:
+        // whole limbs), the later launches adding onto the accumulators of the earlier ones.  Real packing gives
+        // one launch; complexified inputs with an odd last group give a general and a real one.
+        auto same_kinds = [&](u32 ba, u32 bb) {
+            for (u32 g = 0; g < G; ++g)
+                if (w->block_real[(size_t)ba * G + g] != w->block_real[(size_t)bb * G + g] ||
+                    w->block_packed[(size_t)ba * G + g] != w->block_packed[(size_t)bb * G + g])
+                    return false;
+            return true;
+        };
         for (u32 b0 = 0; n_fp && b0 < B;) {
             u32 b1 = b0 + 1;
-            while (b1 < B && w->block_real[b1] == w->block_real[b0] && w->block_packed[b1] == w->block_packed[b0])
-                ++b1;
+            while (b1 < B && same_kinds(b0, b1)) ++b1;
             const u32 bp_first = b0 * N2, bp_count = (b1 - b0) * N2;
             const u64 *wp = w->d_w ? w->d_w + (size_t)bp_first * GQ * level * N : nullptr;
             u64 *ap = d_acc + (size_t)bp_first * ctw;
-            const u32 runs = N / (4 * MM_THREADS);
+            const u32 runs = N / (4 * MM_THREADS), gen_runs = N / MM_THREADS / 2;
             const dim3 sym_grid((bp_count + MM_TB - 1) / MM_TB, runs, n_fp);
-            // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
-            if (w->block_packed[b0] == 1) {
-                const u64 *pp = reinterpret_cast<const u64 *>(w->d_wp + (size_t)bp_first * GQ * level *
-                                                                            packed_record_bytes(N));
-                hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, true>), sym_grid, dim3(MM_THREADS), 0, stream, d_bank,
-                                   pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count, runs % 8 == 0 ? 1u : 0u);
-            } else if (w->block_packed[b0] == 2) {
-                const u64 *pp = reinterpret_cast<const u64 *>(w->d_wpf + (size_t)bp_first * GQ * level * 2 *
-                                                                             packed_record_bytes(N));
-                hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2, true>),
-                                   dim3((bp_count + MM_TB - 1) / MM_TB, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS), 0,
-                                   stream, d_bank, pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
-                                   (N / MM_THREADS / 2) % 8 == 0 ? 1u : 0u);
-            } else if (w->block_real[b0] && N >= 4 * MM_THREADS) {
-                hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, false>), sym_grid, dim3(MM_THREADS), 0, stream, d_bank,
-                                   wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count, runs % 8 == 0 ? 1u : 0u);
-            } else {   // 8 accumulators x 2 coefficients per thread (16-byte loads)
-                hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2, false>),
-                                   dim3((bp_count + MM_TB - 1) / MM_TB, N / MM_THREADS / 2, n_fp), dim3(MM_THREADS), 0,
-                                   stream, d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
-                                   (N / MM_THREADS / 2) % 8 == 0 ? 1u : 0u);
+            const dim3 gen_grid((bp_count + MM_TB - 1) / MM_TB, gen_runs, n_fp);
+            for (u32 g0 = 0; g0 < G;) {
+                const size_t grp = (size_t)b0 * G + g0;
+                u32 g1 = g0 + 1;
+                while (g1 < G && w->block_real[grp + (g1 - g0)] == w->block_real[grp] &&
+                       w->block_packed[grp + (g1 - g0)] == w->block_packed[grp])
+                    ++g1;
+                const u32 q0 = g0 * N1, q1 = g1 * N1, add = g0 ? 1u : 0u;
+                // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
+                if (w->block_packed[grp] == 1) {
+                    const u64 *pp = reinterpret_cast<const u64 *>(w->d_wp + (size_t)bp_first * GQ * level *
+                                                                                packed_record_bytes(N));
+                    hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, true>), sym_grid, dim3(MM_THREADS), 0, stream,
+                                       d_bank, pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
+                                       runs % 8 == 0 ? 1u : 0u, q0, q1, add);
+                } else if (w->block_packed[grp] == 2) {
+                    const u64 *pp = reinterpret_cast<const u64 *>(w->d_wpf + (size_t)bp_first * GQ * level * 2 *
+                                                                                 packed_record_bytes(N));
+                    hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2, true>), gen_grid, dim3(MM_THREADS), 0, stream,
+                                       d_bank, pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
+                                       gen_runs % 8 == 0 ? 1u : 0u, q0, q1, add);
+                } else if (w->block_real[grp] && N >= 4 * MM_THREADS) {
+                    hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, false>), sym_grid, dim3(MM_THREADS), 0, stream,
+                                       d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
+                                       runs % 8 == 0 ? 1u : 0u, q0, q1, add);
+                } else {   // 8 accumulators x 2 coefficients per thread (16-byte loads)
+                    hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2, false>), gen_grid, dim3(MM_THREADS), 0, stream,
+                                       d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
+                                       gen_runs % 8 == 0 ? 1u : 0u, q0, q1, add);
+                }
+                g0 = g1;
             }
             b0 = b1;
         }
