@@ -193,14 +193,16 @@ def weight_diagonal_complex(W, m, n, C, N1, b, p, u, q, half=True):
     return 0.5 * z if half else z
 
 
-def encode_diagonals_complex(W, m, N, C, N1, scale, half=True):
-    """int64 [B_out][N2][U][N1][N] encodings of the complexified diagonals."""
+def encode_diagonals_complex(W, m, N, C, N1, scale, half=True, blocks=None):
+    """int64 [B_out][N2][U][N1][N] encodings of the complexified diagonals (blocks: subset of b kept, others zero)."""
     n = N // 2
     d_in, d_out = W.shape
     G, B_out, N2 = -(-d_in // C), -(-d_out // C), C // N1
     U = -(-G // 2)
     out = np.zeros((B_out, N2, U, N1, N), dtype=np.int64)
     for b in range(B_out):
+        if blocks is not None and b not in blocks:
+            continue
         for p in range(N2):
             z = np.stack([weight_diagonal_complex(W, m, n, C, N1, b, p, u, q, half) for u in range(U) for q in range(N1)])
             out[b, p] = encode(z, scale, N).reshape(U, N1, N)

@@ -17,8 +17,11 @@ from paper_2604_09975_amd import workload as W
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("merged", [False, True], ids=["default", "merged_giant"])
-def test_bert_qkv_sampled_block_bit_exact(merged):
+@pytest.mark.parametrize("merged,pairs", [(False, False), (True, False), (True, True)],
+                         ids=["default", "merged_giant", "complex_pairs_merged_giant"])
+def test_bert_qkv_sampled_block_bit_exact(merged, pairs):
+    """pairs: complex-pair compression of the inputs (Sec. 3.2): two complexified inputs, the second with
+    imaginary part zero and real weights (half records, second launch), one conjugation per block."""
     from paper_2604_09975_amd import binding as B
     t0 = time.time()
     spec = W.BERT_QKV
@@ -29,10 +32,17 @@ def test_bert_qkv_sampled_block_bit_exact(merged):
     scale = 2.0 ** spec.ring.log_scale
     X, Wm, bias = W.matmul_inputs(spec)
     cl = helpers.Client(O, spec.seed)
-    mx = E.encode(E.pack_columns(X, n, C) + 0j, scale, N)
+    if pairs:
+        G = -(-G // 2)
+        mx = E.encode(E.pack_columns_complex(X, n, C), scale, N)
+    else:
+        mx = E.encode(E.pack_columns(X, n, C) + 0j, scale, N)
     ct_x = np.stack([cl.encrypt_coeffs(mx[g], level) for g in range(G)])
     baby_np, baby_h = load_keys(P, O, cl, [q * m for q in range(1, N1)])
     giant_np, giant_h = load_keys(P, O, cl, [p * N1 * m for p in range(1, N2)])
+    conj_np, conj_h = None, None
+    if pairs:
+        (conj_np,), (conj_h,) = load_keys(P, O, cl, ["conj"])
     print(f"[full] keys ready {time.time() - t0:.0f}s", flush=True)
     bias_c = np.stack([E.encode(E.bias_slots(bias, m, n, C, b) + 0j, scale, N) for b in range(B_out)])
     block = int(W.rng(spec.seed + 7).integers(B_out))          # the sampled block
@@ -41,24 +51,29 @@ def test_bert_qkv_sampled_block_bit_exact(merged):
     for b in range(B_out):
         # exactly antisymmetric coefficients, as bench.py's encoder produces them for real diagonals: the
         # library then runs the kernel that reads half of each weight limb, the one the benchmark times
-        d = make_real(E.encode_diagonals(Wm, m, N, C, N1, scale, blocks={b})[b])          # [N2][G][N1][N]
+        if pairs:
+            d = E.encode_diagonals_complex(Wm, m, N, C, N1, scale, half=True, blocks={b})[b]
+            d[:, G - 1] = make_real(d[:, G - 1])      # the odd third group: imaginary part zero
+        else:
+            d = make_real(E.encode_diagonals(Wm, m, N, C, N1, scale, blocks={b})[b])      # [N2][G][N1][N]
         B.ckks_weights_set_diagonals(w, b * N2 * G * N1, to_dev(d.reshape(-1, N)))
         if b == block:
             diag_block = d
     B.ckks_weights_set_bias(w, to_dev(bias_c), int(scale))
     print(f"[full] weights ready {time.time() - t0:.0f}s", flush=True)
-    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h,
+    y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, conj_key=conj_h,
                                     flags=B.MATMUL_MERGED_GIANT if merged else 0)
     y_res = B.ckks_rescale(P, y_dev, level, B_out)
     torch.cuda.synchronize()
     got, got_res = to_host(y_dev), to_host(y_res)
-    assert cnt.key_switches == G * (N1 - 1) + B_out * (N2 - 1) and cnt.ptmuls == G * N1 * B_out * N2
+    assert cnt.key_switches == G * (N1 - 1) + B_out * (N2 - 1) + (B_out if pairs else 0)
+    assert cnt.ptmuls == G * N1 * B_out * N2
 
     # oracle on the sampled block: it needs that block's diagonals only
     diag = np.zeros((B_out, N2, G, N1, N), dtype=np.int64)
     diag[block] = diag_block
     want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(scale), ct_x, baby_np, giant_np,
-                         b_first=block, b_count=1, merged=merged)
+                         b_first=block, b_count=1, merged=merged, conj_key=conj_np)
     print(f"[full] oracle block {block} done {time.time() - t0:.0f}s", flush=True)
     assert (got[block] == want[block]).all()
     assert (got_res[block] == O.rescale(want[block:block + 1], level)[0]).all()
