@@ -72,8 +72,7 @@ def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False, pair
                     z = CL.diagonal_slots_complex(M, spec.m, n, spec.C, n1, b, p).reshape(G * n1, n)
                 else:
                     z = CL.diagonal_slots(M, spec.m, n, spec.C, n1, b, p).reshape(G * n1, n)
-                coeffs = cl.enc.encode(z, scale)
-                B.ckks_weights_set_diagonals(w, ((b_first + b) * N2 + p) * G * n1, torch.from_numpy(coeffs).cuda())
+                B.ckks_weights_set_diagonals(w, ((b_first + b) * N2 + p) * G * n1, cl.enc.encode(z, scale))
     if bias is not None:
         nseg = n // spec.m
         bz = np.zeros((B_out, n))
@@ -81,7 +80,7 @@ def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False, pair
             col = b * spec.C + np.arange(nseg) % spec.C
             v = np.where(col < spec.d_out, bias[np.minimum(col, spec.d_out - 1)], 0.0)
             bz[b] = np.repeat(v, spec.m)
-        B.ckks_weights_set_bias(w, torch.from_numpy(cl.enc.encode(bz, scale)).cuda(), int(scale))
+        B.ckks_weights_set_bias(w, cl.enc.encode(bz, scale), int(scale))
     torch.cuda.synchronize()
     log(f"[bench] {G * n1 * B_out * N2} weight diagonals encoded and expanded in {time.time() - t0:.1f}s")
     ref = X @ Wm + (bias if bias is not None else 0.0)
@@ -314,7 +313,7 @@ def run_primitives(args, B, CL, W, P, cl):
     res = {}
     for level in (P.L, 17):
         ca, cb = cl.encrypt_slots(za, 2.0 ** 40, level), cl.encrypt_slots(zb, 2.0 ** 40, level)
-        pt = B.ckks_plain_expand(P, level, cl._dev(cl.enc.encode(zb, 2.0 ** 40))[None])[0]
+        pt = B.ckks_plain_expand(P, level, cl.enc.encode(zb, 2.0 ** 40)[None])[0]
         o1 = torch.empty((1, 2, level, P.N), dtype=torch.int64, device="cuda")
         o2 = torch.empty((2, level, P.N), dtype=torch.int64, device="cuda")
         lo = torch.empty((1, 2, level - 1, P.N), dtype=torch.int64, device="cuda")
@@ -359,7 +358,7 @@ def run_primitives(args, B, CL, W, P, cl):
                 steps += list(st)
                 masks += [cl.enc.encode(h, 2.0 ** 40), cl.enc.encode(u, 2.0 ** 40)]
             keymap = {s: cl.galois_key(s) for s in sorted(set(steps))}
-            d_masks = B.ckks_plain_expand(P, level, cl._dev(np.stack(masks))).reshape(len(ts), 2, level, P.N)
+            d_masks = B.ckks_plain_expand(P, level, torch.stack(masks)).reshape(len(ts), 2, level, P.N)
             bank = torch.empty((len(ts), 2, level, P.N), dtype=torch.int64, device="cuda")
             f = lambda: B.ckks_shift_bank(P, ca, level, steps, [keymap[s] for s in steps], d_masks, bank)
             f()

@@ -257,6 +257,30 @@ int ckks_client_encrypt(ckks_params_t *params, const ckks_secret_t *secret, uint
 int ckks_client_decrypt(ckks_params_t *params, const ckks_secret_t *secret, const uint64_t *d_ct, uint32_t level,
                         uint32_t nlimbs, uint64_t *d_out, void *stream);
 
+/* ---- complex-slot encode / decode on the device (Sec. 2.1 Encode / Decode; slot order of Sec. 3.1) ----
+ * Slot j of a plaintext m(X) is m(zeta^(5^j)), zeta = exp(i*pi/N), j < n = N/2, so that a rotation by r is the
+ * cyclic left shift of the slot vector.  fp64 throughout (one N-point complex transform per vector); results agree
+ * with an exact evaluation to about 1e-13 * N * max|z| relative to the scale, so a rounded coefficient can differ by
+ * one unit from another fp64 implementation's when it falls next to a half-integer. */
+
+#define CKKS_ENCODE_REAL 1u /* flags: imaginary parts are taken as zero and the coefficients satisfy
+                               c[N-k] = -c[k], c[N/2] = 0 exactly (what ckks_weights_set_diagonals needs to keep
+                               half of every limb) */
+
+/* d_slots: device, [count][n] complex doubles (re, im interleaved).  d_coeffs: device, int64 [count][N], the
+ * nearest integers to scale * m_k, ready for ckks_client_encrypt, ckks_plain_expand or
+ * ckks_weights_set_diagonals.  scale * max|z| must stay below 2^62.  Enqueues on `stream`; uses the library's
+ * scratch arena (64 vectors per pass). */
+int ckks_encode(ckks_params_t *params, const double *d_slots, uint32_t count, double scale, uint32_t flags,
+                int64_t *d_coeffs, void *stream);
+
+/* d_res: device, [count][nlimbs][N] canonical residues of the plaintext polynomial on the first nlimbs (1 or 2)
+ * ciphertext primes, coefficient domain (what ckks_client_decrypt writes); the centred lift must be the
+ * plaintext itself, i.e. |coefficients| < q_0/2 (or q_0*q_1/2).  d_slots: device, [count][n] complex doubles,
+ * m(zeta^(5^j)) / scale. */
+int ckks_decode(ckks_params_t *params, const uint64_t *d_res, uint32_t nlimbs, uint32_t count, double scale,
+                double *d_slots, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

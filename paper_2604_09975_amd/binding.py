@@ -55,6 +55,8 @@ _SIGS = {
     "ckks_mod_switch_to_next": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
     "ckks_shift_bank": [_vp, _vp, C.c_uint32, C.c_uint32, C.POINTER(C.c_int32), C.POINTER(_vp), _vp, _vp, _vp],
     "ckks_rot_first": [_vp, _vp, C.c_uint32, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp, _vp],
+    "ckks_encode": [_vp, _vp, C.c_uint32, C.c_double, C.c_uint32, _vp, _vp],
+    "ckks_decode": [_vp, _vp, C.c_uint32, C.c_uint32, C.c_double, _vp, _vp],
 }
 for _n, _a in _SIGS.items():
     getattr(lib, _n).argtypes = _a
@@ -335,6 +337,42 @@ def ckks_profile_end(P):
     ms, n = C.c_double(), C.c_uint32()
     _check(lib.ckks_profile_end(P.h, _stream(), C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+ENCODE_REAL = 1
+
+
+def _cdev(t):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == torch.complex128):
+        raise TypeError("expected a contiguous complex128 device tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def ckks_encode(P, d_slots, scale, flags=0, d_coeffs=None):
+    """d_slots complex128 [count][n] -> int64 [count][N], nearest integers to scale * m_k."""
+    n = P.N // 2
+    if d_slots.numel() % n:
+        raise ValueError("slot vectors must have N/2 entries")
+    count = d_slots.numel() // n
+    if d_coeffs is None:
+        d_coeffs = torch.empty((count, P.N), dtype=torch.int64, device=d_slots.device)
+    elif d_coeffs.numel() != count * P.N:
+        raise ValueError("d_coeffs must be [count][N]")
+    _check(lib.ckks_encode(P.h, _cdev(d_slots), count, float(scale), flags, _dev(d_coeffs), _stream()))
+    return d_coeffs
+
+
+def ckks_decode(P, d_res, nlimbs, scale, d_slots=None):
+    """d_res [count][nlimbs][N] coefficient-domain residues -> complex128 [count][n], m(zeta^(5^j)) / scale."""
+    if nlimbs < 1 or d_res.numel() % (nlimbs * P.N):
+        raise ValueError("d_res must be [count][nlimbs][N]")
+    count = d_res.numel() // (nlimbs * P.N)
+    if d_slots is None:
+        d_slots = torch.empty((count, P.N // 2), dtype=torch.complex128, device=d_res.device)
+    elif d_slots.numel() != count * (P.N // 2):
+        raise ValueError("d_slots must be [count][N/2]")
+    _check(lib.ckks_decode(P.h, _dev(d_res), nlimbs, count, float(scale), _cdev(d_slots), _stream()))
+    return d_slots
 
 
 # ---- key holder's side -------------------------------------------------------

@@ -1,7 +1,6 @@
-"""Key holder's helper around the library's ckks_client_* calls: complex-slot
-encode / decode on the host (numpy fp64), segment-column packing, the plaintext
-diagonals of the projection, and a `Client` that draws its randomness from the
-seeded generators in `workload`.  Off the server's path: the benchmark uses it
+"""Key holder's helper around the library's ckks_client_* / ckks_encode / ckks_decode calls: segment-column
+packing and the plaintext slot vectors of the projection on the host (numpy, data layout only), and a `Client`
+that draws its randomness from the seeded generators in `workload`.  Off the server's path: the benchmark uses it
 to make valid keys, ciphertexts and weights and to check decrypted results.
 
 Slot j of a plaintext m(X) is m(zeta^(5^j)) with zeta = exp(i*pi/N); rotations
@@ -15,63 +14,32 @@ from . import workload as W
 
 
 class Encoder:
-    """Canonical-embedding encoder for ring degree N (tables built once)."""
+    """Complex-slot encode / decode of one parameter set, on the device (ckks_encode / ckks_decode)."""
 
-    def __init__(self, N):
-        self.N, self.n = N, N // 2
-        e = np.empty(self.n, dtype=np.int64)
-        x = 1
-        for j in range(self.n):
-            e[j] = x
-            x = x * 5 % (2 * N)
-        self.pos = (e - 1) >> 1                     # FFT bin of slot j (odd exponent e = 2t+1)
-        self.neg = (2 * N - e - 1) >> 1             # bin of the conjugate root
-        self.twist = np.exp(-1j * np.pi * np.arange(N) / N)
+    def __init__(self, P):
+        self.P, self.N, self.n = P, P.N, P.N // 2
 
     def encode(self, z, scale):
-        """z [..., n] complex (or real) -> int64 [..., N]: nearest integers to scale * m, m the real
-        polynomial with m(zeta_j) = z_j."""
+        """z [..., n] complex or real (numpy) -> int64 device tensor [..., N]: nearest integers to scale * m, m
+        the real polynomial with m(zeta_j) = z_j.  Vectors whose imaginary parts are all zero get exactly
+        antisymmetric coefficients (m[N-j] = -m[j]), which lets the weight store keep half of every limb."""
         z = np.asarray(z)
-        v = np.zeros(z.shape[:-1] + (self.N,), dtype=np.complex128)
-        v[..., self.pos] = z
-        v[..., self.neg] = np.conj(z)
-        m = (np.fft.fft(v, axis=-1) * self.twist).real * (scale / self.N)
-        m = np.rint(m).astype(np.int64)
-        # a real slot vector is fixed by conjugation, so m(X) = m(1/X): m[N-j] = -m[j] exactly.  The FFT only
-        # gives that up to rounding; enforcing it (for every vector whose imaginary parts are all zero, also
-        # inside a complex batch) lets the library read half of every such weight limb.
-        h = self.N // 2
+        lead = z.shape[:-1]
         if np.isrealobj(z):
-            m[..., h + 1:] = -m[..., 1:h][..., ::-1]
-            m[..., h] = 0
-        else:
-            real_rows = ~np.any(z.imag != 0, axis=-1)
-            if np.any(real_rows):
-                sub = m[real_rows]
-                sub[..., h + 1:] = -sub[..., 1:h][..., ::-1]
-                sub[..., h] = 0
-                m[real_rows] = sub
-        return m
+            d = torch.from_numpy(np.ascontiguousarray(z.reshape(-1, self.n), dtype=np.float64)).cuda().to(torch.complex128)
+            return B.ckks_encode(self.P, d, scale, B.ENCODE_REAL).reshape(lead + (self.N,))
+        flat = z.reshape(-1, self.n)
+        d = torch.from_numpy(np.ascontiguousarray(flat, dtype=np.complex128)).cuda()
+        out = B.ckks_encode(self.P, d, scale)
+        real_rows = np.flatnonzero(~np.any(flat.imag != 0, axis=-1))
+        if real_rows.size:
+            idx = torch.from_numpy(real_rows).cuda()
+            out[idx] = B.ckks_encode(self.P, d[idx].contiguous(), scale, B.ENCODE_REAL)
+        return out.reshape(lead + (self.N,))
 
-    def decode(self, m, scale):
-        """m: N centred integers (array of Python ints or floats) -> n complex slots."""
-        mf = np.asarray([float(x) for x in m]) if not isinstance(m, np.ndarray) or m.dtype == object else m.astype(np.float64)
-        t = np.fft.ifft(mf * np.conj(self.twist)) * self.N
-        return t[self.pos] / scale
-
-
-def centred_crt(res, moduli):
-    """res [nl][N] uint64 residues (nl <= 3) -> list of centred Python ints."""
-    M = 1
-    for q in moduli:
-        M *= int(q)
-    acc = [0] * res.shape[1]
-    for i, q in enumerate(moduli):
-        Mi = M // int(q)
-        c = Mi * pow(Mi, -1, int(q))
-        acc = [a + int(r) * c for a, r in zip(acc, res[i].tolist())]
-    half = M // 2
-    return [(a % M) - M if (a % M) > half else (a % M) for a in acc]
+    def decode(self, d_res, nlimbs, scale):
+        """d_res device [nlimbs][N] coefficient-domain residues (nlimbs <= 2) -> n complex slots (numpy)."""
+        return B.ckks_decode(self.P, d_res.reshape(1, nlimbs, self.N), nlimbs, scale)[0].cpu().numpy()
 
 
 def pack_columns(X, n, C):
@@ -148,7 +116,7 @@ class Client:
         self.r = W.rng(seed)
         self.s = W.ternary_secret(self.r, P.N, hamming_weight)
         self.S = B.ckks_client_secret_load(P, self.s)
-        self.enc = Encoder(P.N)
+        self.enc = Encoder(P)
         self.moduli = P.q + P.p
 
     def _dev(self, a):
@@ -180,10 +148,9 @@ class Client:
         m = self.enc.encode(z, scale)
         a = W.uniform_residues(self.r, P.q[:level], P.N)
         e = W.gaussian_error(self.r, (P.N,))
-        return B.ckks_client_encrypt(P, self.S, level, self._dev(m), self._dev(a), self._dev(e))
+        return B.ckks_client_encrypt(P, self.S, level, m, self._dev(a), self._dev(e))
 
     def decrypt_slots(self, d_ct, level, scale, nlimbs=2):
         P = self.P
         nlimbs = min(nlimbs, level)
-        res = B.ckks_client_decrypt(P, self.S, d_ct, level, nlimbs).cpu().numpy().view(np.uint64)
-        return self.enc.decode(centred_crt(res, P.q[:nlimbs]), scale)
+        return self.enc.decode(B.ckks_client_decrypt(P, self.S, d_ct, level, nlimbs), nlimbs, scale)

@@ -78,6 +78,10 @@ struct ckks_params {
     ckks::u64 *d_pinv = nullptr;       // [L]: P^-1 mod q_i
     ckks::u64 *d_qlinv = nullptr;      // [L][L]: q_l^-1 mod q_i (rescale), row l
     std::map<ckks::u32, ckks::LevelTables> levels;
+    // complex-slot encode / decode (built on first use): exp(-2*pi*i*e/N), e < N/2; exp(-i*pi*k/N), k < N; and the
+    // transform bin (5^j mod 2N - 1)/2 of slot j
+    double *d_fft_w = nullptr, *d_fft_twist = nullptr;
+    ckks::u32 *d_slot_bin = nullptr;
     // private scratch arena
     void *d_scratch = nullptr;
     size_t scratch_bytes = 0;

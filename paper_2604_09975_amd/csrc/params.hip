@@ -385,6 +385,9 @@ void ckks_params_destroy(ckks_params_t *P) {
         hipFree(kv.second.d_up_mat);
         hipFree(kv.second.d_up_matf);
     }
+    hipFree(P->d_fft_w);
+    hipFree(P->d_fft_twist);
+    hipFree(P->d_slot_bin);
     hipFree(P->d_scratch);
     for (hipEvent_t ev : P->prof_ev) hipEventDestroy(ev);
     delete P;

@@ -1,5 +1,5 @@
 """GPU parity: the key holder's calls (keygen, encrypt, decrypt) against the oracle, bit for bit,
-and the host encoder against the oracle's within rounding."""
+and the client helper (device encoder, host packing) against the oracle."""
 import numpy as np
 import pytest
 import torch
@@ -39,15 +39,22 @@ def test_keygen_encrypt_decrypt_bit_exact(spec):
         assert (dec == O.decrypt(want, lvl, s, nl)).all()
 
 
-def test_host_encoder_matches_oracle_encoder():
+def test_client_encoder_and_packing_match_oracle():
     from paper_2604_09975_amd import client as CL
     r = W.rng(3)
-    for N in (1 << 5, 1 << 12, 1 << 16):
-        enc = CL.Encoder(N)
-        z = W.unit_disk_slots(r, N // 2)
-        a, b = enc.encode(z, 2.0**40), E.encode(z, 2.0**40, N)
-        assert np.abs(a - b).max() <= 1                      # two fp64 evaluations may round a near-tie apart
-        assert np.abs(enc.decode(a, 2.0**40) - z).max() < 1e-7
+    for ring, scale in ((W.TOY_RING, 2.0**30), (W.BIG_RING, 2.0**40)):
+        O, P = make_pair(ring)
+        enc = CL.Encoder(P)
+        z = W.unit_disk_slots(r, O.n)
+        a, b = enc.encode(z, scale), E.encode(z, scale, O.N)
+        assert np.abs(a.cpu().numpy() - b).max() <= 1        # two fp64 evaluations may round a near-tie apart
+        res = torch.remainder(a, int(O.q[0]))
+        assert np.abs(enc.decode(res, 1, scale) - z).max() < O.N / scale
+        # mixed batch: the real row comes out exactly antisymmetric
+        zz = np.stack([z, z.real + 0j])
+        m = enc.encode(zz, scale).cpu().numpy()
+        assert (m[1, O.N // 2 + 1:] == -m[1, 1:O.N // 2][::-1]).all() and m[1, O.N // 2] == 0
+        assert np.abs(m[0] - b).max() <= 1
     X = r.standard_normal((4, 40))
     assert (CL.pack_columns(X, 128, 16) == E.pack_columns(X, 128, 16)).all()
     Wm = r.standard_normal((40, 20))
@@ -59,5 +66,3 @@ def test_host_encoder_matches_oracle_encoder():
                     assert (d[g, q] == E.weight_diagonal(Wm, 4, 128, 16, 4, b, p, g, q)).all()
     sl = r.standard_normal((2, 128))
     assert (CL.unpack_columns(sl, 4, 16, 20) == E.unpack_columns(sl, 4, 16, 20)).all()
-    res = np.array([[5, 0, 7], [1, 3, 2]], dtype=np.uint64)
-    assert CL.centred_crt(res, [11, 13]) == E.crt_centre(res, [11, 13])
