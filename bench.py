@@ -90,6 +90,38 @@ def setup_matmul(B, CL, W, P, cl, spec, n1, key_cache=None, fused_qk=False, pair
                 level=level)
 
 
+def measured_ceilings(B, P):
+    """Streaming rates of plain copy / read / write kernels over 2 GiB buffers and the issue rates of the two
+    modular products, measured live (the fractions beside the published peaks are against these)."""
+    import torch
+    src = torch.ones(1 << 28, dtype=torch.int64, device="cuda")
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(f, reps=5):
+        f()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    nbytes = src.numel() * 8
+    out = {"copy_GBps": 2 * nbytes / timed(lambda: B.ckks_probe_stream(dst, src, B.PROBE_COPY)) / 1e9,
+           "read_GBps": nbytes / timed(lambda: B.ckks_probe_stream(dst, src, B.PROBE_READ)) / 1e9,
+           "write_GBps": nbytes / timed(lambda: B.ckks_probe_stream(dst, None, B.PROBE_WRITE)) / 1e9}
+    del src, dst
+    lanes, iters = 1 << 20, 2000
+    sink = torch.empty(lanes, dtype=torch.int64, device="cuda")
+    for name, kind, limb in (("fp64_mulmod_per_s", B.PROBE_FP64, 0), ("int64_mulmod_per_s", B.PROBE_INT64, P.L)):
+        if kind == B.PROBE_FP64 and P.q[0] >> 50:
+            continue
+        out[name] = 4.0 * lanes * iters / timed(lambda: B.ckks_probe_mulmod(P, limb, kind, lanes, iters, sink), 3)
+    return out
+
+
 def read_traffic(workload, n1):
     """HBM bytes per diag_mac_kernel launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
     WRITE_SIZE runs, scaled by the plain-copy factors stated there); None if it is for another plan."""
@@ -574,6 +606,13 @@ def main():
                      "fp64_issue_frac": mac_ops / (mac_ms * 1e-3) / FP64_ISSUE_PEAK,
                      "frac_at_8_bytes_per_residue": mac_bytes_8 / (mac_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    ceil = measured_ceilings(B, P)
+    out["measured_ceilings"] = ceil
+    out["roofline"]["frac_of_measured_read"] = achieved / ceil["read_GBps"]
+    if "fp64_mulmod_per_s" in ceil:     # 4 products per stored weight residue, against the bare product chain
+        out["roofline"]["frac_of_measured_fp64_mulmod"] = (mac_ops / 7.0) / (mac_ms * 1e-3) / ceil["fp64_mulmod_per_s"]
+    if steps:
+        out["hoisted_batch"]["frac_of_measured_copy"] = ks_bytes * ks_per_s / (ceil["copy_GBps"] * 1e9)
     if not args.no_cpu_baseline:
         t0 = time.time()
         out["cpu_baseline"] = cpu_baseline(W, spec, n1)

@@ -281,6 +281,26 @@ int ckks_encode(ckks_params_t *params, const double *d_slots, uint32_t count, do
 int ckks_decode(ckks_params_t *params, const uint64_t *d_res, uint32_t nlimbs, uint32_t count, double scale,
                 double *d_slots, void *stream);
 
+/* ---- measured ceilings of the machine (what roofline fractions are also reported against) ----
+ * Plain streaming kernels and chains of the two modular products the kernels are built from; the caller times
+ * them with events on `stream`. */
+
+#define CKKS_PROBE_COPY 0u  /* d_dst[i] = d_src[i]: n_words read and n_words written */
+#define CKKS_PROBE_READ 1u  /* n_words of d_src read, at most one word of d_dst written */
+#define CKKS_PROBE_WRITE 2u /* n_words of d_dst written (d_src unused) */
+int ckks_probe_stream(uint64_t *d_dst, const uint64_t *d_src, uint64_t n_words /* even */, uint32_t mode,
+                      void *stream);
+
+#define CKKS_PROBE_INT64 0u /* 64-bit Montgomery product (any prime of the chain) */
+#define CKKS_PROBE_FP64 1u  /* exact product in doubles (primes below 2^50) */
+/* Every one of n_threads lanes (a multiple of 256) runs four independent chains of `iters` dependent products
+ * x <- x * psi mod q, q = prime `limb` (ciphertext primes first, then special), psi its 2N-th root
+ * (ckks_params_root), chain c of lane t starting from (4t + c + 1) mod 2^20; d_out[t] (device, n_threads words) is
+ * the XOR of the four canonical results, so the caller can check the arithmetic it timed:
+ * 4 * n_threads * iters products per launch. */
+int ckks_probe_mulmod(const ckks_params_t *params, uint32_t limb, uint32_t kind, uint32_t n_threads, uint32_t iters,
+                      uint64_t *d_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -55,6 +55,8 @@ _SIGS = {
     "ckks_mod_switch_to_next": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
     "ckks_shift_bank": [_vp, _vp, C.c_uint32, C.c_uint32, C.POINTER(C.c_int32), C.POINTER(_vp), _vp, _vp, _vp],
     "ckks_rot_first": [_vp, _vp, C.c_uint32, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp, _vp],
+    "ckks_probe_stream": [_vp, _vp, C.c_uint64, C.c_uint32, _vp],
+    "ckks_probe_mulmod": [_vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, _vp, _vp],
     "ckks_encode": [_vp, _vp, C.c_uint32, C.c_double, C.c_uint32, _vp, _vp],
     "ckks_decode": [_vp, _vp, C.c_uint32, C.c_uint32, C.c_double, _vp, _vp],
 }
@@ -337,6 +339,28 @@ def ckks_profile_end(P):
     ms, n = C.c_double(), C.c_uint32()
     _check(lib.ckks_profile_end(P.h, _stream(), C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+PROBE_COPY, PROBE_READ, PROBE_WRITE = 0, 1, 2
+PROBE_INT64, PROBE_FP64 = 0, 1
+
+
+def ckks_probe_stream(d_dst, d_src, mode):
+    """One launch of the plain copy / read / write kernel over the whole of d_dst (and d_src)."""
+    n = d_dst.numel() if mode == PROBE_WRITE else d_src.numel()
+    if mode == PROBE_COPY and d_dst.numel() != d_src.numel():
+        raise ValueError("copy needs equal sizes")
+    _check(lib.ckks_probe_stream(_dev(d_dst), _dev(d_src) if d_src is not None else None, n, mode, _stream()))
+
+
+def ckks_probe_mulmod(P, limb, kind, n_threads, iters, d_out=None):
+    """-> d_out [n_threads]: XOR over c < 4 of ((4t + c + 1) mod 2^20) * psi^iters mod q."""
+    if d_out is None:
+        d_out = torch.empty(n_threads, dtype=torch.int64, device="cuda")
+    elif d_out.numel() != n_threads:
+        raise ValueError("d_out must hold n_threads words")
+    _check(lib.ckks_probe_mulmod(P.h, limb, kind, n_threads, iters, _dev(d_out), _stream()))
+    return d_out
 
 
 ENCODE_REAL = 1

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libckks_hip.so")
-SOURCES = ["params.hip", "ntt.hip", "keyswitch.hip", "matmul.hip", "evalops.hip", "encode.hip", "client.hip"]
+SOURCES = ["params.hip", "ntt.hip", "keyswitch.hip", "matmul.hip", "evalops.hip", "encode.hip", "probe.hip", "client.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-ffp-contract=off", "-Wall", "-Wno-unused-function", "-Wno-unused-value", "-Wno-unused-result"]

@@ -183,3 +183,38 @@ def test_shift_bank_errors():
     assert int(out.abs().sum()) == 0
     assert B.lib.ckks_shift_bank(P.h, ct.data_ptr(), 4, 0, None, None, None, None, None) == -2
     assert B.lib.ckks_shift_bank(P.h, ct.data_ptr(), 3, 0, None, None, None, None, None) == 0
+
+
+def test_probe_kernels_compute_what_they_time():
+    """The ceiling probes: the product chains end in x0 * psi^iters mod q (both arithmetics, checked against
+    Python integers), the copy kernel copies, the write kernel writes every word; bad arguments are refused."""
+    from paper_2604_09975_amd import binding as B
+    O, P = make_pair(W.BIG_RING)
+    lanes, iters = 512, 37
+    for kind, limb in ((B.PROBE_FP64, 0), (B.PROBE_FP64, 23), (B.PROBE_INT64, 5), (B.PROBE_INT64, 24 + 7)):
+        q = int(O.moduli[limb])
+        psi = B.ckks_params_root(P, limb)
+        assert pow(psi, 2 * O.N, q) == 1 and pow(psi, O.N, q) == q - 1
+        f = pow(psi, iters, q)
+        got = to_host(B.ckks_probe_mulmod(P, limb, kind, lanes, iters))
+        for t in (0, 1, 255, 256, 511):
+            want = 0
+            for c in range(4):
+                want ^= ((4 * t + c + 1) % (1 << 20)) * f % q
+            assert int(got[t]) == want, (kind, limb, t)
+    src = torch.arange(1 << 16, dtype=torch.int64, device="cuda") * 3 + 1
+    dst = torch.zeros_like(src)
+    B.ckks_probe_stream(dst, src, B.PROBE_COPY)
+    assert bool((dst == src).all())
+    B.ckks_probe_stream(dst, None, B.PROBE_WRITE)
+    d = dst.cpu().numpy().view(np.uint64).reshape(-1, 2)
+    assert (d[:, 0] == np.arange(1 << 15, dtype=np.uint64)).all() and (d[:, 1] == ~np.arange(1 << 15, dtype=np.uint64)).all()
+    before = dst.clone()
+    B.ckks_probe_stream(dst, src, B.PROBE_READ)
+    assert bool((dst == before).all())
+    with pytest.raises(B.CkksError):
+        B.ckks_probe_mulmod(P, 24, B.PROBE_FP64, lanes, iters)       # 60-bit prime: no fp64 product
+    with pytest.raises(B.CkksError):
+        B.ckks_probe_mulmod(P, 0, B.PROBE_INT64, 100, iters)
+    with pytest.raises(B.CkksError):
+        B.ckks_probe_stream(dst, src, 3)
