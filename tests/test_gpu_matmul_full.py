@@ -17,14 +17,18 @@ from paper_2604_09975_amd import workload as W
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("merged,pairs", [(False, False), (True, False), (True, True)],
-                         ids=["default", "merged_giant", "complex_pairs_merged_giant"])
-def test_bert_qkv_sampled_block_bit_exact(merged, pairs):
-    """pairs: complex-pair compression of the inputs (Sec. 3.2): two complexified inputs, the second with
+@pytest.mark.parametrize("spec,merged,pairs", [(W.BERT_QKV, False, False), (W.BERT_QKV, True, False),
+                                               (W.BERT_QKV, True, True), (W.GPT2_LAYERS[1], True, False),
+                                               (W.GPT2_LAYERS[2], True, False)],
+                         ids=["default", "merged_giant", "complex_pairs_merged_giant", "gpt2_attn_out_n1_16",
+                              "gpt2_ffn_up_12_blocks"])
+def test_bert_qkv_sampled_block_bit_exact(spec, merged, pairs):
+    """The QKV projection in the three forms the benchmark times, and the two other 768-wide layers of the GPT-2
+    block (attention output: N1 = 16, 3 output blocks; FFN up: 12 output blocks) as it runs them.
+    pairs: complex-pair compression of the inputs (Sec. 3.2): two complexified inputs, the second with
     imaginary part zero and real weights (half records, second launch), one conjugation per block."""
     from paper_2604_09975_amd import binding as B
     t0 = time.time()
-    spec = W.BERT_QKV
     O, P = make_pair(spec.ring)
     N, n, m, C, N1 = O.N, O.n, spec.m, spec.C, spec.N1
     G, B_out, N2 = W.plan(spec)
