@@ -13,7 +13,7 @@ namespace ckks {
 
 constexpr u32 MAX_LIMBS = 64;     // L + K
 constexpr u32 MAX_DIGIT = 16;     // alpha and K
-constexpr u32 ROT_BATCH = 16;     // key switches in flight per kernel wave
+constexpr u32 ROT_BATCH = 32;     // key switches per batch of kernel launches
 constexpr u32 SKIP_ROW = 255;     // limb id meaning "leave this row alone"
 
 constexpr u32 MAX_ROW_IDS = 128;  // rows described by one LimbIds pattern

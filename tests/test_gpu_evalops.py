@@ -153,10 +153,10 @@ def test_psi_bank_toy():
 
 
 def test_psi_bank_more_outputs_than_one_batch_and_identity_terms():
-    """11 outputs = 22 rotations (two batches of key switches); t = 0 has an identity first term."""
+    """19 outputs = 38 rotations (two batches of key switches); t = 0 has an identity first term."""
     O = helpers.small_oracle(10, L=4, K=2, dnum=2, qbits=40, pbits=45)
     _, P = make_pair(O)
-    _psi_bank(O, P, 4, 32, list(range(0, 11)), 52, 2.0**30)
+    _psi_bank(O, P, 4, 32, list(range(0, 19)), 52, 2.0**30)
 
 
 def test_psi_bank_full_ring():

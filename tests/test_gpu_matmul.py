@@ -176,12 +176,12 @@ def test_merged_giant_step(ring, N1):
 
 @pytest.mark.parametrize("merged", [False, True])
 def test_more_blocks_than_one_switch_batch(merged):
-    """B_out = 20 output blocks: the giant step runs in more than one batch of key switches."""
+    """B_out = 36 output blocks: the giant step runs in more than one batch of (32) key switches."""
     O = helpers.small_oracle(10, L=2, K=1, dnum=2, qbits=40, pbits=42)
     _, P = make_pair(O)
     r = W.rng(10)
     X = r.uniform(-1, 1, (64, 8))
-    Wm = r.uniform(-0.5, 0.5, (8, 160))
+    Wm = r.uniform(-0.5, 0.5, (8, 288))
     Y, ref, cnt, _ = run_case(O, P, X, Wm, None, 64, 8, 4, 30, 2, 29, hw=16, merged=merged)
     assert np.abs(Y - ref).max() <= 1e-3
 

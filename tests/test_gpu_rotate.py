@@ -72,9 +72,9 @@ def test_largest_primes_and_widest_digits():
 
 
 def test_more_steps_than_one_batch():
-    """20 key switches: more than the library keeps in flight at once."""
+    """40 key switches: more than the library keeps in flight at once (32)."""
     O, P = make_pair(W.TOY_RING)
-    _run(O, P, 3, list(range(1, 20)) + ["conj"], 17, 2.0**30)
+    _run(O, P, 3, list(range(1, 40)) + ["conj"], 17, 2.0**30)
 
 
 def test_full_size_hoisted_batch():
