@@ -814,8 +814,13 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         if (rc) return rc;
         SwitchItem items[ROT_BATCH];
         u32 n_it = 0;
+        // the inputs of one step stay in one batch; the steps are spread evenly over the batches they need
+        u32 n_rot = 0;
+        for (u32 q = 0; q < N1; ++q) n_rot += baby_g[q] != 1;
+        const u32 per_max = ROT_BATCH / ng, n_batches = (n_rot + per_max - 1) / per_max;
+        const u32 per = n_batches ? (n_rot + n_batches - 1) / n_batches : per_max;
         for (u32 q = 0; q < N1; ++q) {
-            if (n_it + ng > ROT_BATCH) {   // keep the inputs of one step in one batch
+            if (n_it + ng > per * ng) {
                 rc = switch_batch(P, level, items, n_it, d_work, stream);
                 if (rc) return rc;
                 n_it = 0;
