@@ -16,3 +16,11 @@ def pytest_configure(config):
 def toy_oracle():
     from tests import helpers
     return helpers.make_oracle(helpers.W.TOY_RING)
+
+
+def pytest_runtest_logreport(report):
+    """A GPU run is watched for output: every finished GPU test leaves one unbuffered line on stderr (pytest's own
+    progress dots can sit in a pipe's buffer for the whole run)."""
+    if report.when == "call" and "gpu" in report.keywords:
+        sys.__stderr__.write(f"[gpu-test] {report.nodeid} {report.outcome} {report.duration:.1f}s\n")
+        sys.__stderr__.flush()
