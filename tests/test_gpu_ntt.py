@@ -23,9 +23,10 @@ def test_roots_match_oracle():
             assert B.ckks_params_root(P, limb) == O.psi(limb)
 
 
-@pytest.mark.parametrize("logN,batch", [(10, 3), (11, 2), (12, 5), (13, 3), (14, 2)])
+@pytest.mark.parametrize("logN,batch", [(10, 3), (11, 2), (12, 5), (13, 3), (14, 2), (15, 1), (17, 1)])
 def test_small_rings_bit_exact(logN, batch):
-    """One-tile rings (N <= 4096) and two-pass rings, odd batch sizes, limbs listed out of order."""
+    """One-tile rings (N <= 4096) and two-pass rings up to the largest admitted degree (2^17), odd batch sizes,
+    limbs listed out of order."""
     B = _B()
     O = helpers.small_oracle(logN, L=3, K=2, dnum=3, qbits=50, pbits=60)
     _, P = make_pair(O)

@@ -51,6 +51,15 @@ def test_multi_limb_digits_and_partial_last_digit(L, K, dnum, level):
     _run(O, P, level, [1, 2, "conj", 0, 33], L * 7 + level, 2.0**30, hw=16)
 
 
+@pytest.mark.parametrize("logN", [11, 13, 15, 17])
+def test_other_ring_degrees(logN):
+    """Key switching on the generic transform path: degrees between and beyond the two tuned ones, up to the
+    largest admitted (2^17)."""
+    O = helpers.small_oracle(logN, L=4, K=2, dnum=2, qbits=45, pbits=50)
+    _, P = make_pair(O)
+    _run(O, P, 3, [1, "conj", (1 << (logN - 1)) - 1], 90 + logN, 2.0**36, hw=32)
+
+
 def test_largest_primes_and_widest_digits():
     """16-limb digit and 16 special primes at the largest prime size the library admits for them (16 lazy
     products must stay below 2^64 times the modulus: primes below 2^60), and the refusal one bit above."""
