@@ -202,6 +202,29 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
     }
 }
 
+// dst[z][0 .. words) = src[z * src_stride + 0 .. words), z = blockIdx.z; words is a multiple of 2 * EW_THREADS
+__global__ __launch_bounds__(EW_THREADS) void copy_blocks_kernel(u64 *__restrict__ dst, const u64 *__restrict__ src,
+                                                                 size_t words, size_t src_stride) {
+    typedef u64 vec_t __attribute__((ext_vector_type(2)));
+    const size_t k = ((size_t)blockIdx.x * EW_THREADS + threadIdx.x) * 2;
+    *reinterpret_cast<vec_t *>(dst + blockIdx.z * words + k) =
+        *reinterpret_cast<const vec_t *>(src + blockIdx.z * src_stride + k);
+}
+
+// y[b][0][i][.] += bias[b][i][.]: blockIdx.y = limb, blockIdx.z = output block, two residues per thread
+__global__ __launch_bounds__(EW_THREADS) void add_bias_kernel(u64 *__restrict__ y, const u64 *__restrict__ bias,
+                                                              const ModConst *__restrict__ mods, u32 level, u32 N) {
+    typedef u64 vec_t __attribute__((ext_vector_type(2)));
+    const u32 k = (blockIdx.x * EW_THREADS + threadIdx.x) * 2, i = blockIdx.y, b = blockIdx.z;
+    const u64 q = mods[i].q;
+    vec_t *dst = reinterpret_cast<vec_t *>(y + ((size_t)b * 2 * level + i) * N + k);
+    const vec_t s = *reinterpret_cast<const vec_t *>(bias + ((size_t)b * level + i) * N + k);
+    vec_t v = *dst;
+    v[0] = add_mod(v[0], s[0], q);
+    v[1] = add_mod(v[1], s[1], q);
+    *dst = v;
+}
+
 // Same sum for plaintexts that encode REAL slot vectors.  Such a polynomial is fixed by X -> X^-1, so its
 // transform is a palindrome: w[k] = w[N-1-k] (the exponents 2*bitrev(k)+1 and 2*bitrev(N-1-k)+1 are
 // negatives of each other mod 2N).  Only the first half of every weight limb is read; each value serves
@@ -930,9 +953,12 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         P->prof_used += 2;
     }
     // 3. giant steps: y_b = acc_{b,0} + sum_p rot(acc_{b,p})
-    for (u32 b = 0; b < B; ++b)
-        CKKS_HIP(hipMemcpyAsync(d_ct_y + (size_t)b * ctw, d_acc + (size_t)b * N2 * ctw, ctw * sizeof(u64),
-                                hipMemcpyDeviceToDevice, stream));
+    for (u32 b0 = 0; b0 < B; b0 += 65535) {
+        hipLaunchKernelGGL(copy_blocks_kernel, dim3((u32)(ctw / (2 * EW_THREADS)), 1, std::min<u32>(B - b0, 65535)),
+                           dim3(EW_THREADS), 0, stream, d_ct_y + (size_t)b0 * ctw, d_acc + (size_t)b0 * N2 * ctw, ctw,
+                           (size_t)N2 * ctw);
+        CKKS_LAUNCH_CHECK("copy_blocks_kernel");
+    }
     u64 *d_u = d_acc + acc_w, *d_mdig = d_u + u_w;
     if (merged) {
         // rotations that are a full turn are plain additions; the others are grouped: the accumulators of a
@@ -1033,12 +1059,13 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             CKKS_LAUNCH_CHECK("add_rows_kernel");
         }
     }
-    // 4. bias into c0
+    // 4. bias into c0 of every block
     if (w->d_bias) {
-        for (u32 b = 0; b < B; ++b) {
-            hipLaunchKernelGGL(add_rows_kernel, dim3(N / EW_THREADS, level), dim3(EW_THREADS), 0, stream,
-                               d_ct_y + (size_t)b * ctw, w->d_bias + (size_t)b * level * N, P->d_mod, level, N);
-            CKKS_LAUNCH_CHECK("add_rows_kernel");
+        for (u32 b0 = 0; b0 < B; b0 += 65535) {
+            hipLaunchKernelGGL(add_bias_kernel, dim3(N / (2 * EW_THREADS), level, std::min<u32>(B - b0, 65535)),
+                               dim3(EW_THREADS), 0, stream, d_ct_y + (size_t)b0 * ctw,
+                               w->d_bias + (size_t)b0 * level * N, P->d_mod, level, N);
+            CKKS_LAUNCH_CHECK("add_bias_kernel");
         }
     }
     if (counters) {
