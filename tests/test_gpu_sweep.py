@@ -92,3 +92,29 @@ def test_pair_compression_sweep(seed):
                       for b in range(B_out)])
     assert np.abs(E.unpack_columns(slots.real, m, C, c["d_out"]) - (X @ Wm + bias)).max() <= 1e-3, c
     assert np.abs(slots.imag).max() <= 1e-3, c
+
+
+@pytest.mark.parametrize("seed", range(200, 232))
+def test_key_switch_sweep(seed):
+    """Hoisted rotations (random steps with repeats, the identity and conjugation), ctmul + relinearisation and a
+    small bank of intra-segment shifts on random chains, levels (1 included) and ring degrees 2^10 .. 2^13."""
+    from tests.test_gpu_ctmul import _case as ctmul_case
+    from tests.test_gpu_evalops import _psi_bank
+    from tests.test_gpu_rotate import _run as rotate_case
+    r = W.rng(seed)
+    logN = int(r.choice([10, 11, 12, 13]))
+    L = int(r.choice([1, 2, 3, 4, 6, 8]))
+    dnum = int(r.choice([d for d in (1, 2, 3, 4, 6, 8) if L % d == 0]))
+    K = L // dnum + 1          # P exceeds every digit product by a whole prime: the helpers' decode bounds hold
+    qbits = int(r.choice([40, 45, 49, 52, 55]))
+    level = int(r.integers(1, L + 1))
+    O = helpers.small_oracle(logN, L=L, K=K, dnum=dnum, qbits=qbits, pbits=min(qbits + 6, 60))
+    _, P = make_pair(O)
+    n = O.n
+    steps = [int(s) for s in r.integers(0, n, int(r.integers(1, 6)))] + ["conj", 0]
+    steps.append(steps[0])                                   # a repeated step
+    scale = 2.0 ** (qbits - 4)      # after a mask product and one rescale the scale is still about 2^(qbits - 8)
+    rotate_case(O, P, level, steps, seed, scale, hw=16)
+    ctmul_case(O, P, level, seed + 1, scale, 16)
+    m = int(r.choice([8, 16, 32]))
+    _psi_bank(O, P, level, m, [int(t) for t in r.integers(0, m, 3)], seed + 2, scale)
