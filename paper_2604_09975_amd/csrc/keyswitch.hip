@@ -517,6 +517,13 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
     typedef u64 vec_t __attribute__((ext_vector_type(2)));
     const u32 tid = threadIdx.x, base = blockIdx.x << 12;
     constexpr u32 EPP = EPI / 2;
+    FieldFp ff;
+    ff.q = mf.q;
+    ff.u = mf.u;
+    ff.n0 = ff.n1 = 0.0;
+    ff.tw = nullptr;
+    const u64 pinv_plain = mont_mul(pi, 1, m);                       // P^-1 (pi is its Montgomery form)
+    const double c_w = ff.in(pinv_plain), c_sum = ff.in(mont_mul(pinv_plain, 1, m));
     for (u32 i0 = 0; i0 < 8; i0 += EPP) {
         u64 dv[EPP][2][MAX_BETA], cv[EPP][2];
         vec_t kv[EPP][MAX_BETA], ov[EPP];
@@ -545,13 +552,25 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
             vec_t out;
 #pragma unroll
             for (u32 z = 0; z < 2; ++z) {
-                u128 acc = {0, 0};
+                if (mf.ok) {
+                    // primes below 2^50: the same residues through exact fp64 products.  The keys are in
+                    // Montgomery form (times 2^64), so the sum is multiplied by 2^-64 * P^-1 and w by P^-1.
+                    double sum = 0.0;
 #pragma unroll
-                for (u32 j = 0; j < MAX_BETA; ++j)
-                    if (j < beta) mac(acc, dv[e][z][j], kv[e][j][z]);
-                u64 v = mont_mul(sub_mod(redc_wide(acc, m), lds[lds_pad(loc + z)], m.q), pi, m);
-                v = add_mod(v, cv[e][z], m.q);
-                out[z] = add_mod(v, ov[e][z], m.q);
+                    for (u32 j = 0; j < MAX_BETA; ++j)
+                        if (j < beta) sum += ff.mul(ff.in(dv[e][z][j]), ff.in(kv[e][j][z]));
+                    const double t = ff.mul(sum, c_sum) - ff.mul(ff.in(lds[lds_pad(loc + z)]), c_w) +
+                                     (ff.in(cv[e][z]) + ff.in(ov[e][z]));
+                    out[z] = ff.out(t);
+                } else {
+                    u128 acc = {0, 0};
+#pragma unroll
+                    for (u32 j = 0; j < MAX_BETA; ++j)
+                        if (j < beta) mac(acc, dv[e][z][j], kv[e][j][z]);
+                    u64 v = mont_mul(sub_mod(redc_wide(acc, m), lds[lds_pad(loc + z)], m.q), pi, m);
+                    v = add_mod(v, cv[e][z], m.q);
+                    out[z] = add_mod(v, ov[e][z], m.q);
+                }
             }
             __builtin_nontemporal_store(out, reinterpret_cast<vec_t *>(dst + base + loc));
         }
