@@ -262,17 +262,33 @@ __global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, c
     for (u32 i = 0; i < rots.n_rot; ++i) {
         const u32 kp = galois_index(k, rots.galois_elt[i], logN);
         const u64 *key = rots.key[i];
-        for (u32 j = 0; j < beta; ++j) {
-            const u64 k0 = __builtin_nontemporal_load(key + (((size_t)j * 2 + 0) * Wt + gl) * N + k);
-            const u64 k1 = __builtin_nontemporal_load(key + (((size_t)j * 2 + 1) * Wt + gl) * N + k);
+        // the loads of up to MAX_BETA digits are issued before their products
+        for (u32 j0 = 0; j0 < beta; j0 += MAX_BETA) {
+            u64 k0[MAX_BETA], k1[MAX_BETA], d[MAX_BETA][MR];
 #pragma unroll
-            for (u32 r = 0; r < MR; ++r)
-                if (r0 + r < n) {
-                    const u64 d = own == j ? c0_base[(size_t)(r0 + r) * c0_stride_r + rots.c0_off[i] +
+            for (u32 jj = 0; jj < MAX_BETA; ++jj) {
+                const u32 j = j0 + jj;
+                if (j < beta) {
+                    k0[jj] = __builtin_nontemporal_load(key + (((size_t)j * 2 + 0) * Wt + gl) * N + k);
+                    k1[jj] = __builtin_nontemporal_load(key + (((size_t)j * 2 + 1) * Wt + gl) * N + k);
+#pragma unroll
+                    for (u32 r = 0; r < MR; ++r)
+                        if (r0 + r < n)
+                            d[jj][r] = own == j
+                                           ? c0_base[(size_t)(r0 + r) * c0_stride_r + rots.c0_off[i] +
                                                      ((size_t)level + t) * N + kp]
                                            : digits[((size_t)i * n + r0 + r) * dig_w + ((size_t)j * Wl + t) * N + kp];
-                    mac(a0[r], d, k0);
-                    mac(a1[r], d, k1);
+                }
+            }
+#pragma unroll
+            for (u32 jj = 0; jj < MAX_BETA; ++jj)
+                if (j0 + jj < beta) {
+#pragma unroll
+                    for (u32 r = 0; r < MR; ++r)
+                        if (r0 + r < n) {
+                            mac(a0[r], d[jj][r], k0[jj]);
+                            mac(a1[r], d[jj][r], k1[jj]);
+                        }
                 }
         }
         if (t < level) {
