@@ -228,9 +228,6 @@ __global__ __launch_bounds__(KS_THREADS) void inner_product_kernel(ItemPack pack
     }
 }
 
-// y holds, per (item, component), the K special-limb rows y_k = INTT(u_{p_k}) * (P/p_k)^-1 in the coefficient
-// domain (the scaling comes out of the inverse transform); row (pc, k) starts at y + (pc*ystride + yoff + k)*N.
-// w_i = sum_k y_k * (P/p_k mod q_i) mod q_i for a chunk of target limbs i.
 // Inner products of several rotations summed in the extended basis (the merged giant step): a thread owns one
 // coefficient of one limb for MR ciphertexts, so that a key residue, read once, serves MR multiply-accumulates.
 // The 128-bit sums are folded before more than 16 products (each below 2^124) have been added.
@@ -330,6 +327,9 @@ __global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, c
     }
 }
 
+// y holds, per (item, component), the K special-limb rows y_k = INTT(u_{p_k}) * (P/p_k)^-1 in the coefficient
+// domain (the scaling comes out of the inverse transform); row (pc, k) starts at y + (pc*ystride + yoff + k)*N.
+// w_i = sum_k y_k * (P/p_k mod q_i) mod q_i for a chunk of target limbs i.
 template <u32 KMAX, bool FP>
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__restrict__ y, u64 *__restrict__ w,
                                                                   const ModConst *__restrict__ mods,
