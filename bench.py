@@ -135,6 +135,20 @@ def read_traffic(workload, n1):
     return None
 
 
+def read_valu(workload):
+    """Vector-ALU utilisation of the diagonal multiply-accumulate kernel from the committed SQ-counter summary
+    (instructions * 4 cycles / SIMDs / elapsed cycles) and the clock the kernel ran at; None for another workload."""
+    path = os.path.join(ROOT, "profiles", "bert_qkv_valu_utilisation.txt")
+    try:
+        kv = dict(l.strip().split("=", 1) for l in open(path) if "=" in l and not l.startswith("#"))
+        if kv.get("workload") == workload:
+            return {"valu_busy": float(kv["valu_busy"]), "sclk_ghz": float(kv["sclk_ghz"]),
+                    "valu_insts_per_launch": float(kv["valu_insts_per_launch"])}
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
+
+
 def cpu_baseline(W, spec, n1):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
     import oracle
@@ -606,6 +620,8 @@ def main():
                      "fp64_issue_frac": mac_ops / (mac_ms * 1e-3) / FP64_ISSUE_PEAK,
                      "frac_at_8_bytes_per_residue": mac_bytes_8 / (mac_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    if not (args.fused_qk or args.pair_compression or args.n1):
+        out["roofline"]["valu"] = read_valu(spec.name)
     ceil = measured_ceilings(B, P)
     out["measured_ceilings"] = ceil
     out["roofline"]["frac_of_measured_read"] = achieved / ceil["read_GBps"]
