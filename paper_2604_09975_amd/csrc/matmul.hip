@@ -60,12 +60,14 @@ __host__ __device__ inline u32 packed_hi(u32 k) { return (k >> 7) * 800u + 512u 
 __host__ __device__ inline u32 packed_top(u32 k) { return (k >> 7) * 800u + 768u + ((k & 127u) >> 2); }
 
 // PACKED (VEC = 2): the weight limbs are whole-limb packed records.
-template <u32 TB, u32 VEC, bool PACKED>
+// FULL: every tile of the launch has all its TB pairs (no per-pair guards: the loop body stays one basic block and the
+// loaded registers are not copied around); tiles are numbered from tile0.
+template <u32 TB, u32 VEC, bool PACKED, bool FULL>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restrict__ bank,
                                                               const u64 *__restrict__ w, u64 *__restrict__ acc,
                                                               const ModFp *__restrict__ modf, LimbIds limbs,
                                                               u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle,
-                                                              u32 gq0, u32 gq1, u32 accumulate) {
+                                                              u32 gq0, u32 gq1, u32 accumulate, u32 tile0) {
     // steps gq0 .. gq1-1 of the GQ per pair are summed; accumulate: onto what acc already holds
     static_assert(!PACKED || VEC == 2, "packed weights are read in pairs");
     typedef u64 vec_t __attribute__((ext_vector_type(VEC)));
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
         tile = slot % gridDim.x;
         run = (slot / gridDim.x) * 8 + xcd;
     }
-    const u32 bp0 = tile * TB;
+    const u32 bp0 = (tile0 + tile) * TB;
     const u32 k = (run * MM_THREADS + threadIdx.x) * VEC;
     const u32 i = limbs.id[blockIdx.z];
     const size_t limb_off = (size_t)i * N + k;
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
         xb1 = *reinterpret_cast<const vec_t *>(bank + ((size_t)gq * 2 + 1) * w_stride + limb_off);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t)
-            if (bp0 + t < BP) {
+            if (FULL || bp0 + t < BP) {
                 if (PACKED) {
                     const unsigned char *r = wbytes + (((size_t)(bp0 + t) * GQ + gq) * level + i) * rec;
                     const __amdgpu_buffer_rsrc_t rs =
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
     if (accumulate) {
 #pragma unroll
         for (u32 t = 0; t < TB; ++t)
-            if (bp0 + t < BP) {
+            if (FULL || bp0 + t < BP) {
                 const vec_t p0 = *reinterpret_cast<const vec_t *>(acc + ((size_t)(bp0 + t) * 2 + 0) * w_stride + limb_off);
                 const vec_t p1 = *reinterpret_cast<const vec_t *>(acc + ((size_t)(bp0 + t) * 2 + 1) * w_stride + limb_off);
 #pragma unroll
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
         if (gq + 1 < gq1) fetch(gq + 1);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t) {
-            if (bp0 + t < BP) {
+            if (FULL || bp0 + t < BP) {
 #pragma unroll
                 for (u32 e = 0; e < VEC; ++e) {
                     const double wv = wd[t][e];
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_kernel(const u64 *__restr
     }
 #pragma unroll
     for (u32 t = 0; t < TB; ++t) {
-        if (bp0 + t < BP) {
+        if (FULL || bp0 + t < BP) {
             vec_t o0, o1;
 #pragma unroll
             for (u32 e = 0; e < VEC; ++e) {
@@ -235,12 +237,13 @@ __global__ __launch_bounds__(EW_THREADS) void add_bias_kernel(u64 *__restrict__ 
 // PACKED: the half limb is stored in 50 bits per residue instead of 64 (packed_record_bytes) in three parts,
 // the low 32 bits, bits 32..47, and bits 48..49 four residues to a byte.  The double is rebuilt as
 // (2^52 + x) - 2^52 from the bit pattern, one addition per weight.
-template <u32 TB, bool PACKED>
+// FULL, tile0: as in diag_mac_kernel.
+template <u32 TB, bool PACKED, bool FULL>
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__restrict__ bank,
                                                                   const u64 *__restrict__ w, u64 *__restrict__ acc,
                                                                   const ModFp *__restrict__ modf, LimbIds limbs,
                                                                   u32 level, u32 N, u32 GQ, u32 BP, u32 swizzle,
-                                                                  u32 gq0, u32 gq1, u32 accumulate) {
+                                                                  u32 gq0, u32 gq1, u32 accumulate, u32 tile0) {
     // steps gq0 .. gq1-1 of the GQ per pair are summed; accumulate: onto what acc already holds
     typedef u64 vec_t __attribute__((ext_vector_type(2)));
     typedef u32 wvec_t __attribute__((ext_vector_type(4)));      // one (b,p) pair's two weights as loaded
@@ -251,7 +254,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
         tile = slot % gridDim.x;
         run = (slot / gridDim.x) * 8 + xcd;
     }
-    const u32 bp0 = tile * TB;
+    const u32 bp0 = (tile0 + tile) * TB;
     const u32 k = (run * MM_THREADS + threadIdx.x) * 2;          // k < N/2
     const u32 km = N - 2 - k;                                    // mirrors of k+1, k
     const u32 i = limbs.id[blockIdx.z];
@@ -279,7 +282,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
         }
 #pragma unroll
         for (u32 t = 0; t < TB; ++t)
-            if (bp0 + t < BP) {
+            if (FULL || bp0 + t < BP) {
                 if (PACKED) {
                     // buffer loads: the record's address is workgroup-uniform (scalar registers) and the lanes
                     // add 32-bit offsets, which keeps the 24 addresses of a step out of the vector registers
@@ -301,7 +304,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
     if (accumulate) {
 #pragma unroll
         for (u32 t = 0; t < TB; ++t)
-            if (bp0 + t < BP) {
+            if (FULL || bp0 + t < BP) {
 #pragma unroll
                 for (u32 c = 0; c < 2; ++c) {
                     const u64 *src = acc + ((size_t)(bp0 + t) * 2 + c) * w_stride + row;
@@ -342,7 +345,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
         if (gq + 1 < gq1) fetch(gq + 1);
 #pragma unroll
         for (u32 t = 0; t < TB; ++t) {
-            if (bp0 + t < BP) {
+            if (FULL || bp0 + t < BP) {
                 // weight of k serves k and N-1-k; weight of k+1 serves k+1 and N-2-k
                 const double wv[4] = {wd[t][0], wd[t][1], wd[t][1], wd[t][0]};
 #pragma unroll
@@ -366,7 +369,7 @@ __global__ __launch_bounds__(MM_THREADS) void diag_mac_sym_kernel(const u64 *__r
     }
 #pragma unroll
     for (u32 t = 0; t < TB; ++t) {
-        if (bp0 + t < BP) {
+        if (FULL || bp0 + t < BP) {
 #pragma unroll
             for (u32 c = 0; c < 2; ++c) {
                 u64 o[4];
@@ -446,6 +449,12 @@ __global__ __launch_bounds__(EW_THREADS) void fill_u32_kernel(u32 *p, u32 v, u32
     const u32 i = blockIdx.x * EW_THREADS + threadIdx.x;
     if (i < n) p[i] = v;
 }
+
+// the fp64 multiply-accumulate kernels by weight store, FULL left open
+template <bool FULL> constexpr auto sym_packed = diag_mac_sym_kernel<MM_TB, true, FULL>;
+template <bool FULL> constexpr auto sym_plain = diag_mac_sym_kernel<MM_TB, false, FULL>;
+template <bool FULL> constexpr auto gen_packed = diag_mac_kernel<MM_TB, 2, true, FULL>;
+template <bool FULL> constexpr auto gen_plain = diag_mac_kernel<MM_TB, 2, false, FULL>;
 
 __global__ __launch_bounds__(MM_THREADS) void diag_mac_int_kernel(const u64 *__restrict__ bank,
                                                                   const u64 *__restrict__ w, u64 *__restrict__ acc,
@@ -908,8 +917,8 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             const u64 *wp = w->d_w ? w->d_w + (size_t)bp_first * GQ * level * N : nullptr;
             u64 *ap = d_acc + (size_t)bp_first * ctw;
             const u32 runs = N / (4 * MM_THREADS), gen_runs = N / MM_THREADS / 2;
-            const dim3 sym_grid((bp_count + MM_TB - 1) / MM_TB, runs, n_fp);
-            const dim3 gen_grid((bp_count + MM_TB - 1) / MM_TB, gen_runs, n_fp);
+            // full tiles of MM_TB pairs go to the unguarded kernels, a ragged last tile to the guarded ones
+            const u32 full_tiles = bp_count / MM_TB, rag = bp_count % MM_TB ? 1u : 0u;
             for (u32 g0 = 0; g0 < G;) {
                 const size_t grp = (size_t)b0 * G + g0;
                 u32 g1 = g0 + 1;
@@ -918,27 +927,31 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                     ++g1;
                 const u32 q0 = g0 * N1, q1 = g1 * N1, add = g0 ? 1u : 0u;
                 // 8 (b,p) pairs x 4 coefficients per thread with the next step's loads in flight measured best
+#define MM_LAUNCH(KERNEL, RUNS, WPTR)                                                                              \
+    do {                                                                                                           \
+        if (full_tiles)                                                                                            \
+            hipLaunchKernelGGL((KERNEL<true>), dim3(full_tiles, RUNS, n_fp), dim3(MM_THREADS), 0, stream, d_bank,  \
+                               WPTR, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count, (RUNS) % 8 == 0 ? 1u : 0u,   \
+                               q0, q1, add, 0u);                                                                   \
+        if (rag)                                                                                                   \
+            hipLaunchKernelGGL((KERNEL<false>), dim3(1, RUNS, n_fp), dim3(MM_THREADS), 0, stream, d_bank, WPTR,    \
+                               ap, P->d_modf, fp_limbs, level, N, GQ, bp_count, (RUNS) % 8 == 0 ? 1u : 0u, q0, q1, \
+                               add, full_tiles);                                                                   \
+    } while (0)
                 if (w->block_packed[grp] == 1) {
                     const u64 *pp = reinterpret_cast<const u64 *>(w->d_wp + (size_t)bp_first * GQ * level *
                                                                                 packed_record_bytes(N));
-                    hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, true>), sym_grid, dim3(MM_THREADS), 0, stream,
-                                       d_bank, pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
-                                       runs % 8 == 0 ? 1u : 0u, q0, q1, add);
+                    MM_LAUNCH(sym_packed, runs, pp);
                 } else if (w->block_packed[grp] == 2) {
                     const u64 *pp = reinterpret_cast<const u64 *>(w->d_wpf + (size_t)bp_first * GQ * level * 2 *
                                                                                  packed_record_bytes(N));
-                    hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2, true>), gen_grid, dim3(MM_THREADS), 0, stream,
-                                       d_bank, pp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
-                                       gen_runs % 8 == 0 ? 1u : 0u, q0, q1, add);
+                    MM_LAUNCH(gen_packed, gen_runs, pp);
                 } else if (w->block_real[grp] && N >= 4 * MM_THREADS) {
-                    hipLaunchKernelGGL((diag_mac_sym_kernel<MM_TB, false>), sym_grid, dim3(MM_THREADS), 0, stream,
-                                       d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
-                                       runs % 8 == 0 ? 1u : 0u, q0, q1, add);
+                    MM_LAUNCH(sym_plain, runs, wp);
                 } else {   // 8 accumulators x 2 coefficients per thread (16-byte loads)
-                    hipLaunchKernelGGL((diag_mac_kernel<MM_TB, 2, false>), gen_grid, dim3(MM_THREADS), 0, stream,
-                                       d_bank, wp, ap, P->d_modf, fp_limbs, level, N, GQ, bp_count,
-                                       gen_runs % 8 == 0 ? 1u : 0u, q0, q1, add);
+                    MM_LAUNCH(gen_plain, gen_runs, wp);
                 }
+#undef MM_LAUNCH
                 g0 = g1;
             }
             b0 = b1;
