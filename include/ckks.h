@@ -137,6 +137,11 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
  * bias_coeffs[b] * bias_mul (an integer factor that lifts the bias encoding to
  * the product scale). */
 int ckks_weights_set_bias(ckks_weights_t *w, const int64_t *d_bias_coeffs, uint64_t bias_mul, void *stream);
+/* The three calls above in one: all B_out*N2*G*N1 diagonals (d_coeffs, int64 [B_out][N2][G][N1][N], device) and, if
+ * d_bias_coeffs is not NULL, the bias.  On error nothing is left allocated. */
+int ckks_weights_load(const ckks_params_t *params, uint32_t level, uint32_t m, uint32_t C, uint32_t G,
+                      uint32_t B_out, uint32_t N1, const int64_t *d_coeffs, const int64_t *d_bias_coeffs,
+                      uint64_t bias_mul, void *stream, ckks_weights_t **out);
 void ckks_weights_destroy(ckks_weights_t *w);
 
 /* Y = XW + bias on ciphertexts (Sec. 3.2):

@@ -44,6 +44,7 @@ _SIGS = {
     "ckks_weights_create": [_vp] + [C.c_uint32] * 6 + [C.POINTER(_vp)],
     "ckks_weights_set_diagonals": [_vp, C.c_uint32, C.c_uint32, _vp, _vp],
     "ckks_weights_set_bias": [_vp, _vp, C.c_uint64, _vp],
+    "ckks_weights_load": [_vp] + [C.c_uint32] * 6 + [_vp, _vp, C.c_uint64, _vp, C.POINTER(_vp)],
     "ckks_ctpt_matmul": [_vp, _vp, _vp, C.POINTER(_vp), C.POINTER(_vp), _vp, C.c_uint32, _vp, C.POINTER(Counters),
                          _vp],
     "ckks_rescale": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
@@ -231,6 +232,22 @@ def ckks_weights_set_bias(w, d_bias_coeffs, bias_mul):
     if d_bias_coeffs.numel() != w.B_out * w.N:
         raise ValueError("bias coefficients must be [B_out][N]")
     _check(lib.ckks_weights_set_bias(w.h, _dev(d_bias_coeffs), int(bias_mul), _stream()))
+
+
+def ckks_weights_load(P, level, m, Cc, G, B_out, N1, d_coeffs, d_bias_coeffs=None, bias_mul=0):
+    N2 = Cc // max(N1, 1)
+    if d_coeffs.numel() != B_out * N2 * G * N1 * P.N:
+        raise ValueError("coefficients must be [B_out][N2][G][N1][N]")
+    if d_bias_coeffs is not None and d_bias_coeffs.numel() != B_out * P.N:
+        raise ValueError("bias coefficients must be [B_out][N]")
+    h = _vp()
+    _check(lib.ckks_weights_load(P.h, level, m, Cc, G, B_out, N1, _dev(d_coeffs),
+                                 _dev(d_bias_coeffs) if d_bias_coeffs is not None else None, int(bias_mul),
+                                 _stream(), C.byref(h)))
+    w = Weights(h)
+    w.level, w.m, w.C, w.G, w.B_out, w.N1, w.N2 = level, m, Cc, G, B_out, N1, N2
+    w.N = P.N
+    return w
 
 
 MATMUL_MERGED_GIANT = 1

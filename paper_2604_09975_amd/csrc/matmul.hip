@@ -759,6 +759,31 @@ int ckks_weights_set_bias(ckks_weights_t *w, const int64_t *d_bias_coeffs, uint6
     return CKKS_OK;
 }
 
+int ckks_weights_load(const ckks_params_t *P, uint32_t level, uint32_t m, uint32_t C, uint32_t G, uint32_t B_out,
+                      uint32_t N1, const int64_t *d_coeffs, const int64_t *d_bias_coeffs, uint64_t bias_mul,
+                      void *stream, ckks_weights_t **out) {
+    if (!d_coeffs || !out) {
+        set_error("ckks_weights_load: null argument");
+        return CKKS_E_INVAL;
+    }
+    ckks_weights_t *w = nullptr;
+    int rc = ckks_weights_create(P, level, m, C, G, B_out, N1, &w);
+    if (rc) return rc;
+    const uint64_t total = (uint64_t)B_out * w->N2 * G * N1;
+    // in pieces of whole (b, p) runs, so that one call's device-side checks stay small
+    const uint32_t piece = G * N1 * std::max<uint32_t>(1u, 4096u / (G * N1));
+    for (uint64_t first = 0; first < total && rc == CKKS_OK; first += piece)
+        rc = ckks_weights_set_diagonals(w, (uint32_t)first, (uint32_t)std::min<uint64_t>(piece, total - first),
+                                        d_coeffs + first * P->N, stream);
+    if (rc == CKKS_OK && d_bias_coeffs) rc = ckks_weights_set_bias(w, d_bias_coeffs, bias_mul, stream);
+    if (rc) {
+        ckks_weights_destroy(w);
+        return rc;
+    }
+    *out = w;
+    return CKKS_OK;
+}
+
 void ckks_weights_destroy(ckks_weights_t *w) {
     if (!w) return;
     hipFree(w->d_w);

@@ -310,3 +310,37 @@ def test_conj_key_must_be_a_conjugation_key():
     with pytest.raises(B.CkksError) as e:
         B.ckks_ctpt_matmul(P, w, x, [], giant, conj_key=k1)
     assert e.value.code == -1
+
+
+def test_weights_load_in_one_call_equals_streamed_upload():
+    """ckks_weights_load = create + set_diagonals (in pieces) + set_bias: same output ciphertexts, bit for bit."""
+    B = _B()
+    O = helpers.small_oracle(10, L=3, K=1, dnum=3, qbits=40, pbits=42)
+    _, P = make_pair(O)
+    r = W.rng(77)
+    m, C, N1, level = 4, 16, 4, 3
+    X, Wm, bias = r.uniform(-1, 1, (m, 40)), r.uniform(-0.5, 0.5, (40, 20)), r.uniform(-0.5, 0.5, 20)
+    G, B_out, N2 = 3, 2, C // N1
+    sc = 2.0**30
+    cl = helpers.Client(O, 78, hamming_weight=16)
+    mx = E.encode(E.pack_columns(X, O.n, C) + 0j, sc, O.N)
+    ct_x = to_dev(np.stack([cl.encrypt_coeffs(mx[g], level) for g in range(G)]))
+    diag = to_dev(E.encode_diagonals(Wm, m, O.N, C, N1, sc).reshape(-1, O.N))
+    bias_c = to_dev(np.stack([E.encode(E.bias_slots(bias, m, O.n, C, b) + 0j, sc, O.N) for b in range(B_out)]))
+    _, baby = load_keys(P, O, cl, [q * m for q in range(1, N1)])
+    _, giant = load_keys(P, O, cl, [p * N1 * m for p in range(1, N2)])
+    w1 = B.ckks_weights_create(P, level, m, C, G, B_out, N1)
+    B.ckks_weights_set_diagonals(w1, 0, diag)
+    B.ckks_weights_set_bias(w1, bias_c, int(sc))
+    w2 = B.ckks_weights_load(P, level, m, C, G, B_out, N1, diag, bias_c, int(sc))
+    y1, _ = B.ckks_ctpt_matmul(P, w1, ct_x, baby, giant)
+    y2, _ = B.ckks_ctpt_matmul(P, w2, ct_x, baby, giant)
+    assert bool((y1 == y2).all())
+    w3 = B.ckks_weights_load(P, level, m, C, G, B_out, N1, diag)            # no bias
+    y3, _ = B.ckks_ctpt_matmul(P, w3, ct_x, baby, giant)
+    assert not bool((y3 == y1).all())
+    with pytest.raises(ValueError):
+        B.ckks_weights_load(P, level, m, C, G, B_out, N1, diag[:-1])
+    with pytest.raises(B.CkksError):
+        B.ckks_weights_load(P, level + 1, m, C, G, B_out, N1, diag)
+    assert B.lib.ckks_weights_load(P.h, level, m, C, G, B_out, N1, None, None, 0, None, None) == -1
