@@ -18,9 +18,18 @@
  *    HOST pointers.  The caller owns every buffer it passes.  Handles returned
  *    by *_create / *_load are owned by the library until the matching *_destroy.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Compute calls enqueue work on it and return without synchronising; the
- *    library's scratch memory is private to a params handle, so calls on one
- *    handle must be issued on one stream at a time.
+ *    Compute calls enqueue work on it and return without synchronising or
+ *    allocating: every table is built and the scratch arena sized by the
+ *    *_create calls (ckks_params_create for every call whose need follows from
+ *    the parameter set, ckks_weights_create for its projection) or by
+ *    ckks_params_reserve.  The *_create / *_load / *_set_* / *_reserve calls are
+ *    set-up: they may allocate and synchronise the device.
+ *  - The scratch arena and the error text belong to a params handle and to the
+ *    calling thread respectively: calls on one handle must come from one thread
+ *    at a time and be issued on one stream at a time (two calls in flight on
+ *    different streams would share the arena).
+ *  - Outputs may not overlap inputs unless a call says so; a call that would
+ *    read what it has already overwritten returns CKKS_E_INVAL instead.
  *  - Residues are uint64 in [0, q_i), little endian.  A ciphertext at level l is
  *    [component 2][limb l][N], component 0 = c0, 1 = c1, in the NTT domain:
  *    entry k of a limb is the polynomial evaluated at psi^(2*bitrev(k)+1), psi the
@@ -74,6 +83,16 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
                        uint32_t dnum, ckks_params_t **out);
 void ckks_params_destroy(ckks_params_t *params);
 
+/* Scratch arena of a params handle.  ckks_params_create sizes it for a full batch of hoisted key switches at
+ * level L (ckks_rotate_hoisted with any number of steps, ckks_ctmul, ckks_shift_bank, ckks_rot_first, the
+ * ckks_client_* calls), ckks_rescale and ckks_encode / ckks_decode; ckks_weights_create grows it to what
+ * ckks_ctpt_matmul on those weights needs.  ckks_params_reserve grows it to at least `bytes` (set-up call:
+ * synchronises the device; CKKS_E_NOMEM if the device refuses).  Should a compute call ever need more than
+ * is reserved it grows the arena itself after draining its stream -- except on a capturing stream, where it
+ * returns CKKS_E_NOMEM and the caller reserves first.  ckks_params_scratch_bytes reports the current size. */
+int ckks_params_reserve(ckks_params_t *params, uint64_t bytes);
+int ckks_params_scratch_bytes(const ckks_params_t *params, uint64_t *bytes);
+
 /* psi of limb `limb` (host out): the root that fixes the NTT-domain bits. */
 int ckks_params_root(const ckks_params_t *params, uint32_t limb, uint64_t *psi);
 
@@ -92,10 +111,17 @@ int ckks_galois_elt(const ckks_params_t *params, int32_t step, uint64_t *galois_
 
 /* Evaluation key for one Galois element (the "Galois keys" of Sec. 2.1).
  * d_key: [dnum][2][L+K][N], NTT domain, canonical residues; component 0 = b_j,
- * 1 = a_j with b_j = -a_j*s + e_j + P*T_j*sigma_g(s).  The library keeps its own
- * copy (Montgomery form); d_key may be freed once `stream` has drained. */
+ * 1 = a_j with b_j = -a_j*s + e_j + P*T_j*sigma_g(s).  ckks_galois_key_load COPIES:
+ * the library keeps its own copy in its internal (Montgomery) form, 96 MiB at
+ * N = 2^16 with 24 + 8 primes, and d_key may be freed once `stream` has drained.
+ * ckks_galois_key_adopt BORROWS: d_key is rewritten in place into the internal
+ * form (it is no longer a canonical key afterwards) and the handle points at it; the
+ * caller keeps ownership and must keep the buffer alive and untouched until the
+ * handle is destroyed.  No second copy of the key exists on that path. */
 int ckks_galois_key_load(const ckks_params_t *params, uint64_t galois_elt, const uint64_t *d_key,
                          void *stream, ckks_gkey_t **out);
+int ckks_galois_key_adopt(const ckks_params_t *params, uint64_t galois_elt, uint64_t *d_key, void *stream,
+                          ckks_gkey_t **out);
 void ckks_galois_key_destroy(ckks_gkey_t *key);
 
 /* Relinearisation key (Sec. 2.1 "relinearization keys"): same layout as a Galois key, with
@@ -115,8 +141,9 @@ int ckks_ctmul(ckks_params_t *params, const uint64_t *d_ct_a, const uint64_t *d_
  * ModDown, + sigma(c0).  d_ct_in [2][level][N]; steps (host) as in
  * ckks_galois_elt; keys (host array of n_steps handles, in step order; an entry
  * may be NULL only if its step is the identity, which is copied); d_ct_out
- * [n_steps][2][level][N].  Errors: CKKS_E_LEVEL (level 0 or > L), CKKS_E_NOKEY,
- * CKKS_E_INVAL (key of another element, K = 0). */
+ * [n_steps][2][level][N], which may not overlap d_ct_in (the switches gather
+ * from the input while outputs are written).  Errors: CKKS_E_LEVEL (level 0 or
+ * > L), CKKS_E_NOKEY, CKKS_E_INVAL (key of another element, K = 0, overlap). */
 int ckks_rotate_hoisted(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level, const int32_t *steps,
                         uint32_t n_steps, const ckks_gkey_t *const *keys, uint64_t *d_ct_out, void *stream);
 
@@ -164,8 +191,11 @@ void ckks_weights_destroy(ckks_weights_t *w);
  * d_ct_x [G][2][level][N]; baby_keys: N1-1 handles for steps q*m (q = 1..);
  * giant_keys: N2-1 handles for steps p*N1*m; conj_key: NULL or the key of
  * CKKS_STEP_CONJ; d_ct_y [B_out][2][level][N] at the
- * input level and scale(x)*scale(w) -- follow with ckks_rescale.  counters
- * (host, may be NULL) receives the operation counts. */
+ * input level and scale(x)*scale(w) -- follow with ckks_rescale; may not overlap
+ * d_ct_x.  counters (host, may be NULL) receives the operation counts.
+ * CKKS_E_INVAL also for flags with unknown bits and for weights of which some
+ * diagonal was never stored (the message names the first one): nothing is
+ * enqueued then. */
 #define CKKS_MATMUL_MERGED_GIANT 1u /* flags: one ModDown per output block for the whole giant step */
 int ckks_ctpt_matmul(ckks_params_t *params, const ckks_weights_t *w, const uint64_t *d_ct_x,
                      const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys,
@@ -221,16 +251,10 @@ int ckks_rot_first(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t leve
 
 /* rescale (Sec. 2.2): drops limb level_in-1 and divides by its prime with
  * centred rounding.  d_ct_in [n_ct][2][level_in][N] -> d_ct_out
- * [n_ct][2][level_in-1][N].  CKKS_E_LEVEL if level_in < 2 or > L. */
+ * [n_ct][2][level_in-1][N], which may not overlap d_ct_in (CKKS_E_INVAL).
+ * CKKS_E_LEVEL if level_in < 2 or > L. */
 int ckks_rescale(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct,
                  uint64_t *d_ct_out, void *stream);
-
-/* Timing of the diagonal multiply-accumulate kernel inside ckks_ctpt_matmul (the kernel that streams
- * the weights, i.e. the path's byte mover): between begin and end every launch is bracketed by HIP
- * events on the call's stream.  end synchronises `stream` and returns the summed kernel time in ms
- * and the number of launches. */
-int ckks_profile_begin(ckks_params_t *params);
-int ckks_profile_end(ckks_params_t *params, void *stream, double *total_ms, uint32_t *launches);
 
 /* ---- key holder's side (the client of Sec. 2.3: KeyGen, Enc, Dec) ----------
  * Randomness is drawn by the caller and passed in, so results are reproducible
@@ -285,26 +309,6 @@ int ckks_encode(ckks_params_t *params, const double *d_slots, uint32_t count, do
  * m(zeta^(5^j)) / scale. */
 int ckks_decode(ckks_params_t *params, const uint64_t *d_res, uint32_t nlimbs, uint32_t count, double scale,
                 double *d_slots, void *stream);
-
-/* ---- measured ceilings of the machine (what roofline fractions are also reported against) ----
- * Plain streaming kernels and chains of the two modular products the kernels are built from; the caller times
- * them with events on `stream`. */
-
-#define CKKS_PROBE_COPY 0u  /* d_dst[i] = d_src[i]: n_words read and n_words written */
-#define CKKS_PROBE_READ 1u  /* n_words of d_src read, at most one word of d_dst written */
-#define CKKS_PROBE_WRITE 2u /* n_words of d_dst written (d_src unused) */
-int ckks_probe_stream(uint64_t *d_dst, const uint64_t *d_src, uint64_t n_words /* even */, uint32_t mode,
-                      void *stream);
-
-#define CKKS_PROBE_INT64 0u /* 64-bit Montgomery product (any prime of the chain) */
-#define CKKS_PROBE_FP64 1u  /* exact product in doubles (primes below 2^50) */
-/* Every one of n_threads lanes (a multiple of 256) runs four independent chains of `iters` dependent products
- * x <- x * psi mod q, q = prime `limb` (ciphertext primes first, then special), psi its 2N-th root
- * (ckks_params_root), chain c of lane t starting from (4t + c + 1) mod 2^20; d_out[t] (device, n_threads words) is
- * the XOR of the four canonical results, so the caller can check the arithmetic it timed:
- * 4 * n_threads * iters products per launch. */
-int ckks_probe_mulmod(const ckks_params_t *params, uint32_t limb, uint32_t kind, uint32_t n_threads, uint32_t iters,
-                      uint64_t *d_out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -36,10 +36,13 @@ _SIGS = {
     "ckks_find_primes": [C.c_uint32, C.c_uint32, C.c_uint32, _u64p],
     "ckks_params_create": [C.c_uint32, _u64p, C.c_uint32, _u64p, C.c_uint32, C.c_uint32, C.POINTER(_vp)],
     "ckks_params_root": [_vp, C.c_uint32, _u64p],
+    "ckks_params_reserve": [_vp, C.c_uint64],
+    "ckks_params_scratch_bytes": [_vp, _u64p],
     "ckks_ntt": [_vp, _vp, _u32p, C.c_uint32, C.c_uint32, _vp],
     "ckks_intt": [_vp, _vp, _u32p, C.c_uint32, C.c_uint32, _vp],
     "ckks_galois_elt": [_vp, C.c_int32, _u64p],
     "ckks_galois_key_load": [_vp, C.c_uint64, _vp, _vp, C.POINTER(_vp)],
+    "ckks_galois_key_adopt": [_vp, C.c_uint64, _vp, _vp, C.POINTER(_vp)],
     "ckks_rotate_hoisted": [_vp, _vp, C.c_uint32, _i32p, C.c_uint32, C.POINTER(_vp), _vp, _vp],
     "ckks_weights_create": [_vp] + [C.c_uint32] * 6 + [C.POINTER(_vp)],
     "ckks_weights_set_diagonals": [_vp, C.c_uint32, C.c_uint32, _vp, _vp],
@@ -134,6 +137,16 @@ def ckks_params_create(logN, q, p, dnum):
     return P
 
 
+def ckks_params_reserve(P, nbytes):
+    _check(lib.ckks_params_reserve(P.h, int(nbytes)))
+
+
+def ckks_params_scratch_bytes(P):
+    out = C.c_uint64()
+    _check(lib.ckks_params_scratch_bytes(P.h, C.byref(out)))
+    return int(out.value)
+
+
 def ckks_params_root(P, limb):
     out = C.c_uint64()
     _check(lib.ckks_params_root(P.h, limb, C.byref(out)))
@@ -169,6 +182,18 @@ def ckks_galois_key_load(P, galois_elt, d_key):
     _check(lib.ckks_galois_key_load(P.h, galois_elt, _dev(d_key), _stream(), C.byref(h)))
     k = GaloisKey(h)
     k.galois_elt = galois_elt
+    return k
+
+
+def ckks_galois_key_adopt(P, galois_elt, d_key):
+    """Borrowing form: d_key is rewritten in place and must stay alive (the handle keeps a reference to it)."""
+    if d_key.numel() != P.dnum * 2 * (P.L + P.K) * P.N:
+        raise ValueError("key tensor must be [dnum][2][L+K][N]")
+    h = _vp()
+    _check(lib.ckks_galois_key_adopt(P.h, galois_elt, _dev(d_key), _stream(), C.byref(h)))
+    k = GaloisKey(h)
+    k.galois_elt = galois_elt
+    k.buffer = d_key
     return k
 
 

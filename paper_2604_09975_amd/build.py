@@ -19,7 +19,7 @@ def _stale(out, deps):
 def build(force=False, verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    headers.append(os.path.join(os.path.dirname(HERE), "include", "ckks.h"))
+    headers += [os.path.join(os.path.dirname(HERE), "include", h) for h in ("ckks.h", "ckks_measure.h")]
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     objs, procs = [], []

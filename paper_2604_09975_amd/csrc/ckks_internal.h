@@ -6,7 +6,7 @@
 #include <string>
 #include <vector>
 
-#include "../../include/ckks.h"
+#include "../../include/ckks_measure.h"   // includes ckks.h
 #include "modarith.h"
 
 namespace ckks {
@@ -29,6 +29,12 @@ struct ModFp {
     double ninv, ninv_w;   // N^-1 and N^-1 * psi^-(N/2) as plain integers
     u32 ok, pad;           // 1 if q < 2^50 (the FMA butterflies apply)
 };
+
+// Half-open device ranges [a, a + na) and [b, b + nb) of 64-bit words share a word.
+inline bool words_overlap(const void *a, size_t na, const void *b, size_t nb) {
+    const uintptr_t a0 = (uintptr_t)a, a1 = a0 + na * sizeof(u64), b0 = (uintptr_t)b, b1 = b0 + nb * sizeof(u64);
+    return na && nb && a0 < b1 && b0 < a1;
+}
 
 void set_error(const char *fmt, ...);
 int hip_fail(hipError_t e, const char *what);
@@ -93,13 +99,15 @@ struct ckks_params {
     mutable uint64_t limb_ntts = 0;    // limb transforms launched so far (for the operation counters)
 
     int ensure_scratch(size_t bytes, hipStream_t stream);
-    int level_tables(ckks::u32 level, const ckks::LevelTables **out);
+    int level_tables(ckks::u32 level, const ckks::LevelTables **out) const;
+    int build_level_tables(ckks::u32 level);
 };
 
 struct ckks_gkey {
     const ckks_params *params = nullptr;
     ckks::u64 galois_elt = 0;
     ckks::u64 *d_key = nullptr;        // [dnum][2][L+K][N], Montgomery form
+    bool owned = true;                 // false: the caller's buffer, converted in place (ckks_galois_key_adopt)
 };
 
 struct ckks_weights {
@@ -119,6 +127,7 @@ struct ckks_weights {
     // and where the group's diagonals live: 0 = d_w, 1 = half records in d_wp (real), 2 = whole-limb records in d_wpf
     std::vector<uint8_t> block_real;
     std::vector<uint8_t> block_packed;
+    std::vector<uint8_t> loaded;       // per diagonal: ckks_weights_set_diagonals has stored it
     ckks::u32 *d_flag = nullptr;       // per-diagonal check results of the chunk being loaded
     ckks::u32 flag_cap = 0;
 };
@@ -169,6 +178,7 @@ int rotate_hoisted(ckks_params *p, const u64 *d_ct_in, u32 level, const int32_t 
                    const ckks_gkey *const *keys, u64 *d_ct_out, size_t reserve_words, hipStream_t stream);
 
 // matmul.hip
+size_t matmul_scratch_words(const ckks_params *p, const ckks_weights *w, bool merged);
 // int64 coefficients [count][N] -> NTT-domain residues [count][level][N]; weight_form: doubles / Montgomery per limb
 int expand_plain(const ckks_params *p, u32 level, const int64_t *d_coeffs, u32 count, u64 *d_out, bool weight_form,
                  hipStream_t stream);

@@ -112,6 +112,10 @@ static int shift_bank(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level,
             return CKKS_E_INVAL;
         }
     }
+    if (words_overlap(d_ct_in, ctw, d_ct_out, (size_t)n_out * ctw)) {
+        set_error("ckks_shift_bank: d_ct_out overlaps d_ct_in");
+        return CKKS_E_INVAL;
+    }
     // scratch: rotated copies of one chunk of outputs, then the hoisted digits and the switch workspace
     const u32 chunk_out = ROT_BATCH / 2;
     const size_t rot_w = (size_t)ROT_BATCH * ctw, dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
@@ -210,6 +214,10 @@ int ckks_mod_switch_to_next(const ckks_params_t *P, const uint64_t *d_ct_in, uin
     }
     int rc = check_level(P, level_in, 2, "ckks_mod_switch_to_next");
     if (rc || n_ct == 0) return rc;
+    if (words_overlap(d_ct_in, (size_t)n_ct * 2 * level_in * P->N, d_ct_out, (size_t)n_ct * 2 * (level_in - 1) * P->N)) {
+        set_error("ckks_mod_switch_to_next: d_ct_out overlaps d_ct_in");
+        return CKKS_E_INVAL;
+    }
     if (2 * n_ct > 65535) {
         set_error("ckks_mod_switch_to_next: %u ciphertexts exceed one launch", n_ct);
         return CKKS_E_INVAL;

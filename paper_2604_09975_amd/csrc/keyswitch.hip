@@ -833,6 +833,10 @@ int rotate_hoisted(ckks_params *P, const u64 *d_ct_in, u32 level, const int32_t 
     }
     const u32 N = P->N;
     const size_t ctw = (size_t)2 * level * N;
+    if (words_overlap(d_ct_in, ctw, d_ct_out, (size_t)n_steps * ctw)) {   // the switches gather from the input
+        set_error("ckks_rotate_hoisted: d_ct_out overlaps d_ct_in");
+        return CKKS_E_INVAL;
+    }
     std::vector<SwitchItem> items;
     std::vector<u32> copies;
     for (u32 r = 0; r < n_steps; ++r) {
@@ -933,6 +937,35 @@ int ckks_galois_key_load(const ckks_params_t *P, uint64_t galois_elt, const uint
     return CKKS_OK;
 }
 
+int ckks_galois_key_adopt(const ckks_params_t *P, uint64_t galois_elt, uint64_t *d_key, void *stream,
+                          ckks_gkey_t **out) {
+    if (!out) {
+        set_error("ckks_galois_key_adopt: out is null");
+        return CKKS_E_INVAL;
+    }
+    *out = nullptr;
+    if (!P || !d_key || P->K == 0) {
+        set_error("ckks_galois_key_adopt: null argument or no special primes");
+        return CKKS_E_INVAL;
+    }
+    if (!(galois_elt & 1) || galois_elt >= 2ull * P->N || galois_elt == 1) {
+        set_error("ckks_galois_key_adopt: %llu is not a non-trivial Galois element", (unsigned long long)galois_elt);
+        return CKKS_E_INVAL;
+    }
+    const size_t rows = (size_t)P->dnum * 2 * P->W;
+    // elementwise, each thread reads and writes its own word: in place is safe
+    hipLaunchKernelGGL(to_mont_kernel, dim3(P->N / KS_THREADS, (u32)rows), dim3(KS_THREADS), 0, (hipStream_t)stream,
+                       d_key, d_key, P->d_mod, P->W, P->N);
+    CKKS_LAUNCH_CHECK("to_mont_kernel");
+    ckks_gkey *k = new ckks_gkey();
+    k->params = P;
+    k->galois_elt = galois_elt;
+    k->d_key = d_key;
+    k->owned = false;
+    *out = k;
+    return CKKS_OK;
+}
+
 int ckks_relin_key_load(const ckks_params_t *P, const uint64_t *d_key, void *stream, ckks_gkey_t **out) {
     if (!out) {
         set_error("ckks_relin_key_load: out is null");
@@ -984,6 +1017,11 @@ int ckks_ctmul(ckks_params_t *P, const uint64_t *d_ct_a, const uint64_t *d_ct_b,
         return CKKS_E_INVAL;
     }
     const u32 N = P->N;
+    if (words_overlap(d_ct_out, (size_t)2 * level * N, d_ct_a, (size_t)2 * level * N) ||
+        words_overlap(d_ct_out, (size_t)2 * level * N, d_ct_b, (size_t)2 * level * N)) {
+        set_error("ckks_ctmul: d_ct_out overlaps an input");
+        return CKKS_E_INVAL;
+    }
     const size_t dig_w = digits_words(P, level), lim_w = (size_t)level * N;
     int rc = P->ensure_scratch((dig_w + 2 * lim_w + switch_scratch_words(P, level, 1)) * sizeof(u64), stream);
     if (rc) return rc;
@@ -1007,7 +1045,7 @@ int ckks_ctmul(ckks_params_t *P, const uint64_t *d_ct_a, const uint64_t *d_ct_b,
 
 void ckks_galois_key_destroy(ckks_gkey_t *key) {
     if (!key) return;
-    hipFree(key->d_key);
+    if (key->owned) hipFree(key->d_key);
     delete key;
 }
 

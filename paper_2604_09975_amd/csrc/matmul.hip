@@ -557,6 +557,37 @@ __global__ __launch_bounds__(EW_THREADS) void take_last_limb_kernel(const u64 *_
     r[(size_t)pc * N + n] = in[((size_t)pc * level + level - 1) * N + n];
 }
 
+// Arena layout of one ckks_ctpt_matmul call, in words: [key-switch scratch | bank | accumulators | merged sums |
+// merged digits].
+struct MatmulLayout {
+    u32 in_chunk, batch, mg_rots;
+    size_t dig_w, tmp_w, ks_w, bank_w, acc_w, u_w, mg_w;
+    size_t total() const { return ks_w + bank_w + acc_w + u_w + mg_w; }
+};
+
+static MatmulLayout matmul_layout(const ckks_params *P, const ckks_weights *w, bool merged) {
+    MatmulLayout l;
+    const u32 N = P->N, level = w->level, G = w->G, B = w->B_out, N2 = w->N2;
+    const size_t ctw = (size_t)2 * level * N;
+    merged = merged && N2 > 1;
+    l.in_chunk = std::min<u32>(ROT_BATCH, G);                    // inputs decomposed together
+    l.batch = std::min<u32>(ROT_BATCH, std::max(l.in_chunk, B));
+    l.dig_w = digits_words(P, level);
+    l.tmp_w = (size_t)level * N;
+    l.ks_w = l.batch * (l.dig_w + l.tmp_w) + switch_scratch_words(P, level, ROT_BATCH);
+    l.bank_w = (size_t)G * w->N1 * ctw;
+    l.acc_w = (size_t)B * N2 * ctw;
+    l.u_w = merged ? (size_t)B * 2 * (level + P->K) * N : 0;    // extended-basis sums of the giant step
+    // merged giant step: the digits of up to MERGE_GROUP rotations of one batch of blocks are held together
+    l.mg_rots = merged ? std::min<u32>(MERGE_GROUP, N2 - 1) : 0;
+    l.mg_w = (size_t)l.mg_rots * std::min(l.batch, B) * l.dig_w;
+    return l;
+}
+
+size_t matmul_scratch_words(const ckks_params *P, const ckks_weights *w, bool merged) {
+    return matmul_layout(P, w, merged).total();
+}
+
 int expand_plain(const ckks_params *P, u32 level, const int64_t *d_coeffs, u32 count, u64 *d_out, bool mont,
                         hipStream_t stream) {
     const u32 N = P->N;
@@ -618,9 +649,20 @@ int ckks_weights_create(const ckks_params_t *P, uint32_t level, uint32_t m, uint
     w->N2 = C / N1;
     w->block_real.assign((size_t)B_out * G, 1);
     w->block_packed.assign((size_t)B_out * G, 0);
+    w->loaded.assign((size_t)B_out * w->N2 * G * N1, 0);
     w->packable = P->N >= 4 * MM_THREADS;
     for (u32 i = 0; i < level; ++i)
         if (P->mod[i] >> 50) w->packable = false;
+    // the projection's scratch (bank, accumulators, key-switch workspace) is sized here, in either giant-step
+    // order, so that ckks_ctpt_matmul itself neither allocates nor synchronises
+    ckks_params *Pm = const_cast<ckks_params *>(P);
+    CKKS_HIP(hipDeviceSynchronize());
+    int rc = Pm->ensure_scratch(std::max(matmul_scratch_words(P, w, false), matmul_scratch_words(P, w, true)) *
+                                    sizeof(u64), nullptr);
+    if (rc) {
+        delete w;
+        return rc;
+    }
     *out = w;
     return CKKS_OK;
 }
@@ -738,6 +780,7 @@ int ckks_weights_set_diagonals(ckks_weights_t *w, uint32_t first, uint32_t count
                                   w->d_w + (size_t)lo * level * N, true, (hipStream_t)stream);
                 if (rc) return rc;
             }
+            std::fill(w->loaded.begin() + lo, w->loaded.begin() + hi, (uint8_t)1);
             lo = hi;
         }
     }
@@ -840,21 +883,30 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         set_error("ckks_ctpt_matmul: conj_key is not a key for conjugation");
         return CKKS_E_INVAL;
     }
+    if (flags & ~(uint32_t)CKKS_MATMUL_MERGED_GIANT) {
+        set_error("ckks_ctpt_matmul: unknown flags 0x%x", flags);
+        return CKKS_E_INVAL;
+    }
+    for (size_t d = 0; d < w->loaded.size(); ++d)
+        if (!w->loaded[d]) {
+            set_error("ckks_ctpt_matmul: diagonal %zu of %zu was never loaded (ckks_weights_set_diagonals)", d,
+                      w->loaded.size());
+            return CKKS_E_INVAL;
+        }
     const uint64_t ntt0 = P->limb_ntts;
     const size_t ctw = (size_t)2 * level * N;
+    if (words_overlap(d_ct_x, (size_t)G * ctw, d_ct_y, (size_t)B * ctw)) {
+        set_error("ckks_ctpt_matmul: d_ct_y overlaps d_ct_x");
+        return CKKS_E_INVAL;
+    }
     const u32 BP = B * N2, GQ = G * N1;
     // persistent buffers of this call live behind the key-switch scratch
-    const u32 in_chunk = std::min<u32>(ROT_BATCH, G);            // inputs decomposed together
-    const u32 batch = std::min<u32>(ROT_BATCH, std::max(in_chunk, B));
-    const size_t dig_w = digits_words(P, level), tmp_w = (size_t)level * N;
-    const size_t ks_w = batch * (dig_w + tmp_w) + switch_scratch_words(P, level, ROT_BATCH);
-    const size_t bank_w = (size_t)GQ * ctw, acc_w = (size_t)BP * ctw;
     const bool merged = (flags & CKKS_MATMUL_MERGED_GIANT) && N2 > 1;
-    const size_t u_w = merged ? (size_t)B * 2 * (level + P->K) * N : 0;   // extended-basis sums of the giant step
-    // merged giant step: the digits of up to MERGE_GROUP rotations of one batch of blocks are held together
-    const u32 mg_rots = merged ? std::min<u32>(MERGE_GROUP, N2 - 1) : 0;
-    const size_t mg_w = (size_t)mg_rots * std::min(batch, B) * dig_w;
-    int rc = P->ensure_scratch((ks_w + bank_w + acc_w + u_w + mg_w) * sizeof(u64), stream);
+    const MatmulLayout lay = matmul_layout(P, w, merged);
+    const u32 in_chunk = lay.in_chunk, batch = lay.batch, mg_rots = lay.mg_rots;
+    const size_t dig_w = lay.dig_w, tmp_w = lay.tmp_w, ks_w = lay.ks_w, bank_w = lay.bank_w, acc_w = lay.acc_w,
+                 u_w = lay.u_w;
+    int rc = P->ensure_scratch(lay.total() * sizeof(u64), stream);   // reserved by ckks_weights_create: no-op
     if (rc) return rc;
     u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + batch * tmp_w;
     u64 *d_bank = (u64 *)P->d_scratch + ks_w, *d_acc = d_bank + bank_w;
@@ -1122,6 +1174,40 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     return CKKS_OK;
 }
 
+}  // extern "C"
+
+namespace ckks {
+
+constexpr u32 RESCALE_CHUNK = 64;
+
+// rescale of `rows` polynomials (rows = 2 x ciphertexts): d_in [rows][level][N] -> d_out [rows][level-1][N];
+// d_r: rows*N words of scratch (the last limbs in the coefficient domain)
+static int rescale_rows(ckks_params *P, const u64 *d_in, u32 level, u32 rows, u64 *d_out, u64 *d_r,
+                        hipStream_t stream) {
+    const u32 N = P->N;
+    hipLaunchKernelGGL(take_last_limb_kernel, dim3(N / EW_THREADS, rows), dim3(EW_THREADS), 0, stream, d_in, d_r,
+                       level, N);
+    CKKS_LAUNCH_CHECK("take_last_limb_kernel");
+    LimbIds ids;
+    ids.id[0] = (uint8_t)(level - 1);
+    int rc = launch_ntt(P, d_r, ids, 1, rows, true, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(rescale_delta_kernel, dim3(N / EW_THREADS, rows), dim3(EW_THREADS), 0, stream, d_r, d_out,
+                       P->d_mod, level, N);
+    CKKS_LAUNCH_CHECK("rescale_delta_kernel");
+    for (u32 i = 0; i + 1 < level; ++i) ids.id[i] = (uint8_t)i;
+    rc = launch_ntt(P, d_out, ids, level - 1, rows * (level - 1), false, stream);
+    if (rc) return rc;
+    hipLaunchKernelGGL(rescale_final_kernel, dim3(N / EW_THREADS, level - 1, rows), dim3(EW_THREADS), 0, stream, d_in,
+                       d_out, P->d_mod, P->d_qlinv + (size_t)(level - 1) * P->L, level, N);
+    CKKS_LAUNCH_CHECK("rescale_final_kernel");
+    return CKKS_OK;
+}
+
+}  // namespace ckks
+
+extern "C" {
+
 int ckks_profile_begin(ckks_params_t *P) {
     if (!P) {
         set_error("ckks_profile_begin: params is null");
@@ -1163,30 +1249,21 @@ int ckks_rescale(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level_in, u
         return CKKS_E_LEVEL;
     }
     if (n_ct == 0) return CKKS_OK;
-    const u32 N = P->N, level = level_in, rows = 2 * n_ct;
-    if (rows * (level - 1) > 65535) {
-        set_error("ckks_rescale: %u ciphertexts exceed one launch", n_ct);
+    const u32 N = P->N, level = level_in;
+    if (words_overlap(d_ct_in, (size_t)n_ct * 2 * level * N, d_ct_out, (size_t)n_ct * 2 * (level - 1) * N)) {
+        set_error("ckks_rescale: d_ct_out overlaps d_ct_in");
         return CKKS_E_INVAL;
     }
-    int rc = P->ensure_scratch((size_t)rows * N * sizeof(u64), stream);
+    // in slices of RESCALE_CHUNK ciphertexts: the scratch need (one limb polynomial per component) stays within what
+    // ckks_params_create reserved
+    int rc = P->ensure_scratch((size_t)2 * std::min(n_ct, RESCALE_CHUNK) * N * sizeof(u64), stream);
     if (rc) return rc;
-    u64 *d_r = (u64 *)P->d_scratch;
-    hipLaunchKernelGGL(take_last_limb_kernel, dim3(N / EW_THREADS, rows), dim3(EW_THREADS), 0, stream, d_ct_in, d_r,
-                       level, N);
-    CKKS_LAUNCH_CHECK("take_last_limb_kernel");
-    LimbIds ids;
-    ids.id[0] = (uint8_t)(level - 1);
-    rc = launch_ntt(P, d_r, ids, 1, rows, true, stream);
-    if (rc) return rc;
-    hipLaunchKernelGGL(rescale_delta_kernel, dim3(N / EW_THREADS, rows), dim3(EW_THREADS), 0, stream, d_r, d_ct_out,
-                       P->d_mod, level, N);
-    CKKS_LAUNCH_CHECK("rescale_delta_kernel");
-    for (u32 i = 0; i + 1 < level; ++i) ids.id[i] = (uint8_t)i;
-    rc = launch_ntt(P, d_ct_out, ids, level - 1, rows * (level - 1), false, stream);
-    if (rc) return rc;
-    hipLaunchKernelGGL(rescale_final_kernel, dim3(N / EW_THREADS, level - 1, rows), dim3(EW_THREADS), 0, stream,
-                       d_ct_in, d_ct_out, P->d_mod, P->d_qlinv + (size_t)(level - 1) * P->L, level, N);
-    CKKS_LAUNCH_CHECK("rescale_final_kernel");
+    for (u32 done = 0; done < n_ct; done += RESCALE_CHUNK) {
+        const u32 c = std::min(RESCALE_CHUNK, n_ct - done);
+        rc = rescale_rows(P, d_ct_in + (size_t)done * 2 * level * N, level, 2 * c,
+                          d_ct_out + (size_t)done * 2 * (level - 1) * N, (u64 *)P->d_scratch, stream);
+        if (rc) return rc;
+    }
     return CKKS_OK;
 }
 

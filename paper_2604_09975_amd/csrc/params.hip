@@ -119,8 +119,19 @@ static int upload(T **dst, const std::vector<T> &src) {
 
 using namespace ckks;
 
+// Grows the arena.  Every compute call's need at the sizes the *_create calls know about is reserved there
+// (reserve_default, ckks_weights_create) or by ckks_params_reserve, so on the usual path this returns at its first
+// line; a larger need is the documented exception: the stream is drained and the arena reallocated, which a
+// capturing stream cannot do (the call then fails cleanly and asks for a reservation).
 int ckks_params::ensure_scratch(size_t bytes, hipStream_t stream) {
     if (bytes <= scratch_bytes) return CKKS_OK;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess) (void)hipGetLastError();
+    if (cap != hipStreamCaptureStatusNone) {
+        set_error("scratch arena of %zu bytes is too small for this call (%zu bytes) and the stream is capturing: "
+                  "call ckks_params_reserve first", scratch_bytes, bytes);
+        return CKKS_E_NOMEM;
+    }
     if (d_scratch) {
         CKKS_HIP(hipStreamSynchronize(stream));
         CKKS_HIP(hipFree(d_scratch));
@@ -132,12 +143,18 @@ int ckks_params::ensure_scratch(size_t bytes, hipStream_t stream) {
     return CKKS_OK;
 }
 
-int ckks_params::level_tables(u32 level, const LevelTables **out) {
+// Conversion tables of every level are built by ckks_params_create; compute calls only look them up.
+int ckks_params::level_tables(u32 level, const LevelTables **out) const {
     auto it = levels.find(level);
-    if (it != levels.end()) {
-        *out = &it->second;
-        return CKKS_OK;
+    if (it == levels.end()) {
+        set_error("no conversion tables for level %u", level);
+        return CKKS_E_LEVEL;
     }
+    *out = &it->second;
+    return CKKS_OK;
+}
+
+int ckks_params::build_level_tables(u32 level) {
     LevelTables t;
     t.level = level;
     t.beta = (level + alpha - 1) / alpha;
@@ -160,15 +177,12 @@ int ckks_params::level_tables(u32 level, const LevelTables **out) {
             std::memcpy(&matf[(size_t)i * Wl + t2], &fd, sizeof fd);
         }
     }
-    int rc = upload(&t.d_up_inv, inv);
-    if (rc) return rc;
-    rc = upload(&t.d_up_mat, mat);
-    if (rc) return rc;
-    rc = upload(&t.d_up_matf, matf);
-    if (rc) return rc;
-    auto ins = levels.emplace(level, t);
-    *out = &ins.first->second;
-    return CKKS_OK;
+    // entered into the map first, so that ckks_params_destroy frees whatever part was uploaded if a later part fails
+    LevelTables &slot = levels.emplace(level, t).first->second;
+    int rc = upload(&slot.d_up_inv, inv);
+    if (!rc) rc = upload(&slot.d_up_mat, mat);
+    if (!rc) rc = upload(&slot.d_up_matf, matf);
+    return rc;
 }
 
 extern "C" {
@@ -356,11 +370,40 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     if (!rc) rc = upload(&P->d_dn_matf, dn_matf);
     if (!rc) rc = upload(&P->d_pinv, pinv);
     if (!rc) rc = upload(&P->d_qlinv, qlinv);
+    for (u32 level = 1; !rc && level <= L && K; ++level) rc = P->build_level_tables(level);
+    // scratch for every call whose need is known from the parameter set alone: a full batch of hoisted key switches
+    // at the top level (ckks_rotate_hoisted with any number of steps, ckks_ctmul, ckks_rot_first, the key holder's
+    // calls), ckks_rescale of up to 64 ciphertexts, ckks_encode / ckks_decode
+    if (!rc) {
+        size_t words = (size_t)128 * N + 4 * (size_t)W * N;                   // rescale; encode: 64 complex vectors
+        words = std::max(words, (size_t)64 * 2 * N);
+        words = std::max(words, (size_t)dnum * W * N + W);                    // key generation
+        if (K) words = std::max(words, (size_t)ROT_BATCH * 2 * L * N + rotate_hoisted_scratch_words(P, L, ROT_BATCH));   // ckks_shift_bank
+        rc = P->ensure_scratch(words * sizeof(u64), nullptr);
+    }
     if (rc) {
         ckks_params_destroy(P);
         return rc;
     }
     *out = P;
+    return CKKS_OK;
+}
+
+int ckks_params_reserve(ckks_params_t *P, uint64_t bytes) {
+    if (!P) {
+        set_error("ckks_params_reserve: params is null");
+        return CKKS_E_INVAL;
+    }
+    CKKS_HIP(hipDeviceSynchronize());
+    return P->ensure_scratch((size_t)bytes, nullptr);
+}
+
+int ckks_params_scratch_bytes(const ckks_params_t *P, uint64_t *bytes) {
+    if (!P || !bytes) {
+        set_error("ckks_params_scratch_bytes: null argument");
+        return CKKS_E_INVAL;
+    }
+    *bytes = P->scratch_bytes;
     return CKKS_OK;
 }
 

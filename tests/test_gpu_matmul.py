@@ -344,3 +344,81 @@ def test_weights_load_in_one_call_equals_streamed_upload():
     with pytest.raises(B.CkksError):
         B.ckks_weights_load(P, level + 1, m, C, G, B_out, N1, diag)
     assert B.lib.ckks_weights_load(P.h, level, m, C, G, B_out, N1, None, None, 0, None, None) == -1
+
+
+@pytest.mark.parametrize("N1,merged", [(4, False), (8, True)])
+def test_ring_2_13_xcd_unfolded_tile_order(N1, merged):
+    """N = 2^13 is the smallest ring whose coefficient runs divide over the 8 XCDs, which switches the
+    multiply-accumulate kernels to their unfolded workgroup order (the one every N = 2^16 launch uses).  Real
+    diagonals on a sub-2^50 chain (packed half records), 10 output blocks: N1 = 4 gives 40 (b,p) pairs, five full
+    tiles; N1 = 8 gives 20, two full tiles and a ragged one.  Every residue of every block against the oracle."""
+    O = helpers.small_oracle(13, L=3, K=1, dnum=3, qbits=45, pbits=50)
+    _, P = make_pair(O)
+    r = W.rng(1313)
+    X = r.uniform(-1, 1, (8, 40))
+    Wm = r.uniform(-0.5, 0.5, (40, 150))
+    bias = r.uniform(-0.5, 0.5, 150)
+    Y, ref, cnt, slots = run_case(O, P, X, Wm, bias, 8, 16, N1, 35, 3, 77, hw=16, real=True, merged=merged)
+    assert np.abs(Y - ref).max() <= 1e-3
+    assert np.abs(slots.imag).max() <= 1e-3
+
+
+def test_argument_checks_enqueue_nothing():
+    """A weight set with diagonals missing, unknown flag bits and an output that overlaps the input are refused
+    with CKKS_E_INVAL before anything is enqueued; so are overlapping buffers of rescale and the hoisted rotation."""
+    B = _B()
+    O = helpers.small_oracle(10, L=3, K=1, dnum=3, qbits=40, pbits=42)
+    _, P = make_pair(O)
+    N, level, m, C, N1 = O.N, 3, 4, 16, 4
+    w = B.ckks_weights_create(P, level, m, C, 1, 1, N1)
+    x = torch.zeros((1, 2, level, N), dtype=torch.int64, device="cuda")
+    cl = helpers.Client(O, 5, hamming_weight=16)
+    _, baby = load_keys(P, O, cl, [q * m for q in range(1, N1)])
+    _, giant = load_keys(P, O, cl, [p * N1 * m for p in range(1, C // N1)])
+    with pytest.raises(B.CkksError) as e:                       # nothing loaded
+        B.ckks_ctpt_matmul(P, w, x, baby, giant)
+    assert e.value.code == -1 and "diagonal 0 of 16 was never loaded" in str(e.value)
+    B.ckks_weights_set_diagonals(w, 0, torch.zeros((5, N), dtype=torch.int64, device="cuda"))
+    with pytest.raises(B.CkksError) as e:                       # partly loaded
+        B.ckks_ctpt_matmul(P, w, x, baby, giant)
+    assert "diagonal 5 of 16" in str(e.value)
+    B.ckks_weights_set_diagonals(w, 5, torch.zeros((11, N), dtype=torch.int64, device="cuda"))
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_ctpt_matmul(P, w, x, baby, giant, flags=6)
+    assert e.value.code == -1 and "flags" in str(e.value)
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_ctpt_matmul(P, w, x, baby, giant, d_ct_y=x)
+    assert e.value.code == -1 and "overlaps" in str(e.value)
+    y, _ = B.ckks_ctpt_matmul(P, w, x, baby, giant)             # complete and well-formed: runs
+    torch.cuda.synchronize()
+    assert int(y.abs().max()) == 0
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_rescale(P, x, level, 1, d_ct_out=x.view(-1)[:2 * (level - 1) * N])
+    assert "overlaps" in str(e.value)
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_rotate_hoisted(P, x, level, [1], [None], d_ct_out=x)
+    assert "overlaps" in str(e.value)
+    # the scratch arena was sized by the create calls: the projection did not grow it, and a reservation does
+    before = B.ckks_params_scratch_bytes(P)
+    B.ckks_params_reserve(P, before + 4096)
+    assert B.ckks_params_scratch_bytes(P) == before + 4096
+
+
+def test_adopted_key_gives_the_same_rotation():
+    """ckks_galois_key_adopt (the library converts the caller's buffer in place and borrows it) against
+    ckks_galois_key_load (the library keeps a copy): identical outputs of a hoisted rotation."""
+    B = _B()
+    O = helpers.small_oracle(11, L=4, K=2, dnum=2, qbits=45, pbits=50)
+    _, P = make_pair(O)
+    cl = helpers.Client(O, 77, hamming_weight=16)
+    ct = to_dev(cl.encrypt_slots(W.unit_disk_slots(W.rng(3), O.n), 2.0 ** 35, 4))
+    g = O.galois_elt(3)
+    key = cl.galois_key(g)
+    k_copy = B.ckks_galois_key_load(P, g, to_dev(key))
+    buf = to_dev(key)
+    k_adopt = B.ckks_galois_key_adopt(P, g, buf)
+    a = B.ckks_rotate_hoisted(P, ct, 4, [3], [k_copy])
+    b = B.ckks_rotate_hoisted(P, ct, 4, [3], [k_adopt])
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    assert (to_host(a)[0] == O.rotate_hoisted(to_host(ct), 4, [g], [key])[0]).all()
