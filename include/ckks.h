@@ -256,6 +256,18 @@ int ckks_rot_first(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t leve
 int ckks_rescale(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct,
                  uint64_t *d_ct_out, void *stream);
 
+/* ckks_rescale for callers that cannot allocate device memory or tolerate a call that might: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same bits
+ * as ckks_rescale, but the one scratch buffer (the dropped limbs in the coefficient domain, 2 * n_ct * N words)
+ * lives in a static device array of 2^20 words (8 MiB per GPU, held until the process ends) instead of the
+ * params handle's arena: CKKS_E_INVAL if 2 * n_ct * N exceeds that (8 ciphertexts at N = 2^16), or if the
+ * current device is not the parameter set's.  Calls no hipMalloc / hipFree, enqueues on `stream` and returns.
+ * All calls on one GPU share the array: two calls that overlap in time on one GPU (different streams or
+ * threads) race; calls on one stream are ordered and safe.  Nothing needs clearing between calls: every word a
+ * call reads it has written first. */
+int ckks_rescale_static(ckks_params_t *params, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct,
+                        uint64_t *d_ct_out, void *stream);
+
 /* ---- key holder's side (the client of Sec. 2.3: KeyGen, Enc, Dec) ----------
  * Randomness is drawn by the caller and passed in, so results are reproducible
  * and comparable bit for bit.  None of these calls is on the server's path. */

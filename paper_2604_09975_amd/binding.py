@@ -51,6 +51,7 @@ _SIGS = {
     "ckks_ctpt_matmul": [_vp, _vp, _vp, C.POINTER(_vp), C.POINTER(_vp), _vp, C.c_uint32, _vp, C.POINTER(Counters),
                          _vp],
     "ckks_rescale": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
+    "ckks_rescale_static": [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp],
     "ckks_relin_key_load": [_vp, _vp, _vp, C.POINTER(_vp)],
     "ckks_ctmul": [_vp, _vp, _vp, C.c_uint32, _vp, _vp, _vp],
     "ckks_plain_expand": [_vp, C.c_uint32, _vp, C.c_uint32, _vp, _vp],
@@ -300,6 +301,15 @@ def ckks_rescale(P, d_ct_in, level_in, n_ct, d_ct_out=None):
     if d_ct_out is None:
         d_ct_out = torch.empty((n_ct, 2, max(level_in - 1, 1), P.N), dtype=torch.int64, device=d_ct_in.device)
     _check(lib.ckks_rescale(P.h, _dev(d_ct_in), level_in, n_ct, _dev(d_ct_out), _stream()))
+    return d_ct_out
+
+
+def ckks_rescale_static(P, d_ct_in, level_in, n_ct, d_ct_out):
+    """ckks_rescale for callers that may not allocate: the caller passes the output, the library's scratch is a
+    static device array (2 * n_ct * N words must fit it)."""
+    if d_ct_in.numel() != n_ct * 2 * level_in * P.N or d_ct_out.numel() != n_ct * 2 * (level_in - 1) * P.N:
+        raise ValueError("input must be [n_ct][2][level][N], output [n_ct][2][level-1][N]")
+    _check(lib.ckks_rescale_static(P.h, _dev(d_ct_in), level_in, n_ct, _dev(d_ct_out), _stream()))
     return d_ct_out
 
 

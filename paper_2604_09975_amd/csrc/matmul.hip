@@ -1204,6 +1204,28 @@ static int rescale_rows(ckks_params *P, const u64 *d_in, u32 level, u32 rows, u6
     return CKKS_OK;
 }
 
+// Scratch of ckks_rescale_static: device memory that exists from load time on every GPU the library runs on, so
+// that the entry point never allocates.  In host code the array's name is only a stand-in: its device address is
+// looked up once per device (static_scratch_ptr) and that pointer is what kernels and copies receive.
+constexpr size_t STATIC_SCRATCH_WORDS = (size_t)1 << 20;          // 8 MiB: 16 limb polynomials at N = 2^16
+static __device__ __align__(256) u64 scratch[STATIC_SCRATCH_WORDS];
+constexpr int MAX_DEVICES = 64;
+static u64 *g_static_ptr[MAX_DEVICES] = {};
+
+static int static_scratch_ptr(int device, u64 **out) {
+    if (device < 0 || device >= MAX_DEVICES) {
+        set_error("ckks_rescale_static: device %d outside [0,%d)", device, MAX_DEVICES);
+        return CKKS_E_INVAL;
+    }
+    if (!g_static_ptr[device]) {
+        u64 *ptr = nullptr;
+        CKKS_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        g_static_ptr[device] = ptr;
+    }
+    *out = g_static_ptr[device];
+    return CKKS_OK;
+}
+
 }  // namespace ckks
 
 extern "C" {
@@ -1265,6 +1287,41 @@ int ckks_rescale(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level_in, u
         if (rc) return rc;
     }
     return CKKS_OK;
+}
+
+int ckks_rescale_static(ckks_params_t *P, const uint64_t *d_ct_in, uint32_t level_in, uint32_t n_ct,
+                        uint64_t *d_ct_out, void *stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!P || !d_ct_in || !d_ct_out) {
+        set_error("ckks_rescale_static: null argument");
+        return CKKS_E_INVAL;
+    }
+    if (level_in < 2 || level_in > P->L) {
+        set_error("ckks_rescale_static: level %u outside [2,%u]", level_in, P->L);
+        return CKKS_E_LEVEL;
+    }
+    if (n_ct == 0) return CKKS_OK;
+    const u32 N = P->N, level = level_in;
+    if ((size_t)2 * n_ct * N > STATIC_SCRATCH_WORDS) {
+        set_error("ckks_rescale_static: %u ciphertexts of N = %u need %zu words of scratch, the static buffer holds %zu "
+                  "(use ckks_rescale)", n_ct, N, (size_t)2 * n_ct * N, STATIC_SCRATCH_WORDS);
+        return CKKS_E_INVAL;
+    }
+    if (words_overlap(d_ct_in, (size_t)n_ct * 2 * level * N, d_ct_out, (size_t)n_ct * 2 * (level - 1) * N)) {
+        set_error("ckks_rescale_static: d_ct_out overlaps d_ct_in");
+        return CKKS_E_INVAL;
+    }
+    int device = -1;
+    CKKS_HIP(hipGetDevice(&device));
+    if (device != P->device) {
+        set_error("ckks_rescale_static: current device %d is not the parameter set's device %d", device, P->device);
+        return CKKS_E_INVAL;
+    }
+    u64 *d_r = nullptr;
+    int rc = static_scratch_ptr(device, &d_r);
+    if (rc) return rc;
+    // every word of the buffer this call reads is written first (take_last_limb_kernel): nothing to clear
+    return rescale_rows(P, d_ct_in, level, 2 * n_ct, d_ct_out, d_r, stream);
 }
 
 }  // extern "C"
