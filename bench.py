@@ -25,6 +25,15 @@ GIANT_NAMES = {True: "one ModDown per output block (rotated accumulators summed 
                False: "one complete key switch per rotation"}
 
 
+def key_switch_bytes(N, level, K, L, dnum):
+    """Algorithmic bytes of one key switch inside a hoisted batch: both components of the key over the level + K
+    active limbs for each digit, the extended digits once, c0 once, the output once (8 bytes per residue)."""
+    alpha = L // dnum
+    beta = -(-level // alpha)
+    Wl = level + K
+    return (2 * beta * Wl + beta * Wl + level + 2 * level) * 8 * N
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -149,8 +158,21 @@ def read_valu(workload):
     return None
 
 
-def cpu_baseline(W, spec, n1):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+def _omp_threads(n):
+    """Sets the OpenMP thread count of this process (the oracle's C library is parallelised with OpenMP over
+    independent limbs / diagonals / Galois elements only)."""
+    import ctypes
+    try:
+        ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+        return True
+    except OSError:
+        return False
+
+
+def cpu_baseline(W, spec, n1, full=False):
+    """The oracle as it stands, on the host cores.  Default: a bounded sample, three distinct 128 x 256 x 256
+    corners (input group, output block) of the projection, each timed in its parts; the spread of the three is
+    printed and the whole-layer figure is assembled from their means.  full: the whole projection and rescale."""
     import oracle
     from oracle import encoding as E
     ring = spec.ring
@@ -166,47 +188,83 @@ def cpu_baseline(W, spec, n1):
         e = W.gaussian_error(r, (O.dnum, O.N))
         return O.galois_keygen(s, O.galois_elt(step), a, e)
 
-    # sample: the 128 x 256 x 256 corner of the projection (one input group, one output block):
-    # 256 of the 6912 diagonals, 15 of the 45 hoisted and 15 of the 135 single key switches
     C, m = spec.C, spec.m
     N2 = C // n1
-    X, Wm, _ = W.matmul_inputs(spec)
-    X, Wm = X[:, :C], Wm[:C, :C]
+    G, B_out = -(-spec.d_in // C), -(-spec.d_out // C)
+    X, Wm, bias = W.matmul_inputs(spec)
     scale = 2.0 ** ring.log_scale
     mx = E.encode(E.pack_columns(X, O.n, C) + 0j, scale, O.N)
-    a = W.uniform_residues(r, O.q, O.N)
-    ct = O.encrypt(O.L, mx[0], s, a, W.gaussian_error(r, (O.N,)))[None]
-    diag = E.encode_diagonals(Wm, m, O.N, C, n1, scale)
+    cts = np.stack([O.encrypt(O.L, mx[g], s, W.uniform_residues(r, O.q, O.N), W.gaussian_error(r, (O.N,)))
+                    for g in range(G)])
     baby = [key(qq * m) for qq in range(1, n1)]
     giant = [key(pp * n1 * m) for pp in range(1, N2)]
-    t0 = time.time()
-    O.rotate_hoisted(ct[0], O.L, [O.galois_elt(qq * m) for qq in range(n1)], [None] + baby)
-    t_bank = time.time() - t0
-    t0 = time.time()
-    O.rotate_hoisted(ct[0], O.L, [O.galois_elt(n1 * m)], giant[:1])
-    t_single = time.time() - t0
-    t0 = time.time()
-    y = O.ctpt_matmul(O.L, m, 1, 1, n1, N2, diag, None, 0, ct, baby, giant)
-    O.rescale(y, O.L)
-    t_sub = time.time() - t0
-    G, B_out = -(-spec.d_in // C), -(-spec.d_out // C)
-    t_diag = max(t_sub - t_bank - (N2 - 1) * t_single, 0.0)        # 256 diagonals + one rescale
-    full = G * t_bank + G * B_out * t_diag + B_out * (N2 - 1) * t_single
-    ks_per_s = (n1 - 1) / t_bank
-    return dict(value=full * 1e3, unit="ms", cores=cores, kind="oracle",
-                sample=f"128x{C}x{C} corner of the projection run by the oracle in {t_sub + t_bank + t_single:.1f}s "
-                       f"(256/6912 diagonals, {n1 - 1} hoisted + {N2 - 1} single key switches, 1 rescale); "
-                       f"value = {G}*bank + {G * B_out}*diagonals + {B_out * (N2 - 1)}*single switch, extrapolated",
-                key_switches_per_s_hoisted=ks_per_s)
+    gel_bank = [O.galois_elt(qq * m) for qq in range(n1)]
+
+    # single-thread figures for the two smaller configurations: limb transforms and one hoisted batch
+    one = {}
+    if _omp_threads(1):
+        x = W.uniform_residues(r, O.q, O.N)
+        t0 = time.time()
+        for i in range(O.L):
+            O.ntt(i, x[i])
+        one["ntt_limb_polys_per_s"] = O.L / (time.time() - t0)
+        t0 = time.time()
+        O.rotate_hoisted(cts[0], O.L, gel_bank[:5], [None] + baby[:4])
+        one["hoisted_key_switches_per_s"] = 4 / (time.time() - t0)
+        one["sample"] = "24 forward limb transforms; one hoisted call with 4 key switches (decomposition included)"
+        _omp_threads(cores)
+
+    if full:
+        diag = E.encode_diagonals(Wm, m, O.N, C, n1, scale)
+        bias_c = np.stack([E.encode(E.bias_slots(bias, m, O.n, C, b) + 0j, scale, O.N) for b in range(B_out)])
+        t0 = time.time()
+        y = O.ctpt_matmul(O.L, m, G, B_out, n1, N2, diag, bias_c, int(scale), cts, baby, giant)
+        O.rescale(y, O.L)
+        t_full = time.time() - t0
+        return dict(value=t_full * 1e3, unit="ms", cores=cores, kind="oracle",
+                    sample="the whole 128x768x2304 projection + rescale, one complete key switch per giant rotation",
+                    one_thread=one)
+
+    corners = [(0, 0), (1, B_out // 2), (G - 1, B_out - 1)]       # (input group, output block)
+    t_bank, t_single, t_diag = [], [], []
+    t_all = time.time()
+    for g, b in corners:
+        Xc, Wc = X[:, g * C:(g + 1) * C], Wm[g * C:(g + 1) * C, b * C:(b + 1) * C]
+        diag = E.encode_diagonals(Wc, m, O.N, C, n1, scale)
+        ct = cts[g:g + 1]
+        t0 = time.time()
+        O.rotate_hoisted(ct[0], O.L, gel_bank, [None] + baby)
+        t_bank.append(time.time() - t0)
+        t0 = time.time()
+        O.rotate_hoisted(ct[0], O.L, [O.galois_elt(n1 * m)], giant[:1])
+        t_single.append(time.time() - t0)
+        t0 = time.time()
+        y = O.ctpt_matmul(O.L, m, 1, 1, n1, N2, diag, None, 0, ct, baby, giant)
+        O.rescale(y, O.L)
+        t_sub = time.time() - t0
+        t_diag.append(max(t_sub - t_bank[-1] - (N2 - 1) * t_single[-1], 0.0))   # 256 diagonals + one rescale
+    t_all = time.time() - t_all
+    mean = lambda v: sum(v) / len(v)
+    full_est = G * mean(t_bank) + G * B_out * mean(t_diag) + B_out * (N2 - 1) * mean(t_single)
+    spread = {"bank_s": [round(v, 3) for v in t_bank], "single_switch_s": [round(v, 3) for v in t_single],
+              "diagonals_256_s": [round(v, 3) for v in t_diag]}
+    return dict(value=full_est * 1e3, unit="ms", cores=cores, kind="oracle",
+                sample=f"three 128x{C}x{C} corners (input group, output block) = {corners} of the projection run by "
+                       f"the oracle in {t_all:.1f}s, each: {n1 - 1} hoisted + {N2 - 1} single key switches, 256 of the "
+                       f"{G * B_out * C} diagonals, 1 rescale; value = {G}*bank + {G * B_out}*diagonals + "
+                       f"{B_out * (N2 - 1)}*single switch from the means of the three (extrapolated; "
+                       f"--cpu-baseline full runs the whole layer)",
+                spread=spread, key_switches_per_s_hoisted=(n1 - 1) / mean(t_bank), one_thread=one)
 
 
-def run_gpt2_block(args, B, CL, W, P, cl):
+def run_gpt2_block(args, B, CL, W, P, cl, emit=True, steps=None):
     """The four linear layers of a GPT-2-small block (QKV, attention output, FFN up, FFN down) at sequence
     length 128, one after the other; weights of one layer resident at a time; inputs freshly encrypted per
     layer (the MPC boundary between layers is simulated by fresh synthetic activations)."""
     import torch
     from paper_2604_09975_amd import plan
     keys, layers, total = {}, [], 0.0
+    n_steps = steps or args.steps
     for spec in W.GPT2_LAYERS:
         n1 = args.n1 or spec.N1
         if args.pair_compression and not args.n1:
@@ -227,11 +285,11 @@ def run_gpt2_block(args, B, CL, W, P, cl):
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(args.steps):
+        for _ in range(n_steps):
             cnt = step()
         e1.record()
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / args.steps
+        ms = e0.elapsed_time(e1) / n_steps
         out_scale = S["scale"] * S["scale"] / P.q[level - 1]
         slots = np.stack([cl.decrypt_slots(yr[b], level - 1, out_scale) for b in range(B_out)])
         err = float(np.abs(CL.unpack_columns(slots.real, spec.m, spec.C, spec.d_out) - S["ref"]).max())
@@ -246,6 +304,9 @@ def run_gpt2_block(args, B, CL, W, P, cl):
         S["w"].close()
         del S, y, yr
         torch.cuda.empty_cache()
+    if not emit:
+        return {"total_ms": total, "steps": n_steps, "giant_step": GIANT_NAMES[not args.separate_giant],
+                "input_packing": "complex pairs (Sec. 3.2)" if args.pair_compression else "real", "layers": layers}
     print(json.dumps({
         "metric": "GPT-2-small block linear layers total latency ms (seq 128, hidden 768)", "value": total,
         "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total,
@@ -256,7 +317,7 @@ def run_gpt2_block(args, B, CL, W, P, cl):
           flush=True)
 
 
-def run_ntt(args, B, W):
+def run_ntt(args, B, W, emit=True):
     """NTT microbenchmark: 64 polynomials x 24 limbs of 50-bit primes x 2^16, forward then inverse."""
     import torch
     ring = W.NTT_RING
@@ -284,6 +345,14 @@ def run_ntt(args, B, W):
     fwd, inv = fwd / args.steps, inv / args.steps
     nbytes = 2 * 8 * W.NTT_BATCH * 24 * P.N                      # each residue read once and written once
     ach = nbytes / (fwd * 1e-3) / 1e9
+    if not emit:
+        del x, ref
+        P.close()
+        torch.cuda.empty_cache()
+        return {"workload": ring.name, "batch": W.NTT_BATCH, "limbs": 24, "N": 1 << ring.logN, "forward_ms": fwd,
+                "inverse_ms": inv, "forward_GBps": ach, "inverse_GBps": nbytes / (inv * 1e-3) / 1e9,
+                "algorithmic_bytes_per_direction": nbytes, "hbm_roofline_frac": ach / HBM_PEAK_GBS,
+                "roundtrip_bit_exact": True}
     print(json.dumps({
         "metric": "NTT throughput GB/s (64 x 24 limbs x 2^16, forward)", "value": ach, "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": fwd + inv, "higher_is_better": True,
@@ -342,9 +411,9 @@ def run_hoisted(args, B, CL, W, P, cl):
         "max_abs_err": err,
         "literal_32_steps": {"steps": "1..31 and conj", "key_switches": 32, "ms": ms32,
                              "key_switches_per_s": 32 / ms32 * 1e3, "max_abs_err": err32},
-        "roofline": {"bound": "hbm", "kernel": "ckks_rotate_hoisted (all kernels)", "achieved": 188.7e6 * ks / 1e9,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": 188.7e6 * ks / (HBM_PEAK_GBS * 1e9),
-                     "traffic": None, "bytes_per_launch": 188.7e6 * len(steps), "ms_per_launch": ms}}), flush=True)
+        "roofline": {"bound": "hbm", "kernel": "ckks_rotate_hoisted (all kernels)", "achieved": key_switch_bytes(P.N, level, P.K, P.L, P.dnum) * ks / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": key_switch_bytes(P.N, level, P.K, P.L, P.dnum) * ks / (HBM_PEAK_GBS * 1e9),
+                     "traffic": None, "bytes_per_launch": key_switch_bytes(P.N, level, P.K, P.L, P.dnum) * len(steps), "ms_per_launch": ms}}), flush=True)
 
 
 def run_primitives(args, B, CL, W, P, cl):
@@ -438,6 +507,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--n1", type=int, default=0, help="baby steps (0 = the configuration's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline", default="sample", choices=["sample", "full", "none"],
+                    help="oracle timing on the host cores: three sampled corners of the layer (default), the whole "
+                         "layer (about two minutes), or none")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="bert_qkv only: skip the NTT microbenchmark and the GPT-2 block that ride in the same line")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--workload", default="bert_qkv", choices=["bert_qkv", "gpt2_block", "hoisted", "ntt", "primitives"],
                     help="bert_qkv (default, the headline configuration), the four GPT-2-small block layers, the "
@@ -551,21 +625,35 @@ def main():
     torch.cuda.synchronize()
     other_ms = e0.elapsed_time(e1) / args.steps
 
-    # hoisted rotation batch (N = 2^16, L = 24): 26 rotations + conjugation from one ciphertext
+    # hoisted rotation batch (N = 2^16, L = 24): 26 rotations + conjugation from one ciphertext, and the step set
+    # read literally as 32 distinct steps (rotations 1..31 and the conjugation)
     steps = [] if args.no_hoisted else [s for s in W.HOISTED_STEPS if s != (1 << 15)]
     keys = [cl.galois_key(s) for s in steps]
     ct = cl.encrypt_slots(W.unit_disk_slots(W.rng(W.HOISTED_SEED), P.N // 2), S["scale"], level)
-    rot_out = torch.empty((len(steps), 2, level, N), dtype=torch.int64, device="cuda")
-    B.ckks_rotate_hoisted(P, ct, level, steps, keys, rot_out)
-    torch.cuda.synchronize()
     reps = 10
-    e0.record()
-    for _ in range(reps):
-        B.ckks_rotate_hoisted(P, ct, level, steps, keys, rot_out)
-    e1.record()
-    torch.cuda.synchronize()
-    rot_ms = e0.elapsed_time(e1) / reps
+
+    def time_batch(st, ks):
+        o = torch.empty((len(st), 2, level, N), dtype=torch.int64, device="cuda")
+        B.ckks_rotate_hoisted(P, ct, level, st, ks, o)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            B.ckks_rotate_hoisted(P, ct, level, st, ks, o)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rot_ms = time_batch(steps, keys)
     ks_per_s = len(steps) / rot_ms * 1e3 if steps else None
+    literal32 = None
+    if steps:
+        steps32 = list(range(1, 32)) + ["conj"]
+        have = dict(zip(steps, keys))
+        keys32 = [have[s_] if s_ in have else cl.galois_key(s_) for s_ in steps32]
+        ms32 = time_batch(steps32, keys32)
+        literal32 = {"steps": "1..31 and conj", "key_switches": 32, "ms": ms32, "key_switches_per_s": 32 / ms32 * 1e3}
+        del keys32
+    del keys
 
     # algorithmic bytes of one diagonal multiply-accumulate launch: the bank once, the accumulators once (8 bytes
     # per residue), and of every weight limb the half that is not determined by the other half (the diagonals
@@ -585,8 +673,17 @@ def main():
     # remainder, two additions), 4 products per stored weight residue
     mac_ops = 7.0 * 4.0 * n_diag * level * (N // 2)
     achieved = mac_bytes / (mac_ms * 1e-3) / 1e9
-    ks_bytes = 188.7e6
-    traffic = read_traffic(spec.name, n1)
+    ks_bytes = key_switch_bytes(N, level, P.K, P.L, P.dnum)
+    traffic = read_traffic(spec.name, n1) if not (args.fused_qk or args.pair_compression) else None
+    # bytes the whole step must move, two counts: (i) the budget the method is usually stated in, every weight limb
+    # in full at 8 bytes per residue + Galois keys + inputs + outputs; (ii) what this formulation has to read: the
+    # weight store as it is laid out (packed half limbs for real diagonals, packed whole limbs for complex ones)
+    key_bytes = (len(S["baby"]) + len(S["giant"]) + (1 if S["conj"] is not None else 0)) * P.dnum * 2 * (P.L + P.K) * limb_poly
+    io_bytes = (G + B_out) * 2 * level * limb_poly
+    step_bytes_8 = n_diag * level * limb_poly + key_bytes + io_bytes
+    n_cplx_w = (G * n1 * (B_out // 2) * N2) if args.fused_qk else (n_diag if args.pair_compression else 0)
+    step_bytes_stored = (n_diag - n_cplx_w) * level * half_limb_packed + n_cplx_w * level * 2 * half_limb_packed \
+        + key_bytes + io_bytes
     out = {
         "metric": "ct-pt matmul latency ms (128x768x2304)",
         "value": ms_per_step,
@@ -606,22 +703,33 @@ def main():
                    "giant_step": GIANT_NAMES[merged],
                    "input_packing": "complex pairs (Sec. 3.2)" if args.pair_compression else "real",
                    "key_switches_per_step": int(cnt.key_switches), "ptmuls_per_step": int(cnt.ptmuls),
-                   "limb_ntts_per_step": int(cnt.limb_ntts)},
+                   "limb_ntts_per_step": int(cnt.limb_ntts),
+                   "primes": {"rule": "2^b - k*2N + 1, k = 1, 2, ..., the primes in order of k", "q_bits": 50,
+                              "p_bits": 60, "q": [int(v) for v in P.q], "p": [int(v) for v in P.p]}},
         "other_giant_step": {"giant_step": GIANT_NAMES[not merged], "ms_per_step": other_ms},
         "key_switches_per_s": ks_per_s,
-        "hoisted_batch": {"key_switches": len(steps), "ms": rot_ms,
-                          "hbm_roofline_frac": ks_bytes * ks_per_s / (HBM_PEAK_GBS * 1e9) if steps else None},
-        "matmul_hbm_roofline_frac": (90.0e9 / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
+        "hoisted_batch": {"key_switches": len(steps), "ms": rot_ms, "bytes_per_key_switch": ks_bytes,
+                          "hbm_roofline_frac": ks_bytes * ks_per_s / (HBM_PEAK_GBS * 1e9) if steps else None,
+                          "literal_32_steps": literal32},
+        "matmul_hbm_roofline_frac": (step_bytes_8 / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9),
+        "matmul_bytes": {"at_8_bytes_per_residue_full_limbs": step_bytes_8, "as_stored": step_bytes_stored,
+                         "frac_as_stored": (step_bytes_stored / (ms_per_step * 1e-3)) / (HBM_PEAK_GBS * 1e9)},
         "max_abs_err": max_err,
         "wall_s_timed_region": wall,
         "roofline": {"bound": "hbm", "kernel": "diag_mac_sym_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": "profiles/bert_qkv_diag_mac_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / "
+                                       "WRITE_SIZE runs of this command, committed; not measured in this run)"
+                                       if traffic is not None else None,
                      "bytes_per_launch": mac_bytes, "ms_per_launch": mac_ms,
                      "fp64_issue_frac": mac_ops / (mac_ms * 1e-3) / FP64_ISSUE_PEAK,
                      "frac_at_8_bytes_per_residue": mac_bytes_8 / (mac_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
     if not (args.fused_qk or args.pair_compression or args.n1):
         out["roofline"]["valu"] = read_valu(spec.name)
+        if out["roofline"]["valu"] is not None:
+            out["roofline"]["valu"]["source"] = ("profiles/bert_qkv_valu_utilisation.txt (rocprofv3 --pmc SQ counters "
+                                                 "of this command, committed; not measured in this run)")
     ceil = measured_ceilings(B, P)
     out["measured_ceilings"] = ceil
     out["roofline"]["frac_of_measured_read"] = achieved / ceil["read_GBps"]
@@ -629,9 +737,18 @@ def main():
         out["roofline"]["frac_of_measured_fp64_mulmod"] = (mac_ops / 7.0) / (mac_ms * 1e-3) / ceil["fp64_mulmod_per_s"]
     if steps:
         out["hoisted_batch"]["frac_of_measured_copy"] = ks_bytes * ks_per_s / (ceil["copy_GBps"] * 1e9)
-    if not args.no_cpu_baseline:
+    if not args.no_extras and not (args.fused_qk or args.pair_compression or args.n1):
+        # the other configurations ride in the same line: free the headline's weights and keys first
+        S["w"].close()
+        del S, y, yr, ct
+        torch.cuda.empty_cache()
+        out["ntt"] = run_ntt(args, B, W, emit=False)
+        log(f"[bench] ntt: forward {out['ntt']['forward_ms']:.3f} ms, inverse {out['ntt']['inverse_ms']:.3f} ms")
+        out["gpt2_block"] = run_gpt2_block(args, B, CL, W, P, cl, emit=False, steps=min(args.steps, 3))
+        log(f"[bench] gpt2 block: {out['gpt2_block']['total_ms']:.2f} ms")
+    if not args.no_cpu_baseline and args.cpu_baseline != "none":
         t0 = time.time()
-        out["cpu_baseline"] = cpu_baseline(W, spec, n1)
+        out["cpu_baseline"] = cpu_baseline(W, spec, n1, full=args.cpu_baseline == "full")
         log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
     print(json.dumps(out), flush=True)
 

@@ -92,6 +92,30 @@ def diagonal_slots_complex(Wm, m, n, C, N1, b, p, half=True):
     return 0.5 * z if half else z
 
 
+def score_friendly_permutation(H, d_h):
+    """pi_S of App. A.2.1: the head-major column k(h,u) = h*d_h + u of W_Q / W_K goes to position u*H + h, so that the
+    projection emits Q and K in the segment order the score kernel consumes.  Returns `perm` with
+    perm[k(h,u)] = u*H + h (a bijection of range(H*d_h))."""
+    h, u = np.divmod(np.arange(H * d_h), d_h)
+    return u * H + h
+
+
+def permute_columns(Wm, perm, bias=None):
+    """W^pi with W^pi[:, perm[k]] = W[:, k] (and the bias moved the same way): a plaintext-side reordering of the
+    weight matrix before its diagonals are encoded, no homomorphic cost.  pi_V of App. A.2.1 is the identity
+    (W_V stays head-major), so only W_Q and W_K pass through here."""
+    perm = np.asarray(perm)
+    if sorted(perm.tolist()) != list(range(Wm.shape[1])):
+        raise ValueError("perm must be a bijection of the columns")
+    Wp = np.empty_like(Wm)
+    Wp[:, perm] = Wm
+    if bias is None:
+        return Wp
+    bp = np.empty_like(bias)
+    bp[perm] = bias
+    return Wp, bp
+
+
 def rot_first_masks(n, L, tau):
     """Masks and rotation steps of RotFirst_L(.; tau) (App. A.1): first L - tau slots from the plain rotation,
     the next tau from the wrapped one.  -> (a [n], b [n], (step_tau, step_wrap))."""
@@ -130,7 +154,7 @@ class Client:
         a = W.uniform_residues(self.r, self.moduli, P.N, lead=(P.dnum,))
         e = W.gaussian_error(self.r, (P.dnum, P.N))
         d_key = B.ckks_client_galois_keygen(P, self.S, g, self._dev(a), self._dev(e))
-        h = B.ckks_galois_key_load(P, g, d_key)
+        h = B.ckks_galois_key_adopt(P, g, d_key)      # the generated buffer becomes the library's key: no second copy
         torch.cuda.synchronize()
         return h
 

@@ -66,3 +66,39 @@ def test_client_encoder_and_packing_match_oracle():
                     assert (d[g, q] == E.weight_diagonal(Wm, 4, 128, 16, 4, b, p, g, q)).all()
     sl = r.standard_normal((2, 128))
     assert (CL.unpack_columns(sl, 4, 16, 20) == E.unpack_columns(sl, 4, 16, 20)).all()
+
+
+def test_score_friendly_order_at_bert_head_shape():
+    """pi_S of App. A.2.1 at H = 12 heads of d_h = 64 channels (the BERT-base / GPT-2-small shape): the product-side
+    permutation equals the oracle's, and a fused Q + iK projection of the permuted weights through the library (ring
+    2^13, 12 output blocks of 64 columns) delivers column k(h,u) of Q and K at position u*H + h."""
+    from paper_2604_09975_amd import binding as B, client as CL
+    H, d_h = 12, 64
+    perm = CL.score_friendly_permutation(H, d_h)
+    assert (perm == E.score_friendly_permutation(H, d_h)).all()
+    assert perm[5 * d_h + 7] == 7 * H + 5
+    O = helpers.small_oracle(13, L=3, K=1, dnum=3, qbits=45, pbits=50)
+    _, P = make_pair(O)
+    n, N, m, C, N1, level, scale = O.n, O.N, 4, 64, 8, 3, 2.0 ** 35
+    r = W.rng(1264)
+    d_in, d = 40, H * d_h
+    X = r.uniform(-1, 1, (m, d_in))
+    WQ, WK = r.uniform(-0.5, 0.5, (d_in, d)), r.uniform(-0.5, 0.5, (d_in, d))
+    WQp, WKp = CL.permute_columns(WQ, perm), CL.permute_columns(WK, perm)
+    G, B_out, N2 = 1, d // C, C // N1
+    cl = CL.Client(P, 5, hamming_weight=16)
+    ct_x = torch.stack([cl.encrypt_slots(CL.pack_columns(X, n, C)[g], scale, level) for g in range(G)])
+    w = B.ckks_weights_create(P, level, m, C, G, B_out, N1)
+    for b in range(B_out):
+        for p in range(N2):
+            z = CL.diagonal_slots(WQp + 1j * WKp, m, n, C, N1, b, p).reshape(G * N1, n)
+            B.ckks_weights_set_diagonals(w, (b * N2 + p) * G * N1, cl.enc.encode(z, scale))
+    baby = [cl.galois_key(q * m) for q in range(1, N1)]
+    giant = [cl.galois_key(p * N1 * m) for p in range(1, N2)]
+    y, _ = B.ckks_ctpt_matmul(P, w, ct_x, baby, giant)
+    yr = B.ckks_rescale(P, y, level, B_out)
+    slots = np.stack([cl.decrypt_slots(yr[b], level - 1, scale * scale / P.q[level - 1]) for b in range(B_out)])
+    Qp, Kp = CL.unpack_columns(slots.real, m, C, d), CL.unpack_columns(slots.imag, m, C, d)
+    Qref, Kref = X @ WQ, X @ WK
+    assert np.abs(Qp[:, perm] - Qref).max() < 1e-3 and np.abs(Kp[:, perm] - Kref).max() < 1e-3
+    assert np.abs(Qp[:, 7 * H + 5] - Qref[:, 5 * d_h + 7]).max() < 1e-3
