@@ -773,8 +773,11 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
         u64 *y = d_work;                                   // [n][2][K][N]
         u64 *w = d_work + (size_t)n * 2 * K * N;           // [n][2][level][N]
         const u32 tiles = N >> 12;
+        // at N = 2^12 the tile pass is the whole inverse transform and carries the (P/p_k)^-1 scaling itself
+        const bool whole = p->logN == 12;
         hipLaunchKernelGGL(ip_intt_kernel, dim3(tiles, n * 2 * K), dim3(NTT_THREADS), 0, stream, pack, y, p->d_mod,
-                           p->d_modf, p->d_tw_inv, p->d_twf_inv, p->d_ninv, n, level, K, L, beta, p->logN);
+                           whole ? p->d_modf_dn : p->d_modf, p->d_tw_inv, p->d_twf_inv,
+                           whole ? p->d_ninv_dn : p->d_ninv, n, level, K, L, beta, p->logN);
         CKKS_LAUNCH_CHECK("ip_intt_kernel");
         p->limb_ntts += (u64)n * 2 * K;
         for (u32 k = 0; k < K; ++k) ids.id[k] = (uint8_t)(L + k);

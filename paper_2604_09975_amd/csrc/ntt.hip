@@ -4,18 +4,22 @@
 // (X^t - psi^e)(X^t + psi^e) stage by stage; stage s has 2^s nodes and node i
 // uses the twiddle psi^bitrev(2^s + i).  A polynomial of N = 2^16 residues
 // (512 KiB) does not fit LDS, so the stages are cut into two passes over HBM:
-//   pass A: the first logN - 8 stages.  Elements that interact there share
-//           their index modulo N/2^a; a workgroup owns 2^a rows of a run of
-//           consecutive residues, so global accesses stay contiguous.
-//   pass B: the last 8 stages act inside aligned runs of 256 residues; a
-//           workgroup owns 4096 consecutive residues.
+//   pass A: the first stages.  Elements that interact there share their index
+//           modulo N/2^a; global accesses stay runs of consecutive residues.
+//   pass B: the remaining stages act inside aligned runs of consecutive
+//           residues; a workgroup owns 4096 of them.
 // The inverse runs pass B then pass A with Gentleman-Sande butterflies and folds
 // N^-1 into the last stage.
 //
 // Two implementations:
 //  * N = 2^12 and N = 2^16 (the benchmark rings): every thread keeps 16 residues in
-//    registers and does four stages (radix 16) between exchanges through LDS, so a
-//    pass of 8 stages touches LDS twice instead of 16 times.  Limbs whose prime is
+//    registers and does four stages (radix 16) between exchanges through LDS.
+//    Pass B covers 12 stages (three rounds, two exchanges) on a 4096-residue tile:
+//    the whole transform at N = 2^12, all but the first 4 stages at N = 2^16.
+//    Those 4 stages (pass A) pair residues 4096 apart, so a thread that owns a
+//    column holds its 16 rows in registers and needs no LDS at all -- which is what
+//    lets the base conversions of key switching, which work column by column in the
+//    coefficient domain, carry the neighbouring pass A of both transforms.  Limbs whose prime is
 //    below 2^50 run their butterflies in fp64: residues, twiddles and the two halves
 //    of a product (a*w = h + l exactly, by FMA) are exact integers in doubles, the
 //    quotient comes from one multiplication by 1/q, and values stay signed and
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_pass_kernel(u64 *__restrict__
 }
 
 
-// which: 0 = pass A (N = 2^16), 1 = pass A (N = 2^12), 2 = pass B
+// which: 0 = pass A (N = 2^16: first / last 4 stages, registers only), 2 = pass B (12 stages in a 4096 tile)
 template <bool INV, int WHICH>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__ data,
                                                                const ModConst *__restrict__ mods,
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__
                                                                const double *__restrict__ twf,
                                                                const u64 *__restrict__ ninv, LimbIds ids,
                                                                u32 n_limbs, u32 logN) {
-    __shared__ u64 lds[WHICH == 1 ? 1 : FAST_LDS_WORDS];
+    __shared__ u64 lds[WHICH == 0 ? 1 : FAST_LDS_WORDS];
     const u32 row = blockIdx.y;
     const u32 limb = ids.id[row % n_limbs];
     if (limb == SKIP_ROW) return;
@@ -110,15 +114,14 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__
     const ModFp mf = modf[limb];
     auto load = [&](u32 idx) { return poly[idx]; };
     auto store = [&](u32 idx, u64 v) { poly[idx] = v; };
+    const u32 col = blockIdx.x * NTT_THREADS + threadIdx.x;
     if (mf.ok) {
         const FieldFp f = make_field_fp(mf, twf, limb, logN);
-        if (WHICH == 0) pass_a16_body<INV>(f, lds, load, store);
-        if (WHICH == 1) pass_a12_body<INV>(f, load, store);
+        if (WHICH == 0) pass_a16_body<INV>(f, col, load, store);
         if (WHICH == 2) pass_b_body<INV>(f, logN, lds, load, store);
     } else {
         const FieldInt f = make_field_int(mods, tw, ninv, limb, logN);
-        if (WHICH == 0) pass_a16_body<INV>(f, lds, load, store);
-        if (WHICH == 1) pass_a12_body<INV>(f, load, store);
+        if (WHICH == 0) pass_a16_body<INV>(f, col, load, store);
         if (WHICH == 2) pass_b_body<INV>(f, logN, lds, load, store);
     }
 }
@@ -147,23 +150,16 @@ int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limb
         return CKKS_E_INVAL;
     }
     if (logN == 16 || logN == 12) {
+        // N = 2^16: pass A (4 stages) and pass B (12 stages); N = 2^12: pass B is the whole transform (forward: the
+        // "second" pass, inverse: the "first"), and carries the scaled last stage
         const u32 tb = p->N >> 12;
+        const bool two = logN == 16;
         if (!inverse) {
-            if (pass_mask & 1) {
-                if (logN == 16)
-                    launch_fast<false, 0>(p, d_data, ids, n_limbs, rows, 16, stream, false);
-                else
-                    launch_fast<false, 1>(p, d_data, ids, n_limbs, rows, 1, stream, false);
-            }
+            if ((pass_mask & 1) && two) launch_fast<false, 0>(p, d_data, ids, n_limbs, rows, 16, stream, false);
             if (pass_mask & 2) launch_fast<false, 2>(p, d_data, ids, n_limbs, rows, tb, stream, false);
         } else {
-            if (pass_mask & 1) launch_fast<true, 2>(p, d_data, ids, n_limbs, rows, tb, stream, false);
-            if (pass_mask & 2) {
-                if (logN == 16)
-                    launch_fast<true, 0>(p, d_data, ids, n_limbs, rows, 16, stream, scaled_dn);
-                else
-                    launch_fast<true, 1>(p, d_data, ids, n_limbs, rows, 1, stream, scaled_dn);
-            }
+            if (pass_mask & 1) launch_fast<true, 2>(p, d_data, ids, n_limbs, rows, tb, stream, two ? false : scaled_dn);
+            if ((pass_mask & 2) && two) launch_fast<true, 0>(p, d_data, ids, n_limbs, rows, 16, stream, scaled_dn);
         }
         CKKS_LAUNCH_CHECK("ntt_fast_kernel");
         return CKKS_OK;

@@ -130,11 +130,16 @@ __device__ __forceinline__ void radix16_inv(const F &f, typename F::T (&v)[16], 
     }
 }
 
-// pass B: last 8 stages on 4096 consecutive residues (16 runs of 256), in two halves so that callers can
-// put their own code between global memory and LDS.  LDS slot of residue e of the tile: lds[lds_pad(e)].
+// pass B: the last 12 stages act inside aligned runs of 4096 consecutive residues, one workgroup per run, in three
+// radix-16 rounds with an LDS exchange between them:
+//   round 1 (stages logN-12 .. logN-9): thread t holds residues j*256 + t          (2 KiB runs in global memory)
+//   round 2 (stages logN-8  .. logN-5): thread (blk, c) holds blk*256 + c + 16*j
+//   round 3 (stages logN-4  .. logN-1): thread (blk, c) holds blk*256 + 16*c + j
+// For N = 2^12 this is the whole transform.  The passes come in halves so that callers can put their own code
+// between global memory and LDS.  LDS slot of residue e of the tile: lds[lds_pad(e)].
 //
-// forward: load(idx) gives the canonical residue at index idx of the polynomial (strided register pattern,
-// 128-byte runs); on return the tile's transformed, canonical residues are in LDS and the workgroup is synced.
+// forward: load(idx) gives the canonical residue at index idx of the polynomial (round-1 pattern: coalesced); on
+// return the tile's transformed, canonical residues are in LDS and the workgroup is synced.
 template <class F, class Load>
 __device__ __forceinline__ void pass_b_fwd_to_lds(const F &f, u32 logN, u64 *lds, Load load) {
     const u32 tid = threadIdx.x, blk = tid >> 4, c = tid & 15;
@@ -143,10 +148,16 @@ __device__ __forceinline__ void pass_b_fwd_to_lds(const F &f, u32 logN, u64 *lds
     const u32 strided = blk * 256 + c, contig = blk * 256 + c * 16;
     typename F::T v[16];
 #pragma unroll
-    for (u32 j = 0; j < 16; ++j) v[j] = f.in(load(base + strided + j * 16));
+    for (u32 j = 0; j < 16; ++j) v[j] = f.in(load(base + j * 256 + tid));
+    radix16_fwd(f, v, logN - 12, blockIdx.x);
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) lds[lds_pad(j * 256 + tid)] = f.bits(v[j]);
+    __syncthreads();
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(strided + j * 16)]);
     radix16_fwd(f, v, logN - 8, run);
 #pragma unroll
-    for (u32 j = 0; j < 16; ++j) lds[lds_pad(strided + j * 16)] = f.bits(v[j]);
+    for (u32 j = 0; j < 16; ++j) lds[lds_pad(strided + j * 16)] = f.bits(v[j]);   // a thread's own slots
     __syncthreads();
 #pragma unroll
     for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(contig + j)]);
@@ -157,7 +168,8 @@ __device__ __forceinline__ void pass_b_fwd_to_lds(const F &f, u32 logN, u64 *lds
 }
 
 // inverse: expects the tile's canonical residues in LDS (workgroup synced); store(idx, value) receives the
-// canonical results in the strided register pattern.
+// canonical results in the round-1 pattern (coalesced).  whole: the tile is the whole polynomial (N = 2^12), so the
+// last round ends the transform and folds in N^-1.
 template <class F, class Store>
 __device__ __forceinline__ void pass_b_inv_from_lds(const F &f, u32 logN, u64 *lds, Store store) {
     const u32 tid = threadIdx.x, blk = tid >> 4, c = tid & 15;
@@ -175,7 +187,13 @@ __device__ __forceinline__ void pass_b_inv_from_lds(const F &f, u32 logN, u64 *l
     for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(strided + j * 16)]);
     radix16_inv(f, v, logN - 8, run, false);
 #pragma unroll
-    for (u32 j = 0; j < 16; ++j) store(base + strided + j * 16, f.out(v[j]));
+    for (u32 j = 0; j < 16; ++j) lds[lds_pad(strided + j * 16)] = f.bits(v[j]);   // a thread's own slots
+    __syncthreads();
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(j * 256 + tid)]);
+    radix16_inv(f, v, logN - 12, blockIdx.x, logN == 12);
+#pragma unroll
+    for (u32 j = 0; j < 16; ++j) store(base + j * 256 + tid, f.out(v[j]));
 }
 
 // Whole pass with coalesced stores (forward) / coalesced loads (inverse).
@@ -194,53 +212,20 @@ __device__ __forceinline__ void pass_b_body(const F &f, u32 logN, u64 *lds, Load
     }
 }
 
-// pass A for N = 2^16: first 8 stages on a tile of 256 rows x 16 consecutive residues (blockIdx.x picks the
-// 16 columns).  load(idx) / store(idx, value) see canonical residues at index idx of the polynomial.
+// pass A for N = 2^16: the first 4 stages pair residues 4096 apart, so a thread that owns one of the 4096 columns
+// holds its 16 rows in registers: no LDS, every access a run of consecutive residues.  col: the thread's column;
+// load(idx) / store(idx, value) see canonical residues at index idx of the polynomial.
 template <bool INV, class F, class Load, class Store>
-__device__ __forceinline__ void pass_a16_body(const F &f, u64 *lds, Load load, Store store) {
-    const u32 tid = threadIdx.x, c = tid >> 4, lo = tid & 15;
-    const u32 col = blockIdx.x * 16 + lo;
-    typename F::T v[16];
-    if (!INV) {
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.in(load((j * 16 + c) * 256 + col));
-        radix16_fwd(f, v, 0, 0);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad((j * 16 + c) * 16 + lo)] = f.bits(v[j]);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad((c * 16 + j) * 16 + lo)]);
-        radix16_fwd(f, v, 4, c);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) store((c * 16 + j) * 256 + col, f.out(v[j]));
-    } else {
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.in(load((c * 16 + j) * 256 + col));
-        radix16_inv(f, v, 4, c, false);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) lds[lds_pad((c * 16 + j) * 16 + lo)] = f.bits(v[j]);
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad((j * 16 + c) * 16 + lo)]);
-        radix16_inv(f, v, 0, 0, true);
-#pragma unroll
-        for (u32 j = 0; j < 16; ++j) store((j * 16 + c) * 256 + col, f.out(v[j]));
-    }
-}
-
-// pass A for N = 2^12: first 4 stages, 16 rows x 256 residues, registers only
-template <bool INV, class F, class Load, class Store>
-__device__ __forceinline__ void pass_a12_body(const F &f, Load load, Store store) {
-    const u32 tid = threadIdx.x;
+__device__ __forceinline__ void pass_a16_body(const F &f, u32 col, Load load, Store store) {
     typename F::T v[16];
 #pragma unroll
-    for (u32 j = 0; j < 16; ++j) v[j] = f.in(load(j * 256 + tid));
+    for (u32 j = 0; j < 16; ++j) v[j] = f.in(load(j * 4096 + col));
     if (!INV)
         radix16_fwd(f, v, 0, 0);
     else
         radix16_inv(f, v, 0, 0, true);
 #pragma unroll
-    for (u32 j = 0; j < 16; ++j) store(j * 256 + tid, f.out(v[j]));
+    for (u32 j = 0; j < 16; ++j) store(j * 4096 + col, f.out(v[j]));
 }
 
 // Field objects for limb `limb` from the parameter tables.
