@@ -391,6 +391,116 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__r
     }
 }
 
+// ModDown between the two tile passes at N = 2^16, one kernel instead of three.  The last 4 stages of the inverse
+// transform of the special limbs, the base conversion P -> q_i and the first 4 stages of the forward transform of the
+// correction w all work on columns (residues 4096 apart), so a workgroup that owns MID_COLS columns can do all
+// three without leaving the CU:
+//   1. thread (k, col): column col of special limb k, 16 rows in registers, last inverse round (which folds in
+//      N^-1 (P/p_k)^-1) -> y_k in LDS;
+//   2. thread (row pair, col): its two coefficients' y_k cut into 20-bit pieces once, then for each group of
+//      MID_TG target limbs the exact fp64 sums of moddown_conv_kernel -> w in LDS;
+//   3. thread (target, col): 16 rows of w_i from LDS, first forward round, out.
+// y: rows (pc*ystride + yoff + k) hold the special limbs after the inverse tile pass; w [pc][level][N] receives the
+// correction ready for the forward tile pass.  Needs K <= 8, every target below 2^50 and every special prime below
+// 2^60 (the launcher checks).  grid: x = column tile, y = pc.
+constexpr u32 MID_COLS = 32, MID_TG = 8;
+__global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict__ y, u64 *__restrict__ w,
+                                                          const ModConst *__restrict__ mods,
+                                                          const ModFp *__restrict__ modf,
+                                                          const ModFp *__restrict__ modf_dn,
+                                                          const u64 *__restrict__ tw_inv,
+                                                          const double *__restrict__ twf_inv,
+                                                          const u64 *__restrict__ ninv_dn,
+                                                          const double *__restrict__ twf_fwd,
+                                                          const double *__restrict__ dn_matf, u32 level, u32 K, u32 L,
+                                                          u32 ystride, u32 yoff) {
+    constexpr u32 logN = 16, N = 1u << logN;
+    __shared__ u64 ylds[8 * 16 * MID_COLS];
+    __shared__ u64 wlds[MID_TG * 16 * MID_COLS];
+    const u32 tid = threadIdx.x, col = tid & (MID_COLS - 1), grp = tid / MID_COLS;   // grp < 8
+    const u32 c0 = blockIdx.x * MID_COLS + col;
+    const u32 pc = blockIdx.y;
+    if (grp < K) {
+        const u32 gl = L + grp;
+        const u64 *src = y + ((size_t)pc * ystride + yoff + grp) * N;
+        auto load = [&](u32 idx) { return src[idx]; };
+        auto store = [&](u32 idx, u64 v) { ylds[(grp * 16 + (idx >> 12)) * MID_COLS + col] = v; };
+        const ModFp mf = modf_dn[gl];
+        if (mf.ok)
+            pass_a16_body<true>(make_field_fp(mf, twf_inv, gl, logN), c0, load, store);
+        else
+            pass_a16_body<true>(make_field_int(mods, tw_inv, ninv_dn, gl, logN), c0, load, store);
+    }
+    __syncthreads();
+    // the two coefficients (rows 2*grp, 2*grp + 1 of this column) as 20-bit pieces
+    double yp[2][8][3];
+#pragma unroll
+    for (u32 e = 0; e < 2; ++e)
+#pragma unroll
+        for (u32 k = 0; k < 8; ++k) {
+            const u64 v = k < K ? ylds[(k * 16 + 2 * grp + e) * MID_COLS + col] : 0;
+            yp[e][k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
+            yp[e][k][1] =
+                __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
+            yp[e][k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
+        }
+    for (u32 i0 = 0; i0 < level; i0 += MID_TG) {
+        for (u32 t = 0; t < MID_TG && i0 + t < level; ++t) {
+            const u32 i = i0 + t;
+            const double q = modf[i].q, u = modf[i].u;
+            const double *f = dn_matf + (size_t)i * K * 6;
+            double lo[2] = {0.0, 0.0}, hi[2] = {0.0, 0.0};
+#pragma unroll
+            for (u32 k = 0; k < 8; ++k)
+                if (k < K) {
+#pragma unroll
+                    for (u32 a = 0; a < 3; ++a) {
+                        const double f0 = f[(k * 3 + a) * 2 + 0], f1 = f[(k * 3 + a) * 2 + 1];
+#pragma unroll
+                        for (u32 e = 0; e < 2; ++e) {
+                            lo[e] = fma(yp[e][k][a], f0, lo[e]);
+                            hi[e] = fma(yp[e][k][a], f1, hi[e]);
+                        }
+                    }
+                }
+#pragma unroll
+            for (u32 e = 0; e < 2; ++e) {
+                const double tt = hi[e] * 33554432.0;                       // exact: a power of two
+                double v = fma(-rint(tt * u), q, tt) + lo[e];               // |.| < 0.75 q, plus low < 2^51
+                v = fma(-rint(v * u), q, v);                                // |v| <= q/2: what the forward round takes
+                wlds[(t * 16 + 2 * grp + e) * MID_COLS + col] = (u64)__double_as_longlong(v);
+            }
+        }
+        __syncthreads();
+        if (i0 + grp < level) {
+            const u32 i = i0 + grp;
+            const FieldFp ff = make_field_fp(modf[i], twf_fwd, i, logN);
+            u64 *dst = w + ((size_t)pc * level + i) * N;
+            double v[16];
+#pragma unroll
+            for (u32 j = 0; j < 16; ++j) v[j] = __longlong_as_double((long long)wlds[(grp * 16 + j) * MID_COLS + col]);
+            radix16_fwd(ff, v, 0, 0);
+#pragma unroll
+            for (u32 j = 0; j < 16; ++j) dst[j * 4096 + c0] = ff.out(v[j]);
+        }
+        __syncthreads();
+    }
+}
+
+// Whether the fused kernel applies to this parameter set at this level.
+static bool moddown_mid_ok(const ckks_params *p, u32 level) {
+    bool ok = p->logN == 16 && p->dn_fp && p->K <= 8;
+    for (u32 i = 0; i < level; ++i) ok = ok && (p->mod[i] >> 50) == 0;
+    return ok;
+}
+
+static void launch_moddown_mid(const ckks_params *p, const u64 *y, u64 *w, u32 n, u32 level, u32 ystride, u32 yoff,
+                               hipStream_t stream) {
+    hipLaunchKernelGGL(moddown_mid_kernel, dim3(4096 / MID_COLS, n * 2), dim3(256), 0, stream, y, w, p->d_mod, p->d_modf,
+                       p->d_modf_dn, p->d_tw_inv, p->d_twf_inv, p->d_ninv_dn, p->d_twf_fwd, p->d_dn_matf, level, p->K,
+                       p->L, ystride, yoff);
+}
+
 // base conversion P -> q_i of n*2 polynomials; the rows of polynomial pc start at row pc * ystride + yoff of y
 static void launch_moddown_conv(const ckks_params *p, const u64 *y, u64 *w, u32 n, u32 level, u32 ystride, u32 yoff,
                                 hipStream_t stream) {
@@ -743,12 +853,19 @@ int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64
     }
     LimbIds ids;
     for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
-    int rc = launch_ntt(p, d_u, ids, Wl, n * 2 * Wl, true, stream, 3, true);
+    const bool mid = moddown_mid_ok(p, level);      // the column passes of both transforms ride in the conversion
+    int rc = launch_ntt(p, d_u, ids, Wl, n * 2 * Wl, true, stream, mid ? 1 : 3, true);
     if (rc) return rc;
-    launch_moddown_conv(p, d_u, d_w, n, level, Wl, level, stream);
-    CKKS_LAUNCH_CHECK("moddown_conv_kernel");
+    if (mid) {
+        launch_moddown_mid(p, d_u, d_w, n, level, Wl, level, stream);
+        CKKS_LAUNCH_CHECK("moddown_mid_kernel");
+        p->limb_ntts += (u64)n * 2 * level;
+    } else {
+        launch_moddown_conv(p, d_u, d_w, n, level, Wl, level, stream);
+        CKKS_LAUNCH_CHECK("moddown_conv_kernel");
+    }
     for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
-    rc = launch_ntt(p, d_w, ids, level, n * 2 * level, false, stream);
+    rc = launch_ntt(p, d_w, ids, level, n * 2 * level, false, stream, mid ? 2 : 3);
     if (rc) return rc;
     hipLaunchKernelGGL(moddown_final_kernel, dim3(N / KS_THREADS, level, n * 2), dim3(KS_THREADS), 0, stream, pack,
                        d_u, d_w, p->d_mod, p->d_pinv, level, K, p->logN);
@@ -780,16 +897,23 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
                            whole ? p->d_ninv_dn : p->d_ninv, n, level, K, L, beta, p->logN);
         CKKS_LAUNCH_CHECK("ip_intt_kernel");
         p->limb_ntts += (u64)n * 2 * K;
-        for (u32 k = 0; k < K; ++k) ids.id[k] = (uint8_t)(L + k);
-        int rc = launch_ntt(p, y, ids, K, n * 2 * K, true, stream, 2, true);
-        if (rc) return rc;
-        // (a variant with this base conversion fused into the transform's first pass was measured: its 8 strided
-        // reads per residue from L2 made it slower than the two kernels)
-        launch_moddown_conv(p, y, w, n, level, K, 0u, stream);
-        CKKS_LAUNCH_CHECK("moddown_conv_kernel");
-        for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
-        rc = launch_ntt(p, w, ids, level, n * 2 * level, false, stream, 1, false);
-        if (rc) return rc;
+        int rc;
+        if (moddown_mid_ok(p, level)) {
+            // column passes of the inverse transform (special limbs) and of the forward one (correction) inside the
+            // base conversion: one kernel, y read once, w written once
+            launch_moddown_mid(p, y, w, n, level, K, 0u, stream);
+            CKKS_LAUNCH_CHECK("moddown_mid_kernel");
+            p->limb_ntts += (u64)n * 2 * level;
+        } else {
+            for (u32 k = 0; k < K; ++k) ids.id[k] = (uint8_t)(L + k);
+            rc = launch_ntt(p, y, ids, K, n * 2 * K, true, stream, 2, true);
+            if (rc) return rc;
+            launch_moddown_conv(p, y, w, n, level, K, 0u, stream);
+            CKKS_LAUNCH_CHECK("moddown_conv_kernel");
+            for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
+            rc = launch_ntt(p, w, ids, level, n * 2 * level, false, stream, 1, false);
+            if (rc) return rc;
+        }
         hipLaunchKernelGGL(passb_final_kernel, dim3(tiles, n * 2 * level), dim3(NTT_THREADS), 0, stream, pack, w,
                            p->d_mod, p->d_modf, p->d_tw_fwd, p->d_twf_fwd, p->d_ninv, p->d_pinv, n, level, K, L, beta,
                            p->alpha, p->logN);
