@@ -73,6 +73,12 @@ struct ckks_params {
     ckks::u64 *d_ninv = nullptr;       // [W][2]: N^-1 and N^-1 * psi^-(N/2), Montgomery form
     ckks::ModFp *d_modf = nullptr;     // [W]
     ckks::u64 *d_ninv_dn = nullptr;    // like d_ninv, special limbs scaled by (P/p_k)^-1
+    // the same constants for the lazy integer butterflies of the two-pass kernels (N = 2^12, 2^16): plain values paired
+    // with their quotients floor(w * 2^64 / q); rows of limbs below 2^50 (fp64 butterflies) are left zero
+    ckks::u64 *d_tws_fwd = nullptr;    // [W][N][2]
+    ckks::u64 *d_tws_inv = nullptr;    // [W][N][2]
+    ckks::u64 *d_ninvs = nullptr;      // [W][4]
+    ckks::u64 *d_ninvs_dn = nullptr;   // [W][4], special limbs scaled by (P/p_k)^-1
     ckks::ModFp *d_modf_dn = nullptr;  // like d_modf, special limbs scaled by (P/p_k)^-1
     double *d_twf_fwd = nullptr;       // [W][N]: psi^bitrev(idx) as a double (limbs below 2^50 only)
     double *d_twf_inv = nullptr;       // [W][N]

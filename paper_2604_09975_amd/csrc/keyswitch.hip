@@ -415,8 +415,9 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
                                                           const double *__restrict__ dn_matf, u32 level, u32 K, u32 L,
                                                           u32 ystride, u32 yoff) {
     constexpr u32 logN = 16, N = 1u << logN;
+    static_assert(MID_TG == 8, "the correction tiles reuse the 8 rows of special-limb tiles");
     __shared__ u64 ylds[8 * 16 * MID_COLS];
-    __shared__ u64 wlds[MID_TG * 16 * MID_COLS];
+    u64 *wlds = ylds;               // y lives in registers (as pieces) once step 2 has read it: the same 32 KiB
     const u32 tid = threadIdx.x, col = tid & (MID_COLS - 1), grp = tid / MID_COLS;   // grp < 8
     const u32 c0 = blockIdx.x * MID_COLS + col;
     const u32 pc = blockIdx.y;
@@ -432,41 +433,42 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
             pass_a16_body<true>(make_field_int(mods, tw_inv, ninv_dn, gl, logN), c0, load, store);
     }
     __syncthreads();
-    // the two coefficients (rows 2*grp, 2*grp + 1 of this column) as 20-bit pieces
-    double yp[2][8][3];
+    // the two coefficients of this thread (rows 2*grp, 2*grp + 1 of this column) leave LDS as they are; their
+    // 20-bit pieces are rebuilt per group of targets, one coefficient at a time (24 doubles live instead of 96)
+    u64 yraw[2][8];
 #pragma unroll
     for (u32 e = 0; e < 2; ++e)
 #pragma unroll
-        for (u32 k = 0; k < 8; ++k) {
-            const u64 v = k < K ? ylds[(k * 16 + 2 * grp + e) * MID_COLS + col] : 0;
-            yp[e][k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
-            yp[e][k][1] =
-                __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
-            yp[e][k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
-        }
+        for (u32 k = 0; k < 8; ++k) yraw[e][k] = k < K ? ylds[(k * 16 + 2 * grp + e) * MID_COLS + col] : 0;
+    __syncthreads();                // every thread has its y: the tile may be overwritten
     for (u32 i0 = 0; i0 < level; i0 += MID_TG) {
-        for (u32 t = 0; t < MID_TG && i0 + t < level; ++t) {
-            const u32 i = i0 + t;
-            const double q = modf[i].q, u = modf[i].u;
-            const double *f = dn_matf + (size_t)i * K * 6;
-            double lo[2] = {0.0, 0.0}, hi[2] = {0.0, 0.0};
+#pragma unroll 1
+        for (u32 e = 0; e < 2; ++e) {
+            double yp[8][3];
 #pragma unroll
-            for (u32 k = 0; k < 8; ++k)
-                if (k < K) {
+            for (u32 k = 0; k < 8; ++k) {
+                const u64 v = e ? yraw[1][k] : yraw[0][k];
+                yp[k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
+                yp[k][1] =
+                    __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
+                yp[k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
+            }
+            for (u32 t = 0; t < MID_TG && i0 + t < level; ++t) {
+                const u32 i = i0 + t;
+                const double q = modf[i].q, u = modf[i].u;
+                const double *f = dn_matf + (size_t)i * K * 6;
+                double lo = 0.0, hi = 0.0;
 #pragma unroll
-                    for (u32 a = 0; a < 3; ++a) {
-                        const double f0 = f[(k * 3 + a) * 2 + 0], f1 = f[(k * 3 + a) * 2 + 1];
+                for (u32 k = 0; k < 8; ++k)
+                    if (k < K) {
 #pragma unroll
-                        for (u32 e = 0; e < 2; ++e) {
-                            lo[e] = fma(yp[e][k][a], f0, lo[e]);
-                            hi[e] = fma(yp[e][k][a], f1, hi[e]);
+                        for (u32 a = 0; a < 3; ++a) {
+                            lo = fma(yp[k][a], f[(k * 3 + a) * 2 + 0], lo);
+                            hi = fma(yp[k][a], f[(k * 3 + a) * 2 + 1], hi);
                         }
                     }
-                }
-#pragma unroll
-            for (u32 e = 0; e < 2; ++e) {
-                const double tt = hi[e] * 33554432.0;                       // exact: a power of two
-                double v = fma(-rint(tt * u), q, tt) + lo[e];               // |.| < 0.75 q, plus low < 2^51
+                const double tt = hi * 33554432.0;                          // exact: a power of two
+                double v = fma(-rint(tt * u), q, tt) + lo;                  // |.| < 0.75 q, plus low < 2^51
                 v = fma(-rint(v * u), q, v);                                // |v| <= q/2: what the forward round takes
                 wlds[(t * 16 + 2 * grp + e) * MID_COLS + col] = (u64)__double_as_longlong(v);
             }
@@ -497,7 +499,7 @@ static bool moddown_mid_ok(const ckks_params *p, u32 level) {
 static void launch_moddown_mid(const ckks_params *p, const u64 *y, u64 *w, u32 n, u32 level, u32 ystride, u32 yoff,
                                hipStream_t stream) {
     hipLaunchKernelGGL(moddown_mid_kernel, dim3(4096 / MID_COLS, n * 2), dim3(256), 0, stream, y, w, p->d_mod, p->d_modf,
-                       p->d_modf_dn, p->d_tw_inv, p->d_twf_inv, p->d_ninv_dn, p->d_twf_fwd, p->d_dn_matf, level, p->K,
+                       p->d_modf_dn, p->d_tws_inv, p->d_twf_inv, p->d_ninvs_dn, p->d_twf_fwd, p->d_dn_matf, level, p->K,
                        p->L, ystride, yoff);
 }
 
@@ -743,7 +745,7 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
     for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
     if (fast_ring(p)) {
         hipLaunchKernelGGL(gather_intt_kernel, dim3(N >> 12, n * level), dim3(NTT_THREADS), 0, stream, src, d_tmp,
-                           p->d_mod, p->d_modf, p->d_tw_inv, p->d_twf_inv, p->d_ninv, level, p->logN);
+                           p->d_mod, p->d_modf, p->d_tws_inv, p->d_twf_inv, p->d_ninvs, level, p->logN);
         CKKS_LAUNCH_CHECK("gather_intt_kernel");
         p->limb_ntts += (u64)n * level;
         rc = launch_ntt(p, d_tmp, ids, level, n * level, true, stream, 2);
@@ -893,8 +895,8 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
         // at N = 2^12 the tile pass is the whole inverse transform and carries the (P/p_k)^-1 scaling itself
         const bool whole = p->logN == 12;
         hipLaunchKernelGGL(ip_intt_kernel, dim3(tiles, n * 2 * K), dim3(NTT_THREADS), 0, stream, pack, y, p->d_mod,
-                           whole ? p->d_modf_dn : p->d_modf, p->d_tw_inv, p->d_twf_inv,
-                           whole ? p->d_ninv_dn : p->d_ninv, n, level, K, L, beta, p->logN);
+                           whole ? p->d_modf_dn : p->d_modf, p->d_tws_inv, p->d_twf_inv,
+                           whole ? p->d_ninvs_dn : p->d_ninvs, n, level, K, L, beta, p->logN);
         CKKS_LAUNCH_CHECK("ip_intt_kernel");
         p->limb_ntts += (u64)n * 2 * K;
         int rc;
@@ -915,7 +917,7 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
             if (rc) return rc;
         }
         hipLaunchKernelGGL(passb_final_kernel, dim3(tiles, n * 2 * level), dim3(NTT_THREADS), 0, stream, pack, w,
-                           p->d_mod, p->d_modf, p->d_tw_fwd, p->d_twf_fwd, p->d_ninv, p->d_pinv, n, level, K, L, beta,
+                           p->d_mod, p->d_modf, p->d_tws_fwd, p->d_twf_fwd, p->d_ninvs, p->d_pinv, n, level, K, L, beta,
                            p->alpha, p->logN);
         CKKS_LAUNCH_CHECK("passb_final_kernel");
         return CKKS_OK;

@@ -130,8 +130,8 @@ template <bool INV, int WHICH>
 static void launch_fast(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, u32 tiles,
                         hipStream_t stream, bool scaled_dn) {
     hipLaunchKernelGGL((ntt_fast_kernel<INV, WHICH>), dim3(tiles, rows), dim3(NTT_THREADS), 0, stream, d_data, p->d_mod,
-                       scaled_dn ? p->d_modf_dn : p->d_modf, INV ? p->d_tw_inv : p->d_tw_fwd,
-                       INV ? p->d_twf_inv : p->d_twf_fwd, scaled_dn ? p->d_ninv_dn : p->d_ninv, ids, n_limbs, p->logN);
+                       scaled_dn ? p->d_modf_dn : p->d_modf, INV ? p->d_tws_inv : p->d_tws_fwd,
+                       INV ? p->d_twf_inv : p->d_twf_fwd, scaled_dn ? p->d_ninvs_dn : p->d_ninvs, ids, n_limbs, p->logN);
 }
 
 int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, bool inverse,

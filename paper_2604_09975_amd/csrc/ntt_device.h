@@ -13,31 +13,51 @@ constexpr u32 NTT_THREADS = 256;
 __device__ __forceinline__ u32 lds_pad(u32 i) { return i ^ ((i >> 4) & 31u); }
 constexpr u32 FAST_LDS_WORDS = 4096;
 
+// Integer butterflies for primes that do not fit the fp64 scheme (the 60-bit special primes): lazy values and
+// twiddles with a precomputed quotient.  A twiddle is the pair (w, w') with w' = floor(w * 2^64 / q); for any 64-bit
+// y, y*w - floor(y*w' / 2^64) * q lies in [0, 2q) and is congruent to y*w: one high product and two low products,
+// no correction step.  Forward values live in [0, 4q), inverse values in [0, 2q) (q < 2^62 keeps 4q in a word);
+// out() brings a value back to [0, q).
+struct TwInt {
+    u64 w, ws;
+};
+
 struct FieldInt {
     typedef u64 T;
-    ModConst m;
-    const u64 *tw;
-    u64 n0, n1;
+    typedef TwInt W;
+    u64 q, q2;
+    const ulonglong2 *tw;
+    TwInt n0, n1;
     __device__ __forceinline__ T in(u64 x) const { return x; }
-    __device__ __forceinline__ u64 out(T x) const { return x; }
+    __device__ __forceinline__ u64 out(T x) const {
+        if (x >= q2) x -= q2;
+        if (x >= q) x -= q;
+        return x;
+    }
     __device__ __forceinline__ u64 bits(T x) const { return x; }
     __device__ __forceinline__ T from_bits(u64 x) const { return x; }
-    __device__ __forceinline__ T twid(u32 idx) const { return tw[idx]; }
-    __device__ __forceinline__ void norm(T &) const {}
-    __device__ __forceinline__ void fwd(T &x, T &y, T w) const {
-        const T v = mont_mul(y, w, m);
-        y = sub_mod(x, v, m.q);
-        x = add_mod(x, v, m.q);
+    __device__ __forceinline__ W twid(u32 idx) const {
+        const ulonglong2 t = tw[idx];
+        return TwInt{t.x, t.y};
     }
-    __device__ __forceinline__ void inv(T &x, T &y, T w) const {
-        const T s = add_mod(x, y, m.q);
-        y = mont_mul(sub_mod(x, y, m.q), w, m);
+    __device__ __forceinline__ void norm(T &) const {}
+    __device__ __forceinline__ T mul(T y, const W &w) const { return y * w.w - mul_hi(y, w.ws) * q; }   // [0, 2q)
+    __device__ __forceinline__ void fwd(T &x, T &y, const W &w) const {
+        if (x >= q2) x -= q2;
+        const T v = mul(y, w);
+        y = x - v + q2;
+        x = x + v;
+    }
+    __device__ __forceinline__ void inv(T &x, T &y, const W &w) const {
+        T s = x + y;
+        if (s >= q2) s -= q2;
+        y = mul(x - y + q2, w);
         x = s;
     }
     __device__ __forceinline__ void inv_last(T &x, T &y) const {
-        const T s = add_mod(x, y, m.q), d = sub_mod(x, y, m.q);
-        x = mont_mul(s, n0, m);
-        y = mont_mul(d, n1, m);
+        const T s = x + y, d = x - y + q2;
+        x = mul(s, n0);
+        y = mul(d, n1);
     }
 };
 
@@ -46,6 +66,7 @@ struct FieldInt {
 // |a| <= 2^52.  Sums stay exact below 2^53.  norm() brings a value back to |x| <= q/2.
 struct FieldFp {
     typedef double T;
+    typedef double W;
     double q, u, n0, n1;
     const double *tw;
     __device__ __forceinline__ T in(u64 x) const {
@@ -98,7 +119,7 @@ __device__ __forceinline__ void radix16_fwd(const F &f, typename F::T (&v)[16], 
         const u32 g = 8u >> t;
 #pragma unroll
         for (u32 k = 0; k < (1u << t); ++k) {
-            const typename F::T w = f.twid((1u << (s0 + t)) + (nb << t) + k);
+            const typename F::W w = f.twid((1u << (s0 + t)) + (nb << t) + k);
 #pragma unroll
             for (u32 i = 0; i < g; ++i) f.fwd(v[k * 2 * g + i], v[k * 2 * g + i + g], w);
         }
@@ -122,7 +143,7 @@ __device__ __forceinline__ void radix16_inv(const F &f, typename F::T (&v)[16], 
         } else {
 #pragma unroll
             for (u32 k = 0; k < (1u << t); ++k) {
-                const typename F::T w = f.twid((1u << (s0 + t)) + (nb << t) + k);
+                const typename F::W w = f.twid((1u << (s0 + t)) + (nb << t) + k);
 #pragma unroll
                 for (u32 i = 0; i < g; ++i) f.inv(v[k * 2 * g + i], v[k * 2 * g + i + g], w);
             }
@@ -239,13 +260,15 @@ __device__ __forceinline__ FieldFp make_field_fp(const ModFp &mf, const double *
     return f;
 }
 
-__device__ __forceinline__ FieldInt make_field_int(const ModConst *mods, const u64 *tw, const u64 *ninv, u32 limb,
+// tws: [W][N] pairs (w, w') as consecutive words, ninvs: [W][4] = N^-1, its quotient, N^-1 psi^-(N/2), its quotient
+__device__ __forceinline__ FieldInt make_field_int(const ModConst *mods, const u64 *tws, const u64 *ninvs, u32 limb,
                                                    u32 logN) {
     FieldInt f;
-    f.m = mods[limb];
-    f.tw = tw + ((size_t)limb << logN);
-    f.n0 = ninv[2 * limb];
-    f.n1 = ninv[2 * limb + 1];
+    f.q = mods[limb].q;
+    f.q2 = 2 * f.q;
+    f.tw = reinterpret_cast<const ulonglong2 *>(tws) + ((size_t)limb << logN);
+    f.n0 = TwInt{ninvs[4 * limb], ninvs[4 * limb + 1]};
+    f.n1 = TwInt{ninvs[4 * limb + 2], ninvs[4 * limb + 3]};
     return f;
 }
 

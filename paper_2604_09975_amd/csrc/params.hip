@@ -105,6 +105,7 @@ static ModConst make_mod(u64 q) {
 }
 
 static u64 to_mont(u64 x, const ModConst &m) { return hmul(x % m.q, m.one, m.q); }
+static u64 shoup(u64 w, u64 q) { return (u64)((((wide)w) << 64) / q); }   // floor(w * 2^64 / q), w < q
 
 template <typename T>
 static int upload(T **dst, const std::vector<T> &src) {
@@ -279,6 +280,12 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     std::vector<double> fwd_f((size_t)W * N, 0.0), inv_f((size_t)W * N, 0.0);
     std::vector<ModFp> modf(W);
     std::vector<u64> ninv_plain((size_t)W * 2);
+    const bool two_pass = logN == 16 || logN == 12;
+    std::vector<u64> fwd_s, inv_s;
+    if (two_pass) {
+        fwd_s.assign((size_t)W * N * 2, 0);
+        inv_s.assign((size_t)W * N * 2, 0);
+    }
     for (u32 i = 0; i < W; ++i) {
         const ModConst &m = P->hmod[i];
         pw[0] = 1;
@@ -308,7 +315,22 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
                 fwd_f[(size_t)i * N + idx] = (double)pw[e];
                 inv_f[(size_t)i * N + idx] = (double)pw[2 * N - e];
             }
+        else if (two_pass)
+            for (u32 idx = 1; idx < N; ++idx) {
+                u32 e = bitrev(idx, logN);
+                const size_t o = ((size_t)i * N + idx) * 2;
+                fwd_s[o] = pw[e];
+                fwd_s[o + 1] = shoup(pw[e], m.q);
+                inv_s[o] = pw[2 * N - e];
+                inv_s[o + 1] = shoup(pw[2 * N - e], m.q);
+            }
     }
+    std::vector<u64> ninvs((size_t)W * 4);
+    for (u32 i = 0; i < W; ++i)
+        for (u32 z = 0; z < 2; ++z) {
+            ninvs[4 * i + 2 * z] = ninv_plain[2 * i + z];
+            ninvs[4 * i + 2 * z + 1] = shoup(ninv_plain[2 * i + z], mod[i]);
+        }
     std::vector<u64> dn_inv(K), dn_mat((size_t)K * L), pinv(L), qlinv((size_t)L * L, 0);
     std::vector<double> dn_matf((size_t)L * K * 6, 0.0);
     for (u32 k = 0; k < K; ++k) {
@@ -342,7 +364,7 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     }
     // INTT constants of the special limbs with (P/p_k)^-1 folded in: the ModDown of a key switch then reads
     // y_k = INTT(u_{p_k}) * (P/p_k)^-1 straight from the transform
-    std::vector<u64> ninv_dn = ninv;
+    std::vector<u64> ninv_dn = ninv, ninvs_dn = ninvs;
     std::vector<ModFp> modf_dn = modf;
     for (u32 k = 0; k < K; ++k) {
         const ModConst &m = P->hmod[L + k];
@@ -353,6 +375,10 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
         u64 n0 = hmul(ninv_plain[2 * (L + k)], f, pk), n1 = hmul(ninv_plain[2 * (L + k) + 1], f, pk);
         ninv_dn[2 * (L + k)] = to_mont(n0, m);
         ninv_dn[2 * (L + k) + 1] = to_mont(n1, m);
+        ninvs_dn[4 * (L + k)] = n0;
+        ninvs_dn[4 * (L + k) + 1] = shoup(n0, pk);
+        ninvs_dn[4 * (L + k) + 2] = n1;
+        ninvs_dn[4 * (L + k) + 3] = shoup(n1, pk);
         modf_dn[L + k].ninv = (double)n0;
         modf_dn[L + k].ninv_w = (double)n1;
     }
@@ -370,6 +396,10 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     if (!rc) rc = upload(&P->d_dn_matf, dn_matf);
     if (!rc) rc = upload(&P->d_pinv, pinv);
     if (!rc) rc = upload(&P->d_qlinv, qlinv);
+    if (!rc) rc = upload(&P->d_tws_fwd, fwd_s);
+    if (!rc) rc = upload(&P->d_tws_inv, inv_s);
+    if (!rc) rc = upload(&P->d_ninvs, ninvs);
+    if (!rc) rc = upload(&P->d_ninvs_dn, ninvs_dn);
     for (u32 level = 1; !rc && level <= L && K; ++level) rc = P->build_level_tables(level);
     // scratch for every call whose need is known from the parameter set alone: a full batch of hoisted key switches
     // at the top level (ckks_rotate_hoisted with any number of steps, ckks_ctmul, ckks_rot_first, the key holder's
@@ -423,6 +453,10 @@ void ckks_params_destroy(ckks_params_t *P) {
     hipFree(P->d_dn_matf);
     hipFree(P->d_pinv);
     hipFree(P->d_qlinv);
+    hipFree(P->d_tws_fwd);
+    hipFree(P->d_tws_inv);
+    hipFree(P->d_ninvs);
+    hipFree(P->d_ninvs_dn);
     for (auto &kv : P->levels) {
         hipFree(kv.second.d_up_inv);
         hipFree(kv.second.d_up_mat);
