@@ -58,6 +58,10 @@ struct LevelTables {
     u64 *d_up_inv = nullptr;   // [level]: ((Q_D/q_i)^-1 mod q_i), Montgomery form, D = digit of i
     u64 *d_up_mat = nullptr;   // [level][level+K]: (Q_D/q_i mod t), Montgomery form w.r.t. t; 0 for t in D
     u64 *d_up_matf = nullptr;  // the same factors as doubles (bit patterns), for the conversions done in fp64
+    // for the fused decomposition kernel (N = 2^16, every active prime below 2^50):
+    ModFp *d_modf_up = nullptr;   // [level]: the limb's ModFp with (Q_D/q_i)^-1 folded into the inverse transform's N^-1
+    double *d_up_mats = nullptr;  // [beta][K][8][2][3]: (Q_D/q_i) 2^(25b) 2^64 mod p_k cut into three 20-bit parts
+    double *d_up_ft = nullptr;    // [beta][level+K][8]: (Q_D/q_i) mod q_t for the ciphertext-prime targets t
 };
 
 }  // namespace ckks
@@ -67,6 +71,7 @@ struct ckks_params {
     int device = 0;
     std::vector<ckks::u64> mod, psi;
     std::vector<ckks::ModConst> hmod;
+    std::vector<ckks::u64> hninv;      // [W][2]: N^-1 and N^-1 * psi^-(N/2) as plain residues
     ckks::ModConst *d_mod = nullptr;   // [W]
     ckks::u64 *d_tw_fwd = nullptr;     // [W][N]: psi^bitrev(idx), Montgomery form, idx in [1, N)
     ckks::u64 *d_tw_inv = nullptr;     // [W][N]: psi^-bitrev(idx), Montgomery form

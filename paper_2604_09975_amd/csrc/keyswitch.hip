@@ -170,6 +170,141 @@ __global__ __launch_bounds__(KS_THREADS) void modup_kernel(const u64 *__restrict
     }
 }
 
+// Decomposition between the two tile passes at N = 2^16, one kernel instead of four.  The last 4 stages of the
+// inverse transform of c1, the base conversion of every digit (ModUp) and the first 4 stages of the forward transform
+// of the extended rows all work on columns (residues 4096 apart); a workgroup owns UP_COLS columns of one digit of one
+// ciphertext:
+//   1. thread (a, col): column col of limb lo + a of the digit, 16 rows in registers, last inverse round with
+//      N^-1 (Q_D/q_i)^-1 folded in -> y_a in LDS;
+//   2. thread (row pair, col): for each group of UP_TG targets and each of its two coefficients: targets among the
+//      ciphertext primes as the exact fp64 sums of modup_kernel; targets among the special primes from 25-bit pieces
+//      of y and 20-bit parts of the factors (48 exact fp64 multiply-adds, then one Montgomery reduction of the
+//      recombined 90-bit sum) -> LDS;
+//   3. thread (target, col): 16 rows from LDS, first forward round (fp64 or integer butterflies), out.
+// c1_half [n][level][N]: c1 after the inverse tile pass; digits [n][beta][level+K][N]: rows of targets outside the
+// digit, ready for the forward tile pass.  Needs alpha, K <= 8, every active ciphertext prime below 2^50 and every
+// special prime below 2^60 (the launcher checks).  grid: x = column tile, y = digit, z = ciphertext.
+constexpr u32 UP_COLS = 32, UP_TG = 8;
+__global__ __launch_bounds__(256) void modup_mid_kernel(const u64 *__restrict__ c1_half, u64 *__restrict__ digits,
+                                                        const ModConst *__restrict__ mods,
+                                                        const ModFp *__restrict__ modf,
+                                                        const ModFp *__restrict__ modf_up,
+                                                        const double *__restrict__ twf_inv,
+                                                        const double *__restrict__ twf_fwd,
+                                                        const u64 *__restrict__ tws_fwd,
+                                                        const u64 *__restrict__ ninvs,
+                                                        const double *__restrict__ up_ft,
+                                                        const double *__restrict__ up_mats, u32 level, u32 K, u32 L,
+                                                        u32 alpha, u32 beta) {
+    constexpr u32 logN = 16, N = 1u << logN;
+    static_assert(UP_TG == 8, "the target tiles reuse the 8 rows of source tiles");
+    __shared__ u64 ylds[8 * 16 * UP_COLS];
+    u64 *wlds = ylds;               // the sources live in registers once step 2 has read them: the same 32 KiB
+    const u32 tid = threadIdx.x, col = tid & (UP_COLS - 1), grp = tid / UP_COLS;   // grp < 8
+    const u32 c0 = blockIdx.x * UP_COLS + col;
+    const u32 j = blockIdx.y, r = blockIdx.z;
+    const u32 Wl = level + K;
+    const u32 lo = j * alpha, hi = min(lo + alpha, level), nd = hi - lo;
+    if (grp < nd) {
+        const u32 i = lo + grp;
+        const u64 *src = c1_half + ((size_t)r * level + i) * N;
+        auto load = [&](u32 idx) { return src[idx]; };
+        auto store = [&](u32 idx, u64 v) { ylds[(grp * 16 + (idx >> 12)) * UP_COLS + col] = v; };
+        pass_a16_body<true>(make_field_fp(modf_up[i], twf_inv, i, logN), c0, load, store);
+    }
+    __syncthreads();
+    u64 yraw[2][8];
+#pragma unroll
+    for (u32 e = 0; e < 2; ++e)
+#pragma unroll
+        for (u32 a = 0; a < 8; ++a) yraw[e][a] = a < nd ? ylds[(a * 16 + 2 * grp + e) * UP_COLS + col] : 0;
+    __syncthreads();                // every thread has its y: the tile may be overwritten
+    u64 *dig = digits + ((size_t)r * beta + j) * Wl * N;
+    const u32 nt = Wl - nd;                                          // targets: all rows outside the digit
+    for (u32 u0 = 0; u0 < nt; u0 += UP_TG) {
+#pragma unroll 1
+        for (u32 e = 0; e < 2; ++e) {
+            double yd[8], yp[8][2];
+#pragma unroll
+            for (u32 a = 0; a < 8; ++a) {
+                const u64 v = e ? yraw[1][a] : yraw[0][a];
+                yp[a][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0x1FFFFFFu))) - 4503599627370496.0;
+                yp[a][1] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 25))) - 4503599627370496.0;
+                yd[a] = fma(yp[a][1], 33554432.0, yp[a][0]);         // exact: y < 2^50
+            }
+            for (u32 tt = 0; tt < UP_TG && u0 + tt < nt; ++tt) {
+                const u32 uu = u0 + tt, t = uu < lo ? uu : uu + nd;  // row of the extended basis
+                u64 res;
+                if (t < level) {
+                    // target among the ciphertext primes: every product split exactly into h + l, brought below
+                    // 0.9 q before it is added, the partial sum reduced every four terms
+                    const double q = modf[t].q, u = modf[t].u;
+                    const double *fd = up_ft + ((size_t)j * Wl + t) * 8;   // zero beyond the digit's limbs, as y is
+                    double acc = 0.0;
+#pragma unroll
+                    for (u32 a = 0; a < 8; ++a) {
+                        const double h = yd[a] * fd[a], l = fma(yd[a], fd[a], -h);
+                        acc += fma(-rint(h * u), q, h) + l;
+                        if ((a & 3) == 3) acc = fma(-rint(acc * u), q, acc);
+                    }
+                    acc = fma(-rint(acc * u), q, acc);               // |acc| <= q/2: what the forward round takes
+                    res = (u64)__double_as_longlong(acc);
+                } else {
+                    // target among the special primes: sum_a y_a F_a with F_a 2^64 2^(25b) mod p in 20-bit parts
+                    const u32 k = t - level;
+                    const double *g = up_mats + ((size_t)j * K + k) * 48;   // zero beyond the digit's limbs
+                    double s0 = 0.0, s1 = 0.0, s2 = 0.0;
+#pragma unroll
+                    for (u32 a = 0; a < 8; ++a) {
+#pragma unroll
+                        for (u32 b = 0; b < 2; ++b) {
+                            s0 = fma(yp[a][b], g[(a * 2 + b) * 3 + 0], s0);
+                            s1 = fma(yp[a][b], g[(a * 2 + b) * 3 + 1], s1);
+                            s2 = fma(yp[a][b], g[(a * 2 + b) * 3 + 2], s2);
+                        }
+                    }
+                    // each sum is an exact integer below 2^49; s0 + s1 2^20 + s2 2^40 < 2^90 as a 128-bit number
+                    const u64 i0 = (u64)__double_as_longlong(s0 + 4503599627370496.0) & 0x000fffffffffffffull;
+                    const u64 i1 = (u64)__double_as_longlong(s1 + 4503599627370496.0) & 0x000fffffffffffffull;
+                    const u64 i2 = (u64)__double_as_longlong(s2 + 4503599627370496.0) & 0x000fffffffffffffull;
+                    u128 acc;
+                    acc.lo = i0;
+                    acc.hi = 0;
+                    acc_add(acc, u128{i1 << 20, i1 >> 44});
+                    acc_add(acc, u128{i2 << 40, i2 >> 24});
+                    res = redc_wide(acc, mods[L + k]);               // canonical: the factors carry 2^64
+                }
+                wlds[(tt * 16 + 2 * grp + e) * UP_COLS + col] = res;
+            }
+        }
+        __syncthreads();
+        if (u0 + grp < nt) {
+            const u32 uu = u0 + grp, t = uu < lo ? uu : uu + nd;
+            const u32 gl = t < level ? t : L + (t - level);
+            u64 *dst = dig + (size_t)t * N;
+            const ModFp mf = modf[gl];
+            if (t < level) {
+                const FieldFp ff = make_field_fp(mf, twf_fwd, gl, logN);
+                double v[16];
+#pragma unroll
+                for (u32 jj = 0; jj < 16; ++jj)
+                    v[jj] = __longlong_as_double((long long)wlds[(grp * 16 + jj) * UP_COLS + col]);
+                radix16_fwd(ff, v, 0, 0);
+#pragma unroll
+                for (u32 jj = 0; jj < 16; ++jj) dst[jj * 4096 + c0] = ff.out(v[jj]);
+            } else {
+                auto load = [&](u32 idx) { return wlds[(grp * 16 + (idx >> 12)) * UP_COLS + col]; };
+                auto store = [&](u32 idx, u64 v) { dst[idx] = v; };
+                if (mf.ok)
+                    pass_a16_body<false>(make_field_fp(mf, twf_fwd, gl, logN), c0, load, store);
+                else
+                    pass_a16_body<false>(make_field_int(mods, tws_fwd, ninvs, gl, logN), c0, load, store);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 constexpr u32 MAX_BETA = 4;    // digits the fused kernels unroll (larger dnum uses the plain kernels)
 constexpr u32 EPI = 4;         // residues whose loads are issued together in the fused kernels
 constexpr u32 KEY_GROUP = 4;   // key switches that share one key are served by one thread
@@ -403,7 +538,11 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64 *__r
 // y: rows (pc*ystride + yoff + k) hold the special limbs after the inverse tile pass; w [pc][level][N] receives the
 // correction ready for the forward tile pass.  Needs K <= 8, every target below 2^50 and every special prime below
 // 2^60 (the launcher checks).  grid: x = column tile, y = pc.
-constexpr u32 MID_COLS = 32, MID_TG = 8;
+constexpr u32 MID_COLS = 32, MID_TG = 8, MID_MAX_LEVEL = 32;
+// K8: exactly 8 special primes: no per-prime checks in the conversion loop, so a target's 48 factors arrive through the
+// scalar cache in one burst (with the checks the wave waited for each prime's six in turn).  Staging the factors in
+// LDS instead was measured slower: broadcast reads still take an LDS issue slot per pair of multiply-adds.
+template <bool K8>
 __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict__ y, u64 *__restrict__ w,
                                                           const ModConst *__restrict__ mods,
                                                           const ModFp *__restrict__ modf,
@@ -417,7 +556,7 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
     constexpr u32 logN = 16, N = 1u << logN;
     static_assert(MID_TG == 8, "the correction tiles reuse the 8 rows of special-limb tiles");
     __shared__ u64 ylds[8 * 16 * MID_COLS];
-    u64 *wlds = ylds;               // y lives in registers (as pieces) once step 2 has read it: the same 32 KiB
+    u64 *wlds = ylds;               // y lives in registers once step 2 has read it: the same 32 KiB
     const u32 tid = threadIdx.x, col = tid & (MID_COLS - 1), grp = tid / MID_COLS;   // grp < 8
     const u32 c0 = blockIdx.x * MID_COLS + col;
     const u32 pc = blockIdx.y;
@@ -439,36 +578,42 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
 #pragma unroll
     for (u32 e = 0; e < 2; ++e)
 #pragma unroll
-        for (u32 k = 0; k < 8; ++k) yraw[e][k] = k < K ? ylds[(k * 16 + 2 * grp + e) * MID_COLS + col] : 0;
+        for (u32 k = 0; k < 8; ++k) yraw[e][k] = (K8 || k < K) ? ylds[(k * 16 + 2 * grp + e) * MID_COLS + col] : 0;
     __syncthreads();                // every thread has its y: the tile may be overwritten
+    double yp[2][8][3];
+#pragma unroll
+    for (u32 e = 0; e < 2; ++e)
+#pragma unroll
+        for (u32 k = 0; k < 8; ++k) {
+            const u64 v = yraw[e][k];
+            yp[e][k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
+            yp[e][k][1] =
+                __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
+            yp[e][k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
+        }
     for (u32 i0 = 0; i0 < level; i0 += MID_TG) {
-#pragma unroll 1
-        for (u32 e = 0; e < 2; ++e) {
-            double yp[8][3];
+        for (u32 t = 0; t < MID_TG && i0 + t < level; ++t) {
+            const u32 i = i0 + t;
+            const double q = modf[i].q, u = modf[i].u;
+            const double *f = dn_matf + (size_t)i * K * 6;
+            double lo[2] = {0.0, 0.0}, hi[2] = {0.0, 0.0};
 #pragma unroll
-            for (u32 k = 0; k < 8; ++k) {
-                const u64 v = e ? yraw[1][k] : yraw[0][k];
-                yp[k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
-                yp[k][1] =
-                    __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
-                yp[k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
-            }
-            for (u32 t = 0; t < MID_TG && i0 + t < level; ++t) {
-                const u32 i = i0 + t;
-                const double q = modf[i].q, u = modf[i].u;
-                const double *f = dn_matf + (size_t)i * K * 6;
-                double lo = 0.0, hi = 0.0;
+            for (u32 k = 0; k < 8; ++k)
+                if (K8 || k < K) {
 #pragma unroll
-                for (u32 k = 0; k < 8; ++k)
-                    if (k < K) {
+                    for (u32 a = 0; a < 3; ++a) {
+                        const double f0 = f[(k * 3 + a) * 2 + 0], f1 = f[(k * 3 + a) * 2 + 1];
 #pragma unroll
-                        for (u32 a = 0; a < 3; ++a) {
-                            lo = fma(yp[k][a], f[(k * 3 + a) * 2 + 0], lo);
-                            hi = fma(yp[k][a], f[(k * 3 + a) * 2 + 1], hi);
+                        for (u32 e = 0; e < 2; ++e) {
+                            lo[e] = fma(yp[e][k][a], f0, lo[e]);
+                            hi[e] = fma(yp[e][k][a], f1, hi[e]);
                         }
                     }
-                const double tt = hi * 33554432.0;                          // exact: a power of two
-                double v = fma(-rint(tt * u), q, tt) + lo;                  // |.| < 0.75 q, plus low < 2^51
+                }
+#pragma unroll
+            for (u32 e = 0; e < 2; ++e) {
+                const double tt = hi[e] * 33554432.0;                       // exact: a power of two
+                double v = fma(-rint(tt * u), q, tt) + lo[e];               // |.| < 0.75 q, plus low < 2^51
                 v = fma(-rint(v * u), q, v);                                // |v| <= q/2: what the forward round takes
                 wlds[(t * 16 + 2 * grp + e) * MID_COLS + col] = (u64)__double_as_longlong(v);
             }
@@ -491,16 +636,21 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
 
 // Whether the fused kernel applies to this parameter set at this level.
 static bool moddown_mid_ok(const ckks_params *p, u32 level) {
-    bool ok = p->logN == 16 && p->dn_fp && p->K <= 8;
+    bool ok = p->logN == 16 && p->dn_fp && p->K <= 8 && level <= MID_MAX_LEVEL;
     for (u32 i = 0; i < level; ++i) ok = ok && (p->mod[i] >> 50) == 0;
     return ok;
 }
 
 static void launch_moddown_mid(const ckks_params *p, const u64 *y, u64 *w, u32 n, u32 level, u32 ystride, u32 yoff,
                                hipStream_t stream) {
-    hipLaunchKernelGGL(moddown_mid_kernel, dim3(4096 / MID_COLS, n * 2), dim3(256), 0, stream, y, w, p->d_mod, p->d_modf,
-                       p->d_modf_dn, p->d_tws_inv, p->d_twf_inv, p->d_ninvs_dn, p->d_twf_fwd, p->d_dn_matf, level, p->K,
-                       p->L, ystride, yoff);
+    if (p->K == 8)
+        hipLaunchKernelGGL(moddown_mid_kernel<true>, dim3(4096 / MID_COLS, n * 2), dim3(256), 0, stream, y, w, p->d_mod,
+                           p->d_modf, p->d_modf_dn, p->d_tws_inv, p->d_twf_inv, p->d_ninvs_dn, p->d_twf_fwd,
+                           p->d_dn_matf, level, p->K, p->L, ystride, yoff);
+    else
+        hipLaunchKernelGGL(moddown_mid_kernel<false>, dim3(4096 / MID_COLS, n * 2), dim3(256), 0, stream, y, w, p->d_mod,
+                           p->d_modf, p->d_modf_dn, p->d_tws_inv, p->d_twf_inv, p->d_ninvs_dn, p->d_twf_fwd,
+                           p->d_dn_matf, level, p->K, p->L, ystride, yoff);
 }
 
 // base conversion P -> q_i of n*2 polynomials; the rows of polynomial pc start at row pc * ystride + yoff of y
@@ -743,11 +893,31 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
     for (u32 r = 0; r < ROT_BATCH; ++r) src.p[r] = c1[r < n ? r : 0];
     LimbIds ids;
     for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)i;
+    bool all_fp = true;
+    for (u32 i = 0; i < level; ++i) all_fp = all_fp && (p->mod[i] >> 50) == 0;
+    bool sp60 = true;
+    for (u32 k = 0; k < K; ++k) sp60 = sp60 && (p->mod[L + k] >> 60) == 0;
     if (fast_ring(p)) {
         hipLaunchKernelGGL(gather_intt_kernel, dim3(N >> 12, n * level), dim3(NTT_THREADS), 0, stream, src, d_tmp,
                            p->d_mod, p->d_modf, p->d_tws_inv, p->d_twf_inv, p->d_ninvs, level, p->logN);
         CKKS_LAUNCH_CHECK("gather_intt_kernel");
         p->limb_ntts += (u64)n * level;
+        if (p->logN == 16 && all_fp && sp60 && alpha <= 8 && K <= 8) {
+            // the column passes of both transforms ride in the base conversion: c1 read once, digits written once
+            hipLaunchKernelGGL(modup_mid_kernel, dim3(4096 / UP_COLS, beta, n), dim3(256), 0, stream, d_tmp, d_digits,
+                               p->d_mod, p->d_modf, lt->d_modf_up, p->d_twf_inv, p->d_twf_fwd, p->d_tws_fwd, p->d_ninvs,
+                               lt->d_up_ft, lt->d_up_mats, level, K, L, alpha, beta);
+            CKKS_LAUNCH_CHECK("modup_mid_kernel");
+            p->limb_ntts += (u64)n * beta * Wl - (u64)n * level;
+            auto row_id2 = [&](u32 j, u32 t) -> uint8_t {
+                u32 lo = j * alpha, hi = std::min(lo + alpha, level);
+                if (t >= lo && t < hi) return (uint8_t)SKIP_ROW;
+                return (uint8_t)(t < level ? t : L + (t - level));
+            };
+            for (u32 j = 0; j < beta; ++j)
+                for (u32 t = 0; t < Wl; ++t) ids.id[j * Wl + t] = row_id2(j, t);
+            return launch_ntt(p, d_digits, ids, beta * Wl, n * beta * Wl, false, stream, 2);
+        }
         rc = launch_ntt(p, d_tmp, ids, level, n * level, true, stream, 2);
     } else {
         hipLaunchKernelGGL(gather_c1_kernel, dim3(N / KS_THREADS, level, n), dim3(KS_THREADS), 0, stream, src, d_tmp,
@@ -758,8 +928,6 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
     if (rc) return rc;
     // two launches: the ciphertext-prime targets (fp64 arithmetic when every active prime is below 2^50) and the
     // special-prime targets (integer arithmetic); each keeps only its own form of y in registers
-    bool all_fp = true;
-    for (u32 i = 0; i < level; ++i) all_fp = all_fp && (p->mod[i] >> 50) == 0;
 #define MODUP_LAUNCH(A, FPK, T0, T1)                                                                               \
     hipLaunchKernelGGL((modup_kernel<A, 2, FPK>), dim3(N / KS_THREADS / 2, beta, n), dim3(KS_THREADS), 0, stream,   \
                        d_tmp, d_digits, p->d_mod, p->d_modf, lt->d_up_inv, lt->d_up_mat, lt->d_up_matf, level, K,   \

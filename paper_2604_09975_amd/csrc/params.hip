@@ -178,11 +178,53 @@ int ckks_params::build_level_tables(u32 level) {
             std::memcpy(&matf[(size_t)i * Wl + t2], &fd, sizeof fd);
         }
     }
+    // tables of the fused decomposition kernel
+    std::vector<ModFp> modf_up(level);
+    // per digit j and target row t (k for the special rows): the factors of the digit's up to 8 source limbs side
+    // by side, zero where the digit is shorter (alpha above 8 does not use these tables)
+    std::vector<double> mats((size_t)t.beta * K * 48, 0.0), ft((size_t)t.beta * Wl * 8, 0.0);
+    for (u32 i = 0; i < level; ++i) {
+        u32 lo = (i / alpha) * alpha, hi = std::min(lo + alpha, level);
+        u64 qi = mod[i], prod = 1;
+        for (u32 b = lo; b < hi; ++b)
+            if (b != i) prod = hmul(prod, mod[b] % qi, qi);
+        const u64 invp = hinv(prod, qi);
+        ModFp f;
+        f.q = (double)qi;
+        f.u = 1.0 / (double)qi;
+        f.ninv = (double)hmul(hninv[2 * i], invp, qi);
+        f.ninv_w = (double)hmul(hninv[2 * i + 1], invp, qi);
+        f.ok = (qi >> 50) == 0;
+        f.pad = 0;
+        modf_up[i] = f;
+        const u32 dj = i / alpha, da = i - lo;
+        if (da >= 8) continue;
+        for (u32 k = 0; k < K; ++k) {
+            u64 pk = mod[L + k], fk = 1;
+            for (u32 b = lo; b < hi; ++b)
+                if (b != i) fk = hmul(fk, mod[b] % pk, pk);
+            for (u32 b = 0; b < 2; ++b) {
+                u64 g = hmul(hmul(fk, hpow(2, 25 * b, pk), pk), hmod[L + k].one, pk);
+                for (u32 c = 0; c < 3; ++c)
+                    mats[((((size_t)dj * K + k) * 8 + da) * 2 + b) * 3 + c] = (double)((g >> (20 * c)) & 0xFFFFFu);
+            }
+        }
+        for (u32 t2 = 0; t2 < level; ++t2) {
+            if (t2 >= lo && t2 < hi) continue;
+            u64 mt = mod[t2], fq = 1;
+            for (u32 b = lo; b < hi; ++b)
+                if (b != i) fq = hmul(fq, mod[b] % mt, mt);
+            ft[((size_t)dj * Wl + t2) * 8 + da] = (double)fq;       // exact below 2^53; used for targets below 2^50
+        }
+    }
     // entered into the map first, so that ckks_params_destroy frees whatever part was uploaded if a later part fails
     LevelTables &slot = levels.emplace(level, t).first->second;
     int rc = upload(&slot.d_up_inv, inv);
     if (!rc) rc = upload(&slot.d_up_mat, mat);
     if (!rc) rc = upload(&slot.d_up_matf, matf);
+    if (!rc) rc = upload(&slot.d_modf_up, modf_up);
+    if (!rc) rc = upload(&slot.d_up_mats, mats);
+    if (!rc) rc = upload(&slot.d_up_ft, ft);
     return rc;
 }
 
@@ -331,6 +373,7 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
             ninvs[4 * i + 2 * z] = ninv_plain[2 * i + z];
             ninvs[4 * i + 2 * z + 1] = shoup(ninv_plain[2 * i + z], mod[i]);
         }
+    P->hninv = ninv_plain;
     std::vector<u64> dn_inv(K), dn_mat((size_t)K * L), pinv(L), qlinv((size_t)L * L, 0);
     std::vector<double> dn_matf((size_t)L * K * 6, 0.0);
     for (u32 k = 0; k < K; ++k) {
@@ -461,6 +504,9 @@ void ckks_params_destroy(ckks_params_t *P) {
         hipFree(kv.second.d_up_inv);
         hipFree(kv.second.d_up_mat);
         hipFree(kv.second.d_up_matf);
+        hipFree(kv.second.d_modf_up);
+        hipFree(kv.second.d_up_mats);
+        hipFree(kv.second.d_up_ft);
     }
     hipFree(P->d_fft_w);
     hipFree(P->d_fft_twist);
