@@ -98,7 +98,10 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_pass_kernel(u64 *__restrict__
 
 
 // which: 0 = pass A (N = 2^16: first / last 4 stages, registers only), 2 = pass B (12 stages in a 4096 tile)
-template <bool INV, int WHICH>
+// FP: the kernel serves the rows whose prime is below 2^50 (fp64 butterflies) or the others (integer butterflies);
+// rows of the other kind return at once.  One kernel for both kinds would carry the larger register budget of the
+// integer path into every row (3 instead of 5 waves per SIMD in pass B).
+template <bool INV, int WHICH, bool FP>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__ data,
                                                                const ModConst *__restrict__ mods,
                                                                const ModFp *__restrict__ modf,
@@ -110,12 +113,13 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__
     const u32 row = blockIdx.y;
     const u32 limb = ids.id[row % n_limbs];
     if (limb == SKIP_ROW) return;
-    u64 *poly = data + ((size_t)row << logN);
     const ModFp mf = modf[limb];
+    if ((mf.ok != 0) != FP) return;
+    u64 *poly = data + ((size_t)row << logN);
     auto load = [&](u32 idx) { return poly[idx]; };
     auto store = [&](u32 idx, u64 v) { poly[idx] = v; };
     const u32 col = blockIdx.x * NTT_THREADS + threadIdx.x;
-    if (mf.ok) {
+    if (FP) {
         const FieldFp f = make_field_fp(mf, twf, limb, logN);
         if (WHICH == 0) pass_a16_body<INV>(f, col, load, store);
         if (WHICH == 2) pass_b_body<INV>(f, logN, lds, load, store);
@@ -129,9 +133,22 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__
 template <bool INV, int WHICH>
 static void launch_fast(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, u32 tiles,
                         hipStream_t stream, bool scaled_dn) {
-    hipLaunchKernelGGL((ntt_fast_kernel<INV, WHICH>), dim3(tiles, rows), dim3(NTT_THREADS), 0, stream, d_data, p->d_mod,
-                       scaled_dn ? p->d_modf_dn : p->d_modf, INV ? p->d_tws_inv : p->d_tws_fwd,
-                       INV ? p->d_twf_inv : p->d_twf_fwd, scaled_dn ? p->d_ninvs_dn : p->d_ninvs, ids, n_limbs, p->logN);
+    bool any_fp = false, any_int = false;
+    for (u32 i = 0; i < n_limbs; ++i) {
+        if (ids.id[i] == SKIP_ROW) continue;
+        if ((p->mod[ids.id[i]] >> 50) == 0)
+            any_fp = true;
+        else
+            any_int = true;
+    }
+#define FAST_LAUNCH(FPK)                                                                                             \
+    hipLaunchKernelGGL((ntt_fast_kernel<INV, WHICH, FPK>), dim3(tiles, rows), dim3(NTT_THREADS), 0, stream, d_data,   \
+                       p->d_mod, scaled_dn ? p->d_modf_dn : p->d_modf, INV ? p->d_tws_inv : p->d_tws_fwd,            \
+                       INV ? p->d_twf_inv : p->d_twf_fwd, scaled_dn ? p->d_ninvs_dn : p->d_ninvs, ids, n_limbs,      \
+                       p->logN)
+    if (any_fp) FAST_LAUNCH(true);
+    if (any_int) FAST_LAUNCH(false);
+#undef FAST_LAUNCH
 }
 
 int launch_ntt(const ckks_params *p, u64 *d_data, const LimbIds &ids, u32 n_limbs, u32 rows, bool inverse,
