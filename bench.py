@@ -271,13 +271,13 @@ def run_gpt2_block(args, B, CL, W, P, cl, emit=True, steps=None):
             n1 = plan.choose_n1(-(-(-(-spec.d_in // spec.C)) // 2), -(-spec.d_out // spec.C), spec.C)
         S = setup_matmul(B, CL, W, P, cl, spec, n1, keys, pairs=args.pair_compression)
         level, B_out = S["level"], S["B_out"]
-        y = torch.empty((B_out, 2, level, P.N), dtype=torch.int64, device="cuda")
         yr = torch.empty((B_out, 2, level - 1, P.N), dtype=torch.int64, device="cuda")
 
         def step():
-            _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y, conj_key=S["conj"],
-                                        flags=0 if args.separate_giant else B.MATMUL_MERGED_GIANT)
-            B.ckks_rescale(P, y, level, B_out, yr)
+            # projection and rescale in one call (CKKS_MATMUL_RESCALE): with the merged giant step the ModDown and the
+            # rescale share one pass over the correction
+            _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], yr, conj_key=S["conj"],
+                                        flags=(0 if args.separate_giant else B.MATMUL_MERGED_GIANT) | B.MATMUL_RESCALE)
             return cnt
 
         for _ in range(args.warmup):
@@ -302,7 +302,7 @@ def run_gpt2_block(args, B, CL, W, P, cl, emit=True, steps=None):
                        "ptmuls": int(cnt.ptmuls), "max_abs_err": err})
         total += ms
         S["w"].close()
-        del S, y, yr
+        del S, yr
         torch.cuda.empty_cache()
     if not emit:
         return {"total_ms": total, "steps": n_steps, "giant_step": GIANT_NAMES[not args.separate_giant],
@@ -573,15 +573,15 @@ def main():
         n1 = plan.choose_n1(-(-(-(-spec.d_in // spec.C)) // 2), -(-spec.d_out // spec.C), spec.C)
     S = setup_matmul(B, CL, W, P, cl, spec, n1, fused_qk=args.fused_qk, pairs=args.pair_compression)
     N, level, B_out, G, N2 = P.N, S["level"], S["B_out"], S["G"], S["N2"]
-    y = torch.empty((B_out, 2, level, N), dtype=torch.int64, device="cuda")
     yr = torch.empty((B_out, 2, level - 1, N), dtype=torch.int64, device="cuda")
 
     merged = not args.separate_giant
 
     def step(merged_giant=merged):
-        _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], y, conj_key=S["conj"],
-                                    flags=B.MATMUL_MERGED_GIANT if merged_giant else 0)
-        B.ckks_rescale(P, y, level, B_out, yr)
+        # projection and rescale in one call (CKKS_MATMUL_RESCALE): the same residues as ckks_ctpt_matmul followed by
+        # ckks_rescale; with the merged giant step the ModDown and the rescale share one pass over the correction
+        _, cnt = B.ckks_ctpt_matmul(P, S["w"], S["ct_x"], S["baby"], S["giant"], yr, conj_key=S["conj"],
+                                    flags=(B.MATMUL_MERGED_GIANT if merged_giant else 0) | B.MATMUL_RESCALE)
         return cnt
 
     for _ in range(args.warmup):
@@ -740,7 +740,7 @@ def main():
     if not args.no_extras and not (args.fused_qk or args.pair_compression or args.n1):
         # the other configurations ride in the same line: free the headline's weights and keys first
         S["w"].close()
-        del S, y, yr, ct
+        del S, yr, ct
         torch.cuda.empty_cache()
         out["ntt"] = run_ntt(args, B, W, emit=False)
         log(f"[bench] ntt: forward {out['ntt']['forward_ms']:.3f} ms, inverse {out['ntt']['inverse_ms']:.3f} ms")

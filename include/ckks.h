@@ -197,6 +197,12 @@ void ckks_weights_destroy(ckks_weights_t *w);
  * diagonal was never stored (the message names the first one): nothing is
  * enqueued then. */
 #define CKKS_MATMUL_MERGED_GIANT 1u /* flags: one ModDown per output block for the whole giant step */
+#define CKKS_MATMUL_RESCALE 2u      /* flags: d_ct_y receives the RESCALED blocks, [B_out][2][level-1][N]: the same
+                                       residues as this call without the flag followed by ckks_rescale.  With
+                                       CKKS_MATMUL_MERGED_GIANT (and no conj_key, N = 2^16, primes below 2^50) the
+                                       ModDown of the giant step and the rescale share one pass: the dropped limb is
+                                       taken in the coefficient domain before the correction's forward transform, so
+                                       each remaining limb is transformed once for both.  CKKS_E_LEVEL at level 1. */
 int ckks_ctpt_matmul(ckks_params_t *params, const ckks_weights_t *w, const uint64_t *d_ct_x,
                      const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys,
                      const ckks_gkey_t *conj_key, uint32_t flags, uint64_t *d_ct_y, ckks_counters_t *counters,

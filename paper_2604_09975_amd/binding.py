@@ -277,6 +277,7 @@ def ckks_weights_load(P, level, m, Cc, G, B_out, N1, d_coeffs, d_bias_coeffs=Non
 
 
 MATMUL_MERGED_GIANT = 1
+MATMUL_RESCALE = 2
 
 
 def ckks_ctpt_matmul(P, w, d_ct_x, baby_keys, giant_keys, d_ct_y=None, conj_key=None, flags=0):
@@ -284,10 +285,11 @@ def ckks_ctpt_matmul(P, w, d_ct_x, baby_keys, giant_keys, d_ct_y=None, conj_key=
         raise ValueError("input must be [G][2][level][N]")
     if len(baby_keys) != w.N1 - 1 or len(giant_keys) != w.N2 - 1:
         raise ValueError("need N1-1 baby keys and N2-1 giant keys")
+    out_level = w.level - 1 if flags & MATMUL_RESCALE else w.level
     if d_ct_y is None:
-        d_ct_y = torch.empty((w.B_out, 2, w.level, P.N), dtype=torch.int64, device=d_ct_x.device)
-    elif d_ct_y.numel() != w.B_out * 2 * w.level * P.N:
-        raise ValueError("output must be [B_out][2][level][N]")
+        d_ct_y = torch.empty((w.B_out, 2, max(out_level, 1), P.N), dtype=torch.int64, device=d_ct_x.device)
+    elif d_ct_y.numel() != w.B_out * 2 * out_level * P.N:
+        raise ValueError("output must be [B_out][2][level][N] ([B_out][2][level-1][N] with MATMUL_RESCALE)")
     cnt = Counters()
     _check(lib.ckks_ctpt_matmul(P.h, w.h, _dev(d_ct_x), _keyarr(baby_keys), _keyarr(giant_keys),
                                 conj_key.h if conj_key is not None else None, flags, _dev(d_ct_y), C.byref(cnt),

@@ -93,6 +93,7 @@ struct ckks_params {
     double *d_dn_matf = nullptr;       // [L][K][3][2]: (2^(20a) * P/p_k) mod q_i as two 25-bit halves (doubles)
     bool dn_fp = false;                // every special prime below 2^60: the fp64 ModDown conversion applies
     ckks::u64 *d_pinv = nullptr;       // [L]: P^-1 mod q_i
+    double *d_pinvf = nullptr;         // [L]: the same as plain doubles (exact for primes below 2^53)
     ckks::u64 *d_qlinv = nullptr;      // [L][L]: q_l^-1 mod q_i (rescale), row l
     std::map<ckks::u32, ckks::LevelTables> levels;
     // complex-slot encode / decode (built on first use): exp(-2*pi*i*e/N), e < N/2; exp(-i*pi*k/N), k < N; and the
@@ -168,6 +169,8 @@ size_t switch_scratch_words(const ckks_params *p, u32 level, u32 n_items);
 int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_digits, u64 *d_tmp, hipStream_t stream);
 int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 *d_work, hipStream_t stream);
 int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64 *d_w, hipStream_t stream);
+int moddown_rescale(ckks_params *p, u32 level, u64 *d_u, const u64 *const *z, u64 *const *out, u32 n, u64 *d_w,
+                    u64 *d_t, hipStream_t stream);
 // Several rotations of n ciphertexts each, summed over the extended basis in one pass:
 //   u_r (+)= sum_i sum_j sigma_{g_i}(digits_{i,r,j}) * key_{i,j},   dst_r.c0 += sum_i sigma_{g_i}(c0_{i,r}),
 // r < n <= ROT_BATCH, i < n_rot <= MERGE_GROUP.  digits of (i, r) at d_digits + (i*n + r)*digits_words;

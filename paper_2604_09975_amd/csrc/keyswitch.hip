@@ -542,7 +542,40 @@ constexpr u32 MID_COLS = 32, MID_TG = 8, MID_MAX_LEVEL = 32;
 // K8: exactly 8 special primes: no per-prime checks in the conversion loop, so a target's 48 factors arrive through the
 // scalar cache in one burst (with the checks the wave waited for each prime's six in turn).  Staging the factors in
 // LDS instead was measured slower: broadcast reads still take an LDS issue slot per pair of multiply-adds.
+// w_i = sum_k y_k (P/p_k mod q_i) for the two coefficients of a thread, as doubles with |w| <= q/2: the exact fp64 sums
+// of moddown_conv_kernel (20-bit pieces of y times 25-bit halves of the factors)
 template <bool K8>
+__device__ __forceinline__ void mid_convert(const double (&yp)[2][8][3], const double *__restrict__ f, u32 K, double q,
+                                            double u, double (&v)[2]) {
+    double lo[2] = {0.0, 0.0}, hi[2] = {0.0, 0.0};
+#pragma unroll
+    for (u32 k = 0; k < 8; ++k)
+        if (K8 || k < K) {
+#pragma unroll
+            for (u32 a = 0; a < 3; ++a) {
+                const double f0 = f[(k * 3 + a) * 2 + 0], f1 = f[(k * 3 + a) * 2 + 1];
+#pragma unroll
+                for (u32 e = 0; e < 2; ++e) {
+                    lo[e] = fma(yp[e][k][a], f0, lo[e]);
+                    hi[e] = fma(yp[e][k][a], f1, hi[e]);
+                }
+            }
+        }
+#pragma unroll
+    for (u32 e = 0; e < 2; ++e) {
+        const double tt = hi[e] * 33554432.0;                       // exact: a power of two
+        double x = fma(-rint(tt * u), q, tt) + lo[e];               // |.| < 0.75 q, plus low < 2^51
+        v[e] = fma(-rint(x * u), q, x);                             // |v| <= q/2
+    }
+}
+
+// RESC: ModDown and rescale in one (the merged giant step's last act).  The rescale needs the dropped limb of the
+// brought-down ciphertext in the coefficient domain, r = INTT(z + u P^-1)[l-1] - w_{l-1} P^-1, with z the part of the
+// ciphertext that needs no ModDown; t_rows holds INTT(z + u P^-1)[l-1] and w_{l-1} is computed here first.  With
+// r' = r + floor(q_{l-1}/2) mod q_{l-1}, the correction of limb i < l-1 becomes w_i P^-1 + (r' mod q_i - floor(q_{l-1}/2)
+// mod q_i): one forward transform per limb serves both the ModDown and the rescale, and the rows written are those of
+// the l-1 remaining limbs.  Exact modular arithmetic throughout: the same residues as ModDown followed by rescale.
+template <bool K8, bool RESC>
 __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict__ y, u64 *__restrict__ w,
                                                           const ModConst *__restrict__ mods,
                                                           const ModFp *__restrict__ modf,
@@ -552,7 +585,8 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
                                                           const u64 *__restrict__ ninv_dn,
                                                           const double *__restrict__ twf_fwd,
                                                           const double *__restrict__ dn_matf, u32 level, u32 K, u32 L,
-                                                          u32 ystride, u32 yoff) {
+                                                          u32 ystride, u32 yoff, const u64 *__restrict__ t_rows,
+                                                          const double *__restrict__ pinvf) {
     constexpr u32 logN = 16, N = 1u << logN;
     static_assert(MID_TG == 8, "the correction tiles reuse the 8 rows of special-limb tiles");
     __shared__ u64 ylds[8 * 16 * MID_COLS];
@@ -591,35 +625,57 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
                 __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
             yp[e][k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
         }
-    for (u32 i0 = 0; i0 < level; i0 += MID_TG) {
-        for (u32 t = 0; t < MID_TG && i0 + t < level; ++t) {
+    // rescale: the dropped limb first
+    double rp[2] = {0.0, 0.0}, hq = 0.0;
+    const u32 n_out = RESC ? level - 1 : level;
+    if (RESC) {
+        const u32 il = level - 1;
+        const ModFp ml = modf[il];
+        FieldFp fl;
+        fl.q = ml.q;
+        fl.u = ml.u;
+        fl.n0 = fl.n1 = 0.0;
+        fl.tw = nullptr;
+        double wl[2];
+        mid_convert<K8>(yp, dn_matf + (size_t)il * K * 6, K, ml.q, ml.u, wl);
+        hq = (double)(mods[il].q >> 1);
+#pragma unroll
+        for (u32 e = 0; e < 2; ++e) {
+            const double t = fl.in(t_rows[(size_t)pc * N + (2 * grp + e) * 4096 + c0]);
+            double r = t - fl.mul(wl[e], pinvf[il]);
+            fl.norm(r);
+            if (r < 0) r += ml.q;                                   // r in [0, q_last)
+            r += hq;
+            rp[e] = r >= ml.q ? r - ml.q : r;                       // r' = (r + h) mod q_last
+        }
+    }
+    for (u32 i0 = 0; i0 < n_out; i0 += MID_TG) {
+        for (u32 t = 0; t < MID_TG && i0 + t < n_out; ++t) {
             const u32 i = i0 + t;
             const double q = modf[i].q, u = modf[i].u;
-            const double *f = dn_matf + (size_t)i * K * 6;
-            double lo[2] = {0.0, 0.0}, hi[2] = {0.0, 0.0};
+            double v[2];
+            mid_convert<K8>(yp, dn_matf + (size_t)i * K * 6, K, q, u, v);
+            if (RESC) {
+                FieldFp fi;
+                fi.q = q;
+                fi.u = u;
+                fi.n0 = fi.n1 = 0.0;
+                fi.tw = nullptr;
+                double hi_ = hq;
+                fi.norm(hi_);                                       // floor(q_last / 2) mod q_i
+                const double pv = pinvf[i];
 #pragma unroll
-            for (u32 k = 0; k < 8; ++k)
-                if (K8 || k < K) {
-#pragma unroll
-                    for (u32 a = 0; a < 3; ++a) {
-                        const double f0 = f[(k * 3 + a) * 2 + 0], f1 = f[(k * 3 + a) * 2 + 1];
-#pragma unroll
-                        for (u32 e = 0; e < 2; ++e) {
-                            lo[e] = fma(yp[e][k][a], f0, lo[e]);
-                            hi[e] = fma(yp[e][k][a], f1, hi[e]);
-                        }
-                    }
+                for (u32 e = 0; e < 2; ++e) {
+                    double ri = rp[e];
+                    fi.norm(ri);                                    // r' mod q_i
+                    v[e] = fi.mul(v[e], pv) + (ri - hi_);           // |.| < 2q: the forward round normalises
                 }
-#pragma unroll
-            for (u32 e = 0; e < 2; ++e) {
-                const double tt = hi[e] * 33554432.0;                       // exact: a power of two
-                double v = fma(-rint(tt * u), q, tt) + lo[e];               // |.| < 0.75 q, plus low < 2^51
-                v = fma(-rint(v * u), q, v);                                // |v| <= q/2: what the forward round takes
-                wlds[(t * 16 + 2 * grp + e) * MID_COLS + col] = (u64)__double_as_longlong(v);
             }
+#pragma unroll
+            for (u32 e = 0; e < 2; ++e) wlds[(t * 16 + 2 * grp + e) * MID_COLS + col] = (u64)__double_as_longlong(v[e]);
         }
         __syncthreads();
-        if (i0 + grp < level) {
+        if (i0 + grp < n_out) {
             const u32 i = i0 + grp;
             const FieldFp ff = make_field_fp(modf[i], twf_fwd, i, logN);
             u64 *dst = w + ((size_t)pc * level + i) * N;
@@ -634,6 +690,45 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
     }
 }
 
+// t[pc][k] = z[pc][l-1][k] + u[pc][l-1][k] P^-1 mod q_{l-1} (NTT domain): the dropped limb of the ciphertext before its
+// special-limb correction.  z_r: component-major ciphertexts [2][level][N]; u [n][2][level+K][N].
+__global__ __launch_bounds__(KS_THREADS) void rescale_last_row_kernel(PtrPack z, const u64 *__restrict__ u,
+                                                                      u64 *__restrict__ t,
+                                                                      const ModConst *__restrict__ mods,
+                                                                      const u64 *__restrict__ pinv, u32 level, u32 K,
+                                                                      u32 N) {
+    const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
+    const u32 pc = blockIdx.y, r = pc >> 1, comp = pc & 1, i = level - 1;
+    const ModConst m = mods[i];
+    const u64 zz = z.p[r][((size_t)comp * level + i) * N + k];
+    const u64 uu = u[((size_t)pc * (level + K) + i) * N + k];
+    t[(size_t)pc * N + k] = add_mod(zz, mont_mul(uu, pinv[i], m), m.q);
+}
+
+// out[r][comp][i][k] = (z[r][comp][i][k] + u P^-1 - NTT(w')[i][k]) q_{l-1}^-1 for the l-1 remaining limbs
+__global__ __launch_bounds__(KS_THREADS) void moddown_rescale_final_kernel(PtrPack z, ItemPack out,
+                                                                           const u64 *__restrict__ u,
+                                                                           const u64 *__restrict__ w,
+                                                                           const ModConst *__restrict__ mods,
+                                                                           const u64 *__restrict__ pinv,
+                                                                           const u64 *__restrict__ qlinv, u32 level,
+                                                                           u32 K, u32 N) {
+    typedef u64 vec_t __attribute__((ext_vector_type(2)));
+    const u32 k = (blockIdx.x * KS_THREADS + threadIdx.x) * 2;
+    const u32 i = blockIdx.y, pc = blockIdx.z, r = pc >> 1, comp = pc & 1;
+    const ModConst m = mods[i];
+    const vec_t zz = *reinterpret_cast<const vec_t *>(z.p[r] + ((size_t)comp * level + i) * N + k);
+    const vec_t uu = *reinterpret_cast<const vec_t *>(u + ((size_t)pc * (level + K) + i) * N + k);
+    const vec_t ww = *reinterpret_cast<const vec_t *>(w + ((size_t)pc * level + i) * N + k);
+    vec_t o;
+#pragma unroll
+    for (u32 e = 0; e < 2; ++e) {
+        const u64 y = add_mod(zz[e], mont_mul(uu[e], pinv[i], m), m.q);
+        o[e] = mont_mul(sub_mod(y, ww[e], m.q), qlinv[i], m);
+    }
+    *reinterpret_cast<vec_t *>(out.it[r].dst + ((size_t)comp * (level - 1) + i) * N + k) = o;
+}
+
 // Whether the fused kernel applies to this parameter set at this level.
 static bool moddown_mid_ok(const ckks_params *p, u32 level) {
     bool ok = p->logN == 16 && p->dn_fp && p->K <= 8 && level <= MID_MAX_LEVEL;
@@ -642,15 +737,17 @@ static bool moddown_mid_ok(const ckks_params *p, u32 level) {
 }
 
 static void launch_moddown_mid(const ckks_params *p, const u64 *y, u64 *w, u32 n, u32 level, u32 ystride, u32 yoff,
-                               hipStream_t stream) {
-    if (p->K == 8)
-        hipLaunchKernelGGL(moddown_mid_kernel<true>, dim3(4096 / MID_COLS, n * 2), dim3(256), 0, stream, y, w, p->d_mod,
-                           p->d_modf, p->d_modf_dn, p->d_tws_inv, p->d_twf_inv, p->d_ninvs_dn, p->d_twf_fwd,
-                           p->d_dn_matf, level, p->K, p->L, ystride, yoff);
-    else
-        hipLaunchKernelGGL(moddown_mid_kernel<false>, dim3(4096 / MID_COLS, n * 2), dim3(256), 0, stream, y, w, p->d_mod,
-                           p->d_modf, p->d_modf_dn, p->d_tws_inv, p->d_twf_inv, p->d_ninvs_dn, p->d_twf_fwd,
-                           p->d_dn_matf, level, p->K, p->L, ystride, yoff);
+                               hipStream_t stream, const u64 *t_rows = nullptr) {
+#define MID_LAUNCH(K8, RESC)                                                                                         \
+    hipLaunchKernelGGL((moddown_mid_kernel<K8, RESC>), dim3(4096 / MID_COLS, n * 2), dim3(256), 0, stream, y, w,       \
+                       p->d_mod, p->d_modf, p->d_modf_dn, p->d_tws_inv, p->d_twf_inv, p->d_ninvs_dn, p->d_twf_fwd,    \
+                       p->d_dn_matf, level, p->K, p->L, ystride, yoff, t_rows, p->d_pinvf)
+    if (p->K == 8) {
+        if (t_rows) MID_LAUNCH(true, true); else MID_LAUNCH(true, false);
+    } else {
+        if (t_rows) MID_LAUNCH(false, true); else MID_LAUNCH(false, false);
+    }
+#undef MID_LAUNCH
 }
 
 // base conversion P -> q_i of n*2 polynomials; the rows of polynomial pc start at row pc * ystride + yoff of y
@@ -1040,6 +1137,47 @@ int moddown_add(ckks_params *p, u32 level, u64 *d_u, u64 *const *dst, u32 n, u64
     hipLaunchKernelGGL(moddown_final_kernel, dim3(N / KS_THREADS, level, n * 2), dim3(KS_THREADS), 0, stream, pack,
                        d_u, d_w, p->d_mod, p->d_pinv, level, K, p->logN);
     CKKS_LAUNCH_CHECK("moddown_final_kernel");
+    return CKKS_OK;
+}
+
+// ModDown and rescale in one pass over the correction (merged giant step with CKKS_MATMUL_RESCALE):
+//   out_r = rescale( z_r + ModDown(d_u[r]) ),   z_r [2][level][N] -> out_r [2][level-1][N],   n <= ROT_BATCH.
+// d_u is consumed; d_w: n*2*level*N words, d_t: n*2*N words of scratch.  Returns CKKS_E_INVAL if the fused kernels do
+// not apply to this parameter set (the caller then brings down and rescales in two steps).
+int moddown_rescale(ckks_params *p, u32 level, u64 *d_u, const u64 *const *z, u64 *const *out, u32 n, u64 *d_w,
+                    u64 *d_t, hipStream_t stream) {
+    if (n == 0) return CKKS_OK;
+    if (!moddown_mid_ok(p, level) || level < 2) return CKKS_E_INVAL;
+    const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
+    PtrPack zp;
+    ItemPack op;
+    for (u32 r = 0; r < ROT_BATCH; ++r) {
+        zp.p[r] = z[r < n ? r : 0];
+        SwitchItem &it = op.it[r];
+        it.digits = it.c1 = it.c0 = it.key = nullptr;
+        it.dst = out[r < n ? r : 0];
+        it.galois_elt = 1;
+        it.accumulate = 0;
+    }
+    LimbIds ids;
+    for (u32 t = 0; t < Wl; ++t) ids.id[t] = (uint8_t)(t < level ? SKIP_ROW : L + (t - level));
+    int rc = launch_ntt(p, d_u, ids, Wl, n * 2 * Wl, true, stream, 1, true);     // special limbs: inverse tile pass
+    if (rc) return rc;
+    hipLaunchKernelGGL(rescale_last_row_kernel, dim3(N / KS_THREADS, n * 2), dim3(KS_THREADS), 0, stream, zp, d_u, d_t,
+                       p->d_mod, p->d_pinv, level, K, N);
+    CKKS_LAUNCH_CHECK("rescale_last_row_kernel");
+    ids.id[0] = (uint8_t)(level - 1);
+    rc = launch_ntt(p, d_t, ids, 1, n * 2, true, stream);
+    if (rc) return rc;
+    launch_moddown_mid(p, d_u, d_w, n, level, Wl, level, stream, d_t);
+    CKKS_LAUNCH_CHECK("moddown_mid_kernel");
+    p->limb_ntts += (u64)n * 2 * (level - 1);
+    for (u32 i = 0; i < level; ++i) ids.id[i] = (uint8_t)(i + 1 < level ? i : SKIP_ROW);
+    rc = launch_ntt(p, d_w, ids, level, n * 2 * level, false, stream, 2);
+    if (rc) return rc;
+    hipLaunchKernelGGL(moddown_rescale_final_kernel, dim3(N / KS_THREADS / 2, level - 1, n * 2), dim3(KS_THREADS), 0,
+                       stream, zp, op, d_u, d_w, p->d_mod, p->d_pinv, p->d_qlinv + (size_t)(level - 1) * L, level, K, N);
+    CKKS_LAUNCH_CHECK("moddown_rescale_final_kernel");
     return CKKS_OK;
 }
 

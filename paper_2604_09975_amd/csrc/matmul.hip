@@ -561,11 +561,14 @@ __global__ __launch_bounds__(EW_THREADS) void take_last_limb_kernel(const u64 *_
 // merged digits].
 struct MatmulLayout {
     u32 in_chunk, batch, mg_rots;
-    size_t dig_w, tmp_w, ks_w, bank_w, acc_w, u_w, mg_w;
-    size_t total() const { return ks_w + bank_w + acc_w + u_w + mg_w; }
+    size_t dig_w, tmp_w, ks_w, bank_w, acc_w, u_w, mg_w, yfull_w, t_w;
+    size_t total() const { return ks_w + bank_w + acc_w + u_w + mg_w + yfull_w + t_w; }
 };
 
-static MatmulLayout matmul_layout(const ckks_params *P, const ckks_weights *w, bool merged) {
+constexpr u32 RESCALE_CHUNK = 64;
+static int rescale_rows(ckks_params *P, const u64 *d_in, u32 level, u32 rows, u64 *d_out, u64 *d_r, hipStream_t stream);
+
+static MatmulLayout matmul_layout(const ckks_params *P, const ckks_weights *w, bool merged, bool rescale = true) {
     MatmulLayout l;
     const u32 N = P->N, level = w->level, G = w->G, B = w->B_out, N2 = w->N2;
     const size_t ctw = (size_t)2 * level * N;
@@ -581,6 +584,9 @@ static MatmulLayout matmul_layout(const ckks_params *P, const ckks_weights *w, b
     // merged giant step: the digits of up to MERGE_GROUP rotations of one batch of blocks are held together
     l.mg_rots = merged ? std::min<u32>(MERGE_GROUP, N2 - 1) : 0;
     l.mg_w = (size_t)l.mg_rots * std::min(l.batch, B) * l.dig_w;
+    // CKKS_MATMUL_RESCALE: the unrescaled blocks and the dropped limbs in the coefficient domain
+    l.yfull_w = rescale ? (size_t)B * ctw : 0;
+    l.t_w = rescale ? (size_t)std::max<u32>(l.batch, RESCALE_CHUNK) * 2 * N : 0;
     return l;
 }
 
@@ -883,7 +889,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         set_error("ckks_ctpt_matmul: conj_key is not a key for conjugation");
         return CKKS_E_INVAL;
     }
-    if (flags & ~(uint32_t)CKKS_MATMUL_MERGED_GIANT) {
+    if (flags & ~(uint32_t)(CKKS_MATMUL_MERGED_GIANT | CKKS_MATMUL_RESCALE)) {
         set_error("ckks_ctpt_matmul: unknown flags 0x%x", flags);
         return CKKS_E_INVAL;
     }
@@ -895,14 +901,19 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         }
     const uint64_t ntt0 = P->limb_ntts;
     const size_t ctw = (size_t)2 * level * N;
-    if (words_overlap(d_ct_x, (size_t)G * ctw, d_ct_y, (size_t)B * ctw)) {
+    const bool rescale = (flags & CKKS_MATMUL_RESCALE) != 0;
+    if (rescale && level < 2) {
+        set_error("ckks_ctpt_matmul: CKKS_MATMUL_RESCALE needs weights at level 2 or above");
+        return CKKS_E_LEVEL;
+    }
+    if (words_overlap(d_ct_x, (size_t)G * ctw, d_ct_y, (size_t)B * (rescale ? ctw - 2 * N : ctw))) {
         set_error("ckks_ctpt_matmul: d_ct_y overlaps d_ct_x");
         return CKKS_E_INVAL;
     }
     const u32 BP = B * N2, GQ = G * N1;
     // persistent buffers of this call live behind the key-switch scratch
     const bool merged = (flags & CKKS_MATMUL_MERGED_GIANT) && N2 > 1;
-    const MatmulLayout lay = matmul_layout(P, w, merged);
+    const MatmulLayout lay = matmul_layout(P, w, merged, rescale);
     const u32 in_chunk = lay.in_chunk, batch = lay.batch, mg_rots = lay.mg_rots;
     const size_t dig_w = lay.dig_w, tmp_w = lay.tmp_w, ks_w = lay.ks_w, bank_w = lay.bank_w, acc_w = lay.acc_w,
                  u_w = lay.u_w;
@@ -910,6 +921,17 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     if (rc) return rc;
     u64 *d_digits = (u64 *)P->d_scratch, *d_tmp = d_digits + batch * dig_w, *d_work = d_tmp + batch * tmp_w;
     u64 *d_bank = (u64 *)P->d_scratch + ks_w, *d_acc = d_bank + bank_w;
+    // with CKKS_MATMUL_RESCALE the blocks are assembled at the input level in scratch and leave one limb shorter
+    u64 *d_out_final = d_ct_y;
+    u64 *d_yfull = d_acc + acc_w + u_w + lay.mg_w, *d_t = d_yfull + lay.yfull_w;
+    if (rescale) d_ct_y = d_yfull;
+    // ModDown and rescale of the merged giant step in one pass, where the fused kernels apply
+    const bool fused_rescale = rescale && merged && !conj_key && P->logN == 16 && P->K <= 8 && P->dn_fp &&
+                               [&] {
+                                   for (u32 i = 0; i < level; ++i)
+                                       if (P->mod[i] >> 50) return false;
+                                   return level <= 32;
+                               }();
 
     // 1. baby-step bank: the inputs are decomposed once (hoisting); the switches are issued step by step
     //    with the G inputs of one step next to each other, so that they share the reads of that step's key
@@ -1049,6 +1071,17 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                            (size_t)N2 * ctw);
         CKKS_LAUNCH_CHECK("copy_blocks_kernel");
     }
+    auto add_bias = [&]() -> int {
+        for (u32 b0 = 0; w->d_bias && b0 < B; b0 += 65535) {
+            hipLaunchKernelGGL(add_bias_kernel, dim3(N / (2 * EW_THREADS), level, std::min<u32>(B - b0, 65535)),
+                               dim3(EW_THREADS), 0, stream, d_ct_y + (size_t)b0 * ctw,
+                               w->d_bias + (size_t)b0 * level * N, P->d_mod, level, N);
+            CKKS_LAUNCH_CHECK("add_bias_kernel");
+        }
+        return CKKS_OK;
+    };
+    if (fused_rescale && (rc = add_bias())) return rc;      // the rescale needs the complete dropped limb
+    bool any_giant = false;
     u64 *d_u = d_acc + acc_w, *d_mdig = d_u + u_w;
     if (merged) {
         // rotations that are a full turn are plain additions; the others are grouped: the accumulators of a
@@ -1088,7 +1121,14 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             }
             u64 *dsts[ROT_BATCH];
             for (u32 r = 0; r < nb; ++r) dsts[r] = d_ct_y + (size_t)(b0 + r) * ctw;
-            rc = moddown_add(P, level, u_b, dsts, nb, d_work, stream);
+            any_giant = true;
+            if (fused_rescale) {
+                u64 *outs[ROT_BATCH];
+                for (u32 r = 0; r < nb; ++r) outs[r] = d_out_final + (size_t)(b0 + r) * (ctw - 2 * N);
+                rc = moddown_rescale(P, level, u_b, dsts, outs, nb, d_work, d_t, stream);
+            } else {
+                rc = moddown_add(P, level, u_b, dsts, nb, d_work, stream);
+            }
             if (rc) return rc;
         }
     }
@@ -1149,13 +1189,15 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             CKKS_LAUNCH_CHECK("add_rows_kernel");
         }
     }
-    // 4. bias into c0 of every block
-    if (w->d_bias) {
-        for (u32 b0 = 0; b0 < B; b0 += 65535) {
-            hipLaunchKernelGGL(add_bias_kernel, dim3(N / (2 * EW_THREADS), level, std::min<u32>(B - b0, 65535)),
-                               dim3(EW_THREADS), 0, stream, d_ct_y + (size_t)b0 * ctw,
-                               w->d_bias + (size_t)b0 * level * N, P->d_mod, level, N);
-            CKKS_LAUNCH_CHECK("add_bias_kernel");
+    // 4. bias into c0 of every block; 5. rescale, unless the giant step's ModDown already did both
+    const bool rescaled = fused_rescale && any_giant;
+    if (!fused_rescale && (rc = add_bias())) return rc;
+    if (rescale && !rescaled) {
+        for (u32 b0 = 0; b0 < B; b0 += RESCALE_CHUNK) {
+            const u32 c = std::min(RESCALE_CHUNK, B - b0);
+            rc = rescale_rows(P, d_ct_y + (size_t)b0 * ctw, level, 2 * c, d_out_final + (size_t)b0 * (ctw - 2 * N), d_t,
+                              stream);
+            if (rc) return rc;
         }
     }
     if (counters) {
@@ -1177,8 +1219,6 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
 }  // extern "C"
 
 namespace ckks {
-
-constexpr u32 RESCALE_CHUNK = 64;
 
 // rescale of `rows` polynomials (rows = 2 x ciphertexts): d_in [rows][level][N] -> d_out [rows][level-1][N];
 // d_r: rows*N words of scratch (the last limbs in the coefficient domain)

@@ -375,7 +375,7 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
         }
     P->hninv = ninv_plain;
     std::vector<u64> dn_inv(K), dn_mat((size_t)K * L), pinv(L), qlinv((size_t)L * L, 0);
-    std::vector<double> dn_matf((size_t)L * K * 6, 0.0);
+    std::vector<double> dn_matf((size_t)L * K * 6, 0.0), pinvf(L, 0.0);
     for (u32 k = 0; k < K; ++k) {
         u64 pk = mod[L + k], prod = 1;
         for (u32 b = 0; b < K; ++b)
@@ -402,6 +402,7 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
         u64 pm = 1;
         for (u32 k = 0; k < K; ++k) pm = hmul(pm, mod[L + k] % mod[i], mod[i]);
         pinv[i] = to_mont(hinv(pm, mod[i]), P->hmod[i]);
+        pinvf[i] = (double)hinv(pm, mod[i]);
         for (u32 l = 0; l < L; ++l)
             if (l != i) qlinv[(size_t)l * L + i] = to_mont(hinv(mod[l] % mod[i], mod[i]), P->hmod[i]);
     }
@@ -438,6 +439,7 @@ int ckks_params_create(uint32_t logN, const uint64_t *q, uint32_t L, const uint6
     if (!rc) rc = upload(&P->d_dn_mat, dn_mat);
     if (!rc) rc = upload(&P->d_dn_matf, dn_matf);
     if (!rc) rc = upload(&P->d_pinv, pinv);
+    if (!rc) rc = upload(&P->d_pinvf, pinvf);
     if (!rc) rc = upload(&P->d_qlinv, qlinv);
     if (!rc) rc = upload(&P->d_tws_fwd, fwd_s);
     if (!rc) rc = upload(&P->d_tws_inv, inv_s);
@@ -495,6 +497,7 @@ void ckks_params_destroy(ckks_params_t *P) {
     hipFree(P->d_dn_mat);
     hipFree(P->d_dn_matf);
     hipFree(P->d_pinv);
+    hipFree(P->d_pinvf);
     hipFree(P->d_qlinv);
     hipFree(P->d_tws_fwd);
     hipFree(P->d_tws_inv);

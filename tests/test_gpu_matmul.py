@@ -61,7 +61,11 @@ def run_case(O, P, X, Wm, bias, m, C, N1, log_scale, level, seed, hw=64, oracle_
     y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h,
                                     flags=B.MATMUL_MERGED_GIANT if merged else 0)
     y_res = B.ckks_rescale(P, y_dev, level, B_out)
+    # the same projection with the rescale inside the call: identical residues
+    y_fused, _ = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h,
+                                    flags=(B.MATMUL_MERGED_GIANT if merged else 0) | B.MATMUL_RESCALE)
     torch.cuda.synchronize()
+    assert torch.equal(y_fused, y_res)
     got, got_res = to_host(y_dev), to_host(y_res)
 
     blocks = list(range(B_out)) if oracle_blocks is None else oracle_blocks

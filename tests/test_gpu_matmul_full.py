@@ -77,7 +77,13 @@ def test_full_size_projection_bit_exact(spec, merged, pairs, which):
     y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, conj_key=conj_h,
                                     flags=B.MATMUL_MERGED_GIANT if merged else 0)
     y_res = B.ckks_rescale(P, y_dev, level, B_out)
+    # the same projection with the rescale inside the call (with the merged giant step and real packing: ModDown and
+    # rescale in one pass over the correction): identical residues, hence equal to the oracle's wherever y_res is
+    y_fused, _ = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, conj_key=conj_h,
+                                    flags=(B.MATMUL_MERGED_GIANT if merged else 0) | B.MATMUL_RESCALE)
     torch.cuda.synchronize()
+    assert torch.equal(y_fused, y_res)
+    del y_fused
     got, got_res = to_host(y_dev), to_host(y_res)
     assert cnt.key_switches == G * (N1 - 1) + B_out * (N2 - 1) + (B_out if pairs else 0)
     assert cnt.ptmuls == G * N1 * B_out * N2
