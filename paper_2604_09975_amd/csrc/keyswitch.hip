@@ -195,13 +195,16 @@ __global__ __launch_bounds__(256) void modup_mid_kernel(const u64 *__restrict__ 
                                                         const u64 *__restrict__ ninvs,
                                                         const double *__restrict__ up_ft,
                                                         const double *__restrict__ up_mats, u32 level, u32 K, u32 L,
-                                                        u32 alpha, u32 beta) {
+                                                        u32 alpha, u32 beta, u32 tsplit) {
     constexpr u32 logN = 16, N = 1u << logN;
     static_assert(UP_TG == 8, "the target tiles reuse the 8 rows of source tiles");
     __shared__ u64 ylds[8 * 16 * UP_COLS];
     u64 *wlds = ylds;               // the sources live in registers once step 2 has read them: the same 32 KiB
     const u32 tid = threadIdx.x, col = tid & (UP_COLS - 1), grp = tid / UP_COLS;   // grp < 8
-    const u32 c0 = blockIdx.x * UP_COLS + col;
+    // tsplit > 1 (few ciphertexts): the groups of targets of a tile go to tsplit workgroups, each of which redoes the
+    // cheap step 1, so that a lone decomposition still fills the chip
+    const u32 tile = blockIdx.x % (4096 / UP_COLS), tpart = blockIdx.x / (4096 / UP_COLS);
+    const u32 c0 = tile * UP_COLS + col;
     const u32 j = blockIdx.y, r = blockIdx.z;
     const u32 Wl = level + K;
     const u32 lo = j * alpha, hi = min(lo + alpha, level), nd = hi - lo;
@@ -221,7 +224,7 @@ __global__ __launch_bounds__(256) void modup_mid_kernel(const u64 *__restrict__ 
     __syncthreads();                // every thread has its y: the tile may be overwritten
     u64 *dig = digits + ((size_t)r * beta + j) * Wl * N;
     const u32 nt = Wl - nd;                                          // targets: all rows outside the digit
-    for (u32 u0 = 0; u0 < nt; u0 += UP_TG) {
+    for (u32 u0 = tpart * UP_TG; u0 < nt; u0 += tsplit * UP_TG) {
 #pragma unroll 1
         for (u32 e = 0; e < 2; ++e) {
             double yd[8], yp[8][2];
@@ -1001,9 +1004,11 @@ int decompose(ckks_params *p, const u64 *const *c1, u32 n, u32 level, u64 *d_dig
         p->limb_ntts += (u64)n * level;
         if (p->logN == 16 && all_fp && sp60 && alpha <= 8 && K <= 8) {
             // the column passes of both transforms ride in the base conversion: c1 read once, digits written once
-            hipLaunchKernelGGL(modup_mid_kernel, dim3(4096 / UP_COLS, beta, n), dim3(256), 0, stream, d_tmp, d_digits,
-                               p->d_mod, p->d_modf, lt->d_modf_up, p->d_twf_inv, p->d_twf_fwd, p->d_tws_fwd, p->d_ninvs,
-                               lt->d_up_ft, lt->d_up_mats, level, K, L, alpha, beta);
+            const u32 tgroups = (Wl - std::min(alpha, level) + UP_TG - 1) / UP_TG;
+            const u32 tsplit = n * beta * (4096 / UP_COLS) < 1024 ? std::max<u32>(1, tgroups) : 1;
+            hipLaunchKernelGGL(modup_mid_kernel, dim3(4096 / UP_COLS * tsplit, beta, n), dim3(256), 0, stream, d_tmp,
+                               d_digits, p->d_mod, p->d_modf, lt->d_modf_up, p->d_twf_inv, p->d_twf_fwd, p->d_tws_fwd,
+                               p->d_ninvs, lt->d_up_ft, lt->d_up_mats, level, K, L, alpha, beta, tsplit);
             CKKS_LAUNCH_CHECK("modup_mid_kernel");
             p->limb_ntts += (u64)n * beta * Wl - (u64)n * level;
             auto row_id2 = [&](u32 j, u32 t) -> uint8_t {
