@@ -796,6 +796,16 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(ItemPack pack
 // row (comp, k, r) of y = INTT-pass-B( sum_j sigma_g(d_j)[p_k] * key_j[comp][p_k] ).
 // grid: x = tile of 4096, y = ((k*n + r)*2 + comp): the two components of an item (same digit reads) and the
 // items of a batch that share a key sit next to each other and, with 16 tiles per row, on the same XCD.
+// KEY_NT: key rows are read with non-temporal loads.  Right when every item has a key of its own (the rows are used
+// once and would only push the digit rows, which every item re-reads, out of L2); wrong when neighbouring items share
+// a key, where it is the cached line that lets the second and third reader skip HBM.
+typedef u64 key_vec_t __attribute__((ext_vector_type(2)));
+template <bool NT>
+__device__ __forceinline__ key_vec_t load_key(const key_vec_t *p) {
+    return NT ? __builtin_nontemporal_load(p) : *p;
+}
+
+template <bool KEY_NT>
 __global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64 *__restrict__ y,
                                                               const ModConst *__restrict__ mods,
                                                               const ModFp *__restrict__ modf,
@@ -831,7 +841,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64
                 if (j < beta) {
                     dv[e][0][j] = dig[(size_t)j * Wl * N + kp0];
                     dv[e][1][j] = dig[(size_t)j * Wl * N + kp1];
-                    kv[e][j] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(key + (size_t)j * 2 * Wt * N + idx));
+                    kv[e][j] = load_key<KEY_NT>(reinterpret_cast<const vec_t *>(key + (size_t)j * 2 * Wt * N + idx));
                 }
         }
 #pragma unroll
@@ -858,6 +868,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ip_intt_kernel(ItemPack pack, u64
 // Last pass of the forward transform of w fused with the rest of the key switch on limb q_i:
 //   dst[comp][i] (+)= ( sum_j sigma_g(d_j)[q_i] * key_j[comp][q_i] - NTT(w)[i] ) * P^-1  (+ sigma_g(c0)[i] if comp = 0)
 // grid: x = tile of 4096, y = ((i*n + r)*2 + comp), neighbours share digit and key lines in L2 as above.
+template <bool KEY_NT>
 __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack, const u64 *__restrict__ w,
                                                                   const ModConst *__restrict__ mods,
                                                                   const ModFp *__restrict__ modf,
@@ -914,7 +925,7 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
                 if (j < beta) {
                     dv[e][0][j] = drow[j][kp0];
                     dv[e][1][j] = drow[j][kp1];
-                    kv[e][j] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(key + (size_t)j * 2 * Wt * N + idx));
+                    kv[e][j] = load_key<KEY_NT>(reinterpret_cast<const vec_t *>(key + (size_t)j * 2 * Wt * N + idx));
                 }
             const bool fold = comp == 0 && it.c0;
             cv[e][0] = fold ? c0[kp0] : 0;
@@ -1205,9 +1216,11 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
         const u32 tiles = N >> 12;
         // at N = 2^12 the tile pass is the whole inverse transform and carries the (P/p_k)^-1 scaling itself
         const bool whole = p->logN == 12;
-        hipLaunchKernelGGL(ip_intt_kernel, dim3(tiles, n * 2 * K), dim3(NTT_THREADS), 0, stream, pack, y, p->d_mod,
-                           whole ? p->d_modf_dn : p->d_modf, p->d_tws_inv, p->d_twf_inv,
-                           whole ? p->d_ninvs_dn : p->d_ninvs, n, level, K, L, beta, p->logN);
+        const bool own_keys = n_groups == n;               // no two neighbouring items share a key
+        hipLaunchKernelGGL(own_keys ? ip_intt_kernel<true> : ip_intt_kernel<false>, dim3(tiles, n * 2 * K),
+                           dim3(NTT_THREADS), 0, stream, pack, y, p->d_mod, whole ? p->d_modf_dn : p->d_modf,
+                           p->d_tws_inv, p->d_twf_inv, whole ? p->d_ninvs_dn : p->d_ninvs, n, level, K, L, beta,
+                           p->logN);
         CKKS_LAUNCH_CHECK("ip_intt_kernel");
         p->limb_ntts += (u64)n * 2 * K;
         int rc;
@@ -1227,9 +1240,9 @@ int switch_batch(ckks_params *p, u32 level, const SwitchItem *items, u32 n, u64 
             rc = launch_ntt(p, w, ids, level, n * 2 * level, false, stream, 1, false);
             if (rc) return rc;
         }
-        hipLaunchKernelGGL(passb_final_kernel, dim3(tiles, n * 2 * level), dim3(NTT_THREADS), 0, stream, pack, w,
-                           p->d_mod, p->d_modf, p->d_tws_fwd, p->d_twf_fwd, p->d_ninvs, p->d_pinv, n, level, K, L, beta,
-                           p->alpha, p->logN);
+        hipLaunchKernelGGL(own_keys ? passb_final_kernel<true> : passb_final_kernel<false>, dim3(tiles, n * 2 * level),
+                           dim3(NTT_THREADS), 0, stream, pack, w, p->d_mod, p->d_modf, p->d_tws_fwd, p->d_twf_fwd,
+                           p->d_ninvs, p->d_pinv, n, level, K, L, beta, p->alpha, p->logN);
         CKKS_LAUNCH_CHECK("passb_final_kernel");
         return CKKS_OK;
     }

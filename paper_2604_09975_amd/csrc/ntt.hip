@@ -99,8 +99,8 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_pass_kernel(u64 *__restrict__
 
 // which: 0 = pass A (N = 2^16: first / last 4 stages, registers only), 2 = pass B (12 stages in a 4096 tile)
 // FP: the kernel serves the rows whose prime is below 2^50 (fp64 butterflies) or the others (integer butterflies);
-// rows of the other kind return at once.  One kernel for both kinds would carry the larger register budget of the
-// integer path into every row (3 instead of 5 waves per SIMD in pass B).
+// rows of the other kind return at once.  One kernel for both kinds needs the union of the two register budgets
+// (130 registers, 3 waves per SIMD in pass B, against 112 to 124 and 4 waves for the separate ones).
 template <bool INV, int WHICH, bool FP>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fast_kernel(u64 *__restrict__ data,
                                                                const ModConst *__restrict__ mods,
