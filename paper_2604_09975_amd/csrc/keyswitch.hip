@@ -376,11 +376,16 @@ __global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, c
                                                                size_t dst_stride, u64 *__restrict__ u,
                                                                const ModConst *__restrict__ mods, u32 n, u32 level,
                                                                u32 K, u32 L, u32 beta, u32 alpha, u32 logN,
-                                                               u32 accumulate) {
+                                                               u32 accumulate, u32 groups) {
     const u32 N = 1u << logN;
-    const u32 k = blockIdx.x * KS_THREADS + threadIdx.x;
+    // grid x = ((chunk of 8 coefficient runs) * groups + group of MR ciphertexts) * 8 + run within the chunk: the
+    // groups of ciphertexts, which read the same key rows, follow each other at a distance of 8 workgroups, i.e. on
+    // the same XCD at about the same time, so one of them fetches a key line and the others find it in that L2
+    const u32 chunk = N / KS_THREADS < 8 ? N / KS_THREADS : 8;   // a power of two
+    const u32 xg = blockIdx.x / chunk;
+    const u32 k = ((xg / groups) * chunk + (blockIdx.x & (chunk - 1))) * KS_THREADS + threadIdx.x;
     const u32 t = blockIdx.y;
-    const u32 r0 = blockIdx.z * MR;
+    const u32 r0 = (xg % groups) * MR;
     const u32 Wl = level + K, Wt = L + K;
     const u32 gl = t < level ? t : L + (t - level);
     const u32 own = t < level ? t / alpha : ~0u;                 // the digit whose own limb t is: read from c1
@@ -404,8 +409,8 @@ __global__ __launch_bounds__(KS_THREADS) void merged_ip_kernel(MergedRot rots, c
             for (u32 jj = 0; jj < MAX_BETA; ++jj) {
                 const u32 j = j0 + jj;
                 if (j < beta) {
-                    k0[jj] = __builtin_nontemporal_load(key + (((size_t)j * 2 + 0) * Wt + gl) * N + k);
-                    k1[jj] = __builtin_nontemporal_load(key + (((size_t)j * 2 + 1) * Wt + gl) * N + k);
+                    k0[jj] = key[(((size_t)j * 2 + 0) * Wt + gl) * N + k];
+                    k1[jj] = key[(((size_t)j * 2 + 1) * Wt + gl) * N + k];
 #pragma unroll
                     for (u32 r = 0; r < MR; ++r)
                         if (r0 + r < n)
@@ -1111,9 +1116,10 @@ int switch_accumulate_merged(ckks_params *p, u32 level, const MergedRot &rots, u
     }
     const u32 N = p->N, K = p->K, L = p->L, Wl = level + K;
     const u32 beta = (level + p->alpha - 1) / p->alpha;
-    hipLaunchKernelGGL(merged_ip_kernel, dim3(N / KS_THREADS, Wl, (n + MR - 1) / MR), dim3(KS_THREADS), 0, stream, rots,
+    const u32 groups = (n + MR - 1) / MR;
+    hipLaunchKernelGGL(merged_ip_kernel, dim3(N / KS_THREADS * groups, Wl), dim3(KS_THREADS), 0, stream, rots,
                        d_digits, digits_words(p, level), c0_base, c0_stride_r, dst_base, dst_stride, d_u, p->d_mod, n,
-                       level, K, L, beta, p->alpha, p->logN, accumulate ? 1u : 0u);
+                       level, K, L, beta, p->alpha, p->logN, accumulate ? 1u : 0u, groups);
     CKKS_LAUNCH_CHECK("merged_ip_kernel");
     return CKKS_OK;
 }
