@@ -4,9 +4,10 @@
 One step = one pass of the whole path on the BERT-base QKV projection under CKKS
 (N = 2^16, 24 + 8 primes, scale 2^40, X 128x768 encrypted, W 768x2304 + bias in plaintext):
 ckks_ctpt_matmul (hoisted baby-step bank, diagonal multiply-accumulate over the pre-expanded
-weights, giant-step key switches, bias) followed by ckks_rescale, with keys, weights and input
-ciphertexts resident in HBM.  Prints ONE JSON line; the second headline figure, key switches per
-second on a hoisted batch (N = 2^16, L = 24), rides in the same line.
+weights, giant-step key switches summed over the extended basis, bias, and the rescale fused
+into the one ModDown per output block), with keys, weights and input ciphertexts resident in HBM.
+Prints ONE JSON line; the second headline figure, key switches per second on a hoisted batch
+(N = 2^16, L = 24), the NTT batch, the GPT-2-small block and the oracle's CPU time ride in the same line.
 """
 import argparse
 import json
