@@ -6,8 +6,8 @@ the same on the GPU, so the split is chosen by a two-term cost model rather than
 default unit costs are the measured microseconds per key switch of the N = 2^16, 24+8-limb ring (a hoisted
 switch; a giant-step switch of the merged form including its decomposition)."""
 
-BABY_US = 72.0
-GIANT_US = 84.0
+BABY_US = 49.0
+GIANT_US = 75.0
 
 
 def divisors(C):
@@ -29,24 +29,3 @@ def choose_n1(G, B_out, C, baby_cost=BABY_US, giant_cost=GIANT_US):
         if best is None or cost < best[0] - 1e-9 or (abs(cost - best[0]) <= 1e-9 and N1 > best[1]):
             best = (cost, N1)
     return best[1]
-
-
-def ciphertext_bytes(N, L):
-    """Serialized size of a ciphertext with L RNS limbs (Sec. 5): two polynomials of N 8-byte residues per limb."""
-    return 2 * N * L * 8
-
-
-def blocks(d, C):
-    """Ciphertext blocks of a d-column object with C active columns per ciphertext (Sec. 3.2): ceil(d / C)."""
-    return -(-d // C)
-
-
-def segments(n, m):
-    """N_seg of Sec. 3.1: n = m * N_seg slots."""
-    assert n % m == 0
-    return n // m
-
-
-def complex_pairs(G):
-    """U = ceil(G / 2) complexified inputs x^(2u) + i x^(2u+1) (Sec. 3.2)."""
-    return -(-G // 2)

@@ -1,7 +1,13 @@
-"""Host logic against the few values the paper prints for this path (tests/golden/paper_values.txt)."""
+"""The few values the paper prints for this path (tests/golden/paper_values.txt), reproduced by the oracle's packing and
+ciphertext layout and by the product's host-side packing: block counts, segment counts, complexified input counts,
+ciphertext bytes."""
 import os
 
-from paper_2604_09975_amd import plan
+import numpy as np
+
+import oracle
+from oracle import encoding as OE
+from paper_2604_09975_amd import client as CL
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -16,26 +22,49 @@ def rows():
     return out
 
 
+def ct_bytes(N, L):
+    """Bytes of a fresh ciphertext as the oracle lays it out (Sec. 5: two polynomials of N residues per limb)."""
+    logN = N.bit_length() - 1
+    dnum = 3
+    O = oracle.Oracle(logN, oracle.find_primes(50, logN, L), oracle.find_primes(60, logN, L // dnum), dnum)
+    z = np.zeros(N, dtype=np.int64)
+    ct = O.encrypt(L, z, np.zeros(N, dtype=np.int8), np.zeros((L, N), dtype=np.uint64), z)
+    return ct.nbytes
+
+
+def blocks(d, C, n=16384, m=128):
+    """Ciphertexts that hold a d-column matrix with C active columns each: what the two packers emit."""
+    X = np.arange(m * d, dtype=np.float64).reshape(m, d)
+    a, b = OE.pack_columns(X, n, C), CL.pack_columns(X, n, C)
+    assert np.array_equal(a, b)
+    return a.shape[0]
+
+
+def segments(n, m):
+    """Segments of m slots in a ciphertext of n slots, read off the packed layout: with C = n/m every segment c
+    holds column c, so the number of distinct columns found at stride m is N_seg."""
+    C = n // m
+    X = np.tile(np.arange(1, C + 1, dtype=np.float64), (m, 1))          # column c is constant c + 1
+    packed = OE.pack_columns(X, n, C)
+    assert packed.shape == (1, n)
+    firsts = packed[0, ::m]
+    assert np.array_equal(packed[0], np.repeat(firsts, m))
+    return len(set(firsts.tolist()))
+
+
+def pairs(G, n=16384, m=128, C=128):
+    """Complexified inputs for G real input groups: what the two packers emit."""
+    X = np.arange(m * G * C, dtype=np.float64).reshape(m, G * C)
+    a, b = OE.pack_columns_complex(X, n, C), CL.pack_columns_complex(X, n, C)
+    assert np.array_equal(a, b)
+    return a.shape[0]
+
+
 def test_paper_values():
     seen = set()
     for key, a, value, cite in rows():
         assert cite, "every golden value carries its citation"
-        if key == "ct_bytes":
-            got = plan.ciphertext_bytes(a["N"], a["L"])
-        elif key == "blocks":
-            got = plan.blocks(a["d"], a["C"])
-        elif key == "segments":
-            got = plan.segments(a["n"], a["m"])
-        elif key == "pairs":
-            got = plan.complex_pairs(a["G"])
-        else:
-            raise AssertionError(key)
+        got = {"ct_bytes": ct_bytes, "blocks": blocks, "segments": segments, "pairs": pairs}[key](**a)
         assert got == value, (key, a, got, value, cite)
         seen.add(key)
     assert seen == {"ct_bytes", "blocks", "segments", "pairs"}
-
-
-def test_layout_sizes_match_the_library_s_buffers():
-    # a ciphertext buffer of the library is [2][level][N] 8-byte words: the paper's ct_bytes
-    N, level = 1 << 16, 24
-    assert 2 * level * N * 8 == plan.ciphertext_bytes(N, level)
