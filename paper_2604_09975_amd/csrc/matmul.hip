@@ -1105,12 +1105,22 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             for (size_t i0 = 0; i0 < ps.size(); i0 += mg_rots) {
                 MergedRot rots;
                 rots.n_rot = (u32)std::min<size_t>(mg_rots, ps.size() - i0);
+                // the group's accumulators, rotation-major, are decomposed in as few launches as the batch size
+                // allows (their digits fill d_mdig in the same order); the key-switch scratch is idle until the
+                // ModDown and holds the coefficient-domain c1 of a whole batch
+                const u32 n_dec = rots.n_rot * nb;
+                for (u32 c0 = 0; c0 < n_dec; c0 += ROT_BATCH) {
+                    const u32 cn = std::min(ROT_BATCH, n_dec - c0);
+                    const u64 *c1s[ROT_BATCH];
+                    for (u32 c = 0; c < cn; ++c) {
+                        const u32 i = (c0 + c) / nb, r = (c0 + c) % nb;
+                        c1s[c] = d_acc + ((size_t)(b0 + r) * N2 + ps[i0 + i]) * ctw + (size_t)level * N;
+                    }
+                    rc = decompose(P, c1s, cn, level, d_mdig + (size_t)c0 * dig_w, d_work, stream);
+                    if (rc) return rc;
+                }
                 for (u32 i = 0; i < rots.n_rot; ++i) {
                     const u32 p = ps[i0 + i];
-                    const u64 *c1s[ROT_BATCH];
-                    for (u32 r = 0; r < nb; ++r) c1s[r] = d_acc + ((size_t)(b0 + r) * N2 + p) * ctw + (size_t)level * N;
-                    rc = decompose(P, c1s, nb, level, d_mdig + (size_t)i * nb * dig_w, d_tmp, stream);
-                    if (rc) return rc;
                     rots.key[i] = giant_keys[p - 1]->d_key;
                     rots.galois_elt[i] = giant_g[p];
                     rots.c0_off[i] = (size_t)p * ctw;
