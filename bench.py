@@ -125,7 +125,8 @@ def measured_ceilings(B, P):
     del src, dst
     lanes, iters = 1 << 20, 2000
     sink = torch.empty(lanes, dtype=torch.int64, device="cuda")
-    for name, kind, limb in (("fp64_mulmod_per_s", B.PROBE_FP64, 0), ("int64_mulmod_per_s", B.PROBE_INT64, P.L)):
+    for name, kind, limb in (("fp64_mulmod_per_s", B.PROBE_FP64, 0), ("int64_mulmod_per_s", B.PROBE_INT64, P.L),
+                             ("int64_lazy_mulmod_per_s", B.PROBE_INT64_LAZY, P.L)):
         if kind == B.PROBE_FP64 and P.q[0] >> 50:
             continue
         out[name] = 4.0 * lanes * iters / timed(lambda: B.ckks_probe_mulmod(P, limb, kind, lanes, iters, sink), 3)

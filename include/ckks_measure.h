@@ -34,6 +34,8 @@ int ckks_probe_stream(uint64_t *d_dst, const uint64_t *d_src, uint64_t n_words /
 
 #define CKKS_PROBE_INT64 0u /* 64-bit Montgomery product (any prime of the chain) */
 #define CKKS_PROBE_FP64 1u  /* exact product in doubles (primes below 2^50) */
+#define CKKS_PROBE_INT64_LAZY 2u /* the transforms' integer product: constant factor w stored with floor(w 2^64 / q),
+                                    result kept in [0, 2q) along the chain (primes below 2^62) */
 /* Every one of n_threads lanes (a multiple of 256) runs four independent chains of `iters` dependent products
  * x <- x * psi mod q, q = prime `limb` (ciphertext primes first, then special), psi its 2N-th root
  * (ckks_params_root), chain c of lane t starting from (4t + c + 1) mod 2^20; d_out[t] (device, n_threads words) is

@@ -396,7 +396,7 @@ def ckks_profile_end(P):
 
 
 PROBE_COPY, PROBE_READ, PROBE_WRITE = 0, 1, 2
-PROBE_INT64, PROBE_FP64 = 0, 1
+PROBE_INT64, PROBE_FP64, PROBE_INT64_LAZY = 0, 1, 2
 
 
 def ckks_probe_stream(d_dst, d_src, mode):

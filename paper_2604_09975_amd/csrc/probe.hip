@@ -39,8 +39,27 @@ __global__ __launch_bounds__(PROBE_THREADS) void probe_mulmod_int_kernel(u64 *__
     u64 x[4];
     for (u32 c = 0; c < 4; ++c) x[c] = (t * 4ull + c + 1) % (1u << 20);
     for (u32 i = 0; i < iters; ++i)
+#pragma unroll
         for (u32 c = 0; c < 4; ++c) x[c] = mont_mul(x[c], w, m);
     out[t] = x[0] ^ x[1] ^ x[2] ^ x[3];
+}
+
+// the product of the integer butterflies: x * w - floor(x * w' / 2^64) * q with w' = floor(w * 2^64 / q), in [0, 2q)
+__global__ __launch_bounds__(PROBE_THREADS) void probe_mulmod_lazy_kernel(u64 *__restrict__ out, u64 q, u64 w, u64 ws,
+                                                                          u32 iters) {
+    const u32 t = blockIdx.x * PROBE_THREADS + threadIdx.x;
+    FieldInt f;
+    f.q = q;
+    f.q2 = 2 * q;
+    f.tw = nullptr;
+    f.n0 = f.n1 = TwInt{0, 0};
+    const TwInt tw{w, ws};
+    u64 x[4];
+    for (u32 c = 0; c < 4; ++c) x[c] = (t * 4ull + c + 1) % (1u << 20);
+    for (u32 i = 0; i < iters; ++i)
+#pragma unroll
+        for (u32 c = 0; c < 4; ++c) x[c] = f.mul(x[c], tw);
+    out[t] = f.out(x[0]) ^ f.out(x[1]) ^ f.out(x[2]) ^ f.out(x[3]);
 }
 
 __global__ __launch_bounds__(PROBE_THREADS) void probe_mulmod_fp_kernel(u64 *__restrict__ out, ModFp mf, double w,
@@ -54,6 +73,7 @@ __global__ __launch_bounds__(PROBE_THREADS) void probe_mulmod_fp_kernel(u64 *__r
     double x[4];
     for (u32 c = 0; c < 4; ++c) x[c] = (double)((t * 4ull + c + 1) % (1u << 20));
     for (u32 i = 0; i < iters; ++i)
+#pragma unroll
         for (u32 c = 0; c < 4; ++c) x[c] = f.mul(x[c], w);     // |result| <= q/2 + small: stays a valid operand
     out[t] = f.out(x[0]) ^ f.out(x[1]) ^ f.out(x[2]) ^ f.out(x[3]);
 }
@@ -87,7 +107,7 @@ int ckks_probe_stream(uint64_t *d_dst, const uint64_t *d_src, uint64_t n_words, 
 
 int ckks_probe_mulmod(const ckks_params_t *P, uint32_t limb, uint32_t kind, uint32_t n_threads, uint32_t iters,
                       uint64_t *d_out, void *stream) {
-    if (!P || !d_out || limb >= P->W || kind > CKKS_PROBE_FP64 || n_threads == 0 || n_threads % PROBE_THREADS) {
+    if (!P || !d_out || limb >= P->W || kind > CKKS_PROBE_INT64_LAZY || n_threads == 0 || n_threads % PROBE_THREADS) {
         set_error("ckks_probe_mulmod: bad arguments (limb %u, kind %u, %u threads: a positive multiple of %u)", limb,
                   kind, n_threads, PROBE_THREADS);
         return CKKS_E_INVAL;
@@ -104,6 +124,14 @@ int ckks_probe_mulmod(const ckks_params_t *P, uint32_t limb, uint32_t kind, uint
         const double wc = (double)(w > q / 2 ? (int64_t)w - (int64_t)q : (int64_t)w);
         hipLaunchKernelGGL(probe_mulmod_fp_kernel, dim3(n_threads / PROBE_THREADS), dim3(PROBE_THREADS), 0,
                            (hipStream_t)stream, d_out, mf, wc, iters);
+    } else if (kind == CKKS_PROBE_INT64_LAZY) {
+        if (q >> 62) {
+            set_error("ckks_probe_mulmod: the lazy integer product needs a prime below 2^62 (limb %u is not)", limb);
+            return CKKS_E_INVAL;
+        }
+        const u64 ws = (u64)(((unsigned __int128)w << 64) / q);
+        hipLaunchKernelGGL(probe_mulmod_lazy_kernel, dim3(n_threads / PROBE_THREADS), dim3(PROBE_THREADS), 0,
+                           (hipStream_t)stream, d_out, q, w, ws, iters);
     } else {
         const ModConst &m = P->hmod[limb];
         const u64 wm = (u64)(((unsigned __int128)w << 64) % q);

@@ -186,12 +186,13 @@ def test_shift_bank_errors():
 
 
 def test_probe_kernels_compute_what_they_time():
-    """The ceiling probes: the product chains end in x0 * psi^iters mod q (both arithmetics, checked against
+    """The ceiling probes: the product chains end in x0 * psi^iters mod q (all three arithmetics, checked against
     Python integers), the copy kernel copies, the write kernel writes every word; bad arguments are refused."""
     from paper_2604_09975_amd import binding as B
     O, P = make_pair(W.BIG_RING)
     lanes, iters = 512, 37
-    for kind, limb in ((B.PROBE_FP64, 0), (B.PROBE_FP64, 23), (B.PROBE_INT64, 5), (B.PROBE_INT64, 24 + 7)):
+    for kind, limb in ((B.PROBE_FP64, 0), (B.PROBE_FP64, 23), (B.PROBE_INT64, 5), (B.PROBE_INT64, 24 + 7),
+                       (B.PROBE_INT64_LAZY, 3), (B.PROBE_INT64_LAZY, 24), (B.PROBE_INT64_LAZY, 24 + 7)):
         q = int(O.moduli[limb])
         psi = B.ckks_params_root(P, limb)
         assert pow(psi, 2 * O.N, q) == 1 and pow(psi, O.N, q) == q - 1
