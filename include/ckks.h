@@ -203,6 +203,11 @@ void ckks_weights_destroy(ckks_weights_t *w);
                                        ModDown of the giant step and the rescale share one pass: the dropped limb is
                                        taken in the coefficient domain before the correction's forward transform, so
                                        each remaining limb is transformed once for both.  CKKS_E_LEVEL at level 1. */
+#define CKKS_MATMUL_CONJ_PER_ACC 4u /* flags (needs conj_key, else CKKS_E_NOKEY): the decomplexification in the order
+                                       Sec. 3.2 displays it, acc_{b,p} += conj(acc_{b,p}) for every giant-step
+                                       accumulator before the fold over p, N2 conjugations per output block instead of
+                                       one.  Automorphisms commute, so both orders decrypt to the same values; the
+                                       residues differ (other noise) and each order is defined bit for bit. */
 int ckks_ctpt_matmul(ckks_params_t *params, const ckks_weights_t *w, const uint64_t *d_ct_x,
                      const ckks_gkey_t *const *baby_keys, const ckks_gkey_t *const *giant_keys,
                      const ckks_gkey_t *conj_key, uint32_t flags, uint64_t *d_ct_y, ckks_counters_t *counters,

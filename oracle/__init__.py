@@ -56,7 +56,7 @@ def _lib():
     lib.orc_expand_plain.argtypes = [C.c_void_p, C.c_int, _i64p, _u64p]
     lib.orc_ctpt_matmul.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                     _i64p, _i64p, C.c_uint64, _u64p, C.POINTER(_u64p), C.POINTER(_u64p), _u64p,
-                                    _u64p, C.c_int, C.c_int, C.c_int]
+                                    _u64p, C.c_int, C.c_int, C.c_int, C.c_int]
     lib.orc_rescale.argtypes = [C.c_void_p, _u64p, C.c_int, C.c_int, _u64p]
     lib.orc_galois_keygen.argtypes = [C.c_void_p, _i8p, C.c_uint64, _u64p, _i64p, _u64p]
     lib.orc_add.argtypes = [C.c_void_p, _u64p, _u64p, C.c_int, C.c_int, _u64p]
@@ -220,7 +220,7 @@ class Oracle:
         return out
 
     def ctpt_matmul(self, level, m, G, B_out, N1, N2, diag, bias, bias_mul, ct_x, baby_keys, giant_keys,
-                    b_first=0, b_count=None, conj_key=None, merged=False):
+                    b_first=0, b_count=None, conj_key=None, merged=False, conj_per_acc=False):
         if b_count is None:
             b_count = B_out
         d, dp = _i64(diag)
@@ -250,7 +250,7 @@ class Oracle:
             keep.append(cka)
         out = np.zeros((B_out, 2, level, self.N), dtype=np.uint64)
         LIB.orc_ctpt_matmul(self._h, level, m, G, B_out, N1, N2, dp, bp, bias_mul, xp, bk, gk, ck,
-                            out.ctypes.data_as(_u64p), b_first, b_count, int(merged))
+                            out.ctypes.data_as(_u64p), b_first, b_count, int(merged), int(conj_per_acc))
         return out
 
     def rescale(self, ct, level):

@@ -474,6 +474,8 @@ void orc_expand_plain(const orc_ctx *c, int level, const i64 *coef, u64 *out) {
  *   acc_{b,p} = sum_g sum_q x^(g)_q (.) w_{b,p,g,q}
  *   y_b = acc_{b,0} + sum_{p>=1} rot(acc_{b,p}; p*N1*m)   (each a full key switch)
  *   y_b += conj(y_b)                                       (only if conj_key is given)
+ *   conj_per_acc (variant, needs conj_key): acc_{b,p} += conj(acc_{b,p}) for every p before the giant step, in
+ *   place of the line above: the order in which Sec. 3.2 writes the decomplexification.
  *   y_b.c0 += bias_b * bias_mul.
  * diag [B_out][N2][G][N1][N] int64 coefficient-domain encodings; bias
  * [B_out][N] int64 or NULL; baby_keys[q-1] for step q*m, giant_keys[p-1] for
@@ -482,7 +484,7 @@ void orc_expand_plain(const orc_ctx *c, int level, const i64 *coef, u64 *out) {
 void orc_ctpt_matmul(const orc_ctx *c, int level, int m, int G, int B_out, int N1, int N2,
                      const i64 *diag, const i64 *bias, u64 bias_mul, const u64 *ct_x,
                      const u64 *const *baby_keys, const u64 *const *giant_keys, const u64 *conj_key, u64 *ct_y,
-                     int b_first, int b_count, int merged) {
+                     int b_first, int b_count, int merged, int conj_per_acc) {
     u64 N = c->N;
     u64 ctw = (u64)2 * level * N;
     (void)B_out;
@@ -519,8 +521,22 @@ void orc_ctpt_matmul(const orc_ctx *c, int level, int m, int G, int B_out, int N
             free(w);
         }
         u64 *y = ct_y + (u64)b * ctw;
-        memcpy(y, acc, sizeof(u64) * ctw);
         u64 *rot = (u64 *)malloc(sizeof(u64) * ctw);
+        /* decomplexification as Sec. 3.2 displays it: the real part of every giant-step accumulator is taken first,
+         * c_p = (1/2)(c~_p + conj(c~_p)) with the 1/2 in the weights, and the fold over p follows.  N2 conjugations
+         * per output block. */
+        if (conj_key && conj_per_acc) {
+            u64 g = orc_galois_elt(c, 0, 1);
+            for (int p = 0; p < N2; p++) {
+                u64 *a = acc + (u64)p * ctw;
+                orc_rotate_hoisted(c, a, level, &g, 1, &conj_key, rot);
+                for (int ci = 0; ci < 2 * level; ci++) {
+                    u64 qi = c->mod[ci % level];
+                    for (u64 k = 0; k < N; k++) a[(u64)ci * N + k] = addmod(a[(u64)ci * N + k], rot[(u64)ci * N + k], qi);
+                }
+            }
+        }
+        memcpy(y, acc, sizeof(u64) * ctw);
         if (!merged) {
             for (int p = 1; p < N2; p++) {
                 u64 g = orc_galois_elt(c, (i64)p * N1 * m, 0);
@@ -557,7 +573,7 @@ void orc_ctpt_matmul(const orc_ctx *c, int level, int m, int G, int B_out, int N
         /* decomplexification (Sec. 3.2): with complexified inputs x^(2u) + i x^(2u+1) and weights that carry
          * the factor 1/2, the real part is y + conj(y).  Taken once per output block after the giant-step fold,
          * the count of App. A.2.2 (#conj = O(B_out)). */
-        if (conj_key) {
+        if (conj_key && !conj_per_acc) {
             u64 g = orc_galois_elt(c, 0, 1);
             orc_rotate_hoisted(c, y, level, &g, 1, &conj_key, rot);
             for (int ci = 0; ci < 2 * level; ci++) {

@@ -278,6 +278,7 @@ def ckks_weights_load(P, level, m, Cc, G, B_out, N1, d_coeffs, d_bias_coeffs=Non
 
 MATMUL_MERGED_GIANT = 1
 MATMUL_RESCALE = 2
+MATMUL_CONJ_PER_ACC = 4
 
 
 def ckks_ctpt_matmul(P, w, d_ct_x, baby_keys, giant_keys, d_ct_y=None, conj_key=None, flags=0):

@@ -889,9 +889,14 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         set_error("ckks_ctpt_matmul: conj_key is not a key for conjugation");
         return CKKS_E_INVAL;
     }
-    if (flags & ~(uint32_t)(CKKS_MATMUL_MERGED_GIANT | CKKS_MATMUL_RESCALE)) {
+    if (flags & ~(uint32_t)(CKKS_MATMUL_MERGED_GIANT | CKKS_MATMUL_RESCALE | CKKS_MATMUL_CONJ_PER_ACC)) {
         set_error("ckks_ctpt_matmul: unknown flags 0x%x", flags);
         return CKKS_E_INVAL;
+    }
+    const bool conj_per_acc = (flags & CKKS_MATMUL_CONJ_PER_ACC) != 0;
+    if (conj_per_acc && !conj_key) {
+        set_error("ckks_ctpt_matmul: CKKS_MATMUL_CONJ_PER_ACC needs conj_key");
+        return CKKS_E_NOKEY;
     }
     for (size_t d = 0; d < w->loaded.size(); ++d)
         if (!w->loaded[d]) {
@@ -1064,6 +1069,34 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         CKKS_HIP(hipEventRecord(P->prof_ev[P->prof_used + 1], stream));
         P->prof_used += 2;
     }
+    // 2b. decomplexification in the order Sec. 3.2 displays it: acc_{b,p} += conj(acc_{b,p}) for every accumulator,
+    //     before the fold over p.  The switch gathers from its source while it writes, so it goes to the output
+    //     area (not yet in use) first.
+    if (conj_per_acc) {
+        const u32 step = std::min(batch, B);
+        for (u32 a0 = 0; a0 < BP; a0 += step) {
+            const u32 na = std::min(step, BP - a0);
+            SwitchItem items[ROT_BATCH];
+            const u64 *c1s[ROT_BATCH];
+            for (u32 r = 0; r < na; ++r) c1s[r] = d_acc + (size_t)(a0 + r) * ctw + (size_t)level * N;
+            rc = decompose(P, c1s, na, level, d_digits, d_tmp, stream);
+            if (rc) return rc;
+            for (u32 r = 0; r < na; ++r) {
+                items[r].digits = d_digits + (size_t)r * dig_w;
+                items[r].c1 = c1s[r];
+                items[r].c0 = d_acc + (size_t)(a0 + r) * ctw;
+                items[r].key = conj_key->d_key;
+                items[r].dst = d_ct_y + (size_t)r * ctw;
+                items[r].galois_elt = conj_key->galois_elt;
+                items[r].accumulate = 0;
+            }
+            rc = switch_batch(P, level, items, na, d_work, stream);
+            if (rc) return rc;
+            hipLaunchKernelGGL(add_rows_kernel, dim3(N / EW_THREADS, na * 2 * level), dim3(EW_THREADS), 0, stream,
+                               d_acc + (size_t)a0 * ctw, d_ct_y, P->d_mod, level, N);
+            CKKS_LAUNCH_CHECK("add_rows_kernel");
+        }
+    }
     // 3. giant steps: y_b = acc_{b,0} + sum_p rot(acc_{b,p})
     for (u32 b0 = 0; b0 < B; b0 += 65535) {
         hipLaunchKernelGGL(copy_blocks_kernel, dim3((u32)(ctw / (2 * EW_THREADS)), 1, std::min<u32>(B - b0, 65535)),
@@ -1175,7 +1208,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     }
     // 3b. decomplexification: y_b += conj(y_b), one key switch per output block.  The switch gathers from
     //     y_b while it writes, so it goes to the (now free) accumulator area first.
-    if (conj_key) {
+    if (conj_key && !conj_per_acc) {
         for (u32 b0 = 0; b0 < B; b0 += batch) {
             const u32 nb = std::min(batch, B - b0);
             SwitchItem items[ROT_BATCH];
@@ -1218,7 +1251,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             ks += (g != 1) ? G : 0;
         }
         for (u32 p = 1; p < N2; ++p) ks += (giant_g[p] != 1) ? B : 0;
-        if (conj_key) ks += B;
+        if (conj_key) ks += conj_per_acc ? BP : B;
         counters->key_switches = ks;
         counters->ptmuls = (u64)GQ * BP;
         counters->limb_ntts = P->limb_ntts - ntt0;

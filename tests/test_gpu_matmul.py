@@ -273,6 +273,25 @@ def test_complex_pair_compression_with_decomplexification(d_in, spec, real_tail)
     slots = np.stack([cl.decrypt_slots(got[b], 2, sc * sc / O.q[2], nlimbs=2) for b in range(B_out)])
     assert np.abs(E.unpack_columns(slots.real, m, C, d_out) - (X @ Wm + bias)).max() <= 1e-3
     assert np.abs(slots.imag).max() <= 1e-3
+    # the order Sec. 3.2 displays: the real part of every giant-step accumulator before the fold (N2 conjugations
+    # per block), with either giant-step order after it; other residues, the same values
+    for merged in (False, True):
+        fl = B.MATMUL_CONJ_PER_ACC | (B.MATMUL_MERGED_GIANT if merged else 0)
+        y2, cnt2 = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, conj_key=conj_h, flags=fl)
+        y2r, _ = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, conj_key=conj_h, flags=fl | B.MATMUL_RESCALE)
+        torch.cuda.synchronize()
+        want2 = O.ctpt_matmul(level, m, U, B_out, N1, N2, diag, bias_c, int(sc), ct_x, baby_np, giant_np,
+                              conj_key=conj_np, merged=merged, conj_per_acc=True)
+        assert not (want2 == want).all()
+        assert (to_host(y2) == want2).all()
+        assert (to_host(y2r) == O.rescale(want2, level)).all()
+        assert cnt2.key_switches == U * (N1 - 1) + B_out * (N2 - 1) + B_out * N2
+        got2 = to_host(y2r)
+        slots2 = np.stack([cl.decrypt_slots(got2[b], 2, sc * sc / O.q[2], nlimbs=2) for b in range(B_out)])
+        assert np.abs(E.unpack_columns(slots2.real, m, C, d_out) - (X @ Wm + bias)).max() <= 1e-3
+    with pytest.raises(B.CkksError) as e:
+        B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, flags=B.MATMUL_CONJ_PER_ACC)
+    assert e.value.code == -3                  # CKKS_E_NOKEY: the flag without a conjugation key
 
 
 def test_fused_qk_projection():
@@ -388,7 +407,7 @@ def test_argument_checks_enqueue_nothing():
     assert "diagonal 5 of 16" in str(e.value)
     B.ckks_weights_set_diagonals(w, 5, torch.zeros((11, N), dtype=torch.int64, device="cuda"))
     with pytest.raises(B.CkksError) as e:
-        B.ckks_ctpt_matmul(P, w, x, baby, giant, flags=6)
+        B.ckks_ctpt_matmul(P, w, x, baby, giant, flags=8)
     assert e.value.code == -1 and "flags" in str(e.value)
     with pytest.raises(B.CkksError) as e:
         B.ckks_ctpt_matmul(P, w, x, baby, giant, d_ct_y=x)

@@ -60,6 +60,8 @@ MUTANTS = [
     ("conj_added_twice", "orc_rotate_hoisted(c, y, level, &g, 1, &conj_key, rot);",
      "orc_rotate_hoisted(c, y, level, &g, 1, &conj_key, rot); memcpy(y, rot, sizeof(u64) * 2 * level * N);",
      ["test_oracle_complex.py"]),
+    ("conj_per_accumulator_skips_the_first", "for (int p = 0; p < N2; p++) {\n                u64 *a = acc + (u64)p * ctw;",
+     "for (int p = 1; p < N2; p++) {\n                u64 *a = acc + (u64)p * ctw;", ["test_oracle_complex.py"]),
     ("bias_without_scale_factor", "u64 bm = bias_mul % qi;", "u64 bm = 1;", ["test_oracle_matmul.py"]),
     ("ctmul_cross_term_dropped",
      "t1[(u64)i * N + x] = addmod(mulmod(a0[x], b1[x], q), mulmod(a1[x], b0[x], q), q);",
