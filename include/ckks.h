@@ -191,8 +191,10 @@ void ckks_weights_destroy(ckks_weights_t *w);
  * d_ct_x [G][2][level][N]; baby_keys: N1-1 handles for steps q*m (q = 1..);
  * giant_keys: N2-1 handles for steps p*N1*m; conj_key: NULL or the key of
  * CKKS_STEP_CONJ; d_ct_y [B_out][2][level][N] at the
- * input level and scale(x)*scale(w) -- follow with ckks_rescale; may not overlap
+ * input level and scale(x)*scale(w) -- follow with ckks_rescale, or pass
+ * CKKS_MATMUL_RESCALE and receive [B_out][2][level-1][N]; may not overlap
  * d_ct_x.  counters (host, may be NULL) receives the operation counts.
+ * CKKS_E_NOKEY for a missing key of a step that is not the identity.
  * CKKS_E_INVAL also for flags with unknown bits and for weights of which some
  * diagonal was never stored (the message names the first one): nothing is
  * enqueued then. */
