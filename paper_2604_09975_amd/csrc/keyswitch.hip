@@ -553,27 +553,31 @@ constexpr u32 MID_COLS = 32, MID_TG = 8, MID_MAX_LEVEL = 32;
 // w_i = sum_k y_k (P/p_k mod q_i) for the two coefficients of a thread, as doubles with |w| <= q/2: the exact fp64 sums
 // of moddown_conv_kernel (20-bit pieces of y times 25-bit halves of the factors)
 template <bool K8>
-__device__ __forceinline__ void mid_convert(const double (&yp)[2][8][3], const double *__restrict__ f, u32 K, double q,
-                                            double u, double (&v)[2]) {
-    double lo[2] = {0.0, 0.0}, hi[2] = {0.0, 0.0};
+__device__ __forceinline__ double mid_convert(const double (&yp)[8][3], const double *__restrict__ f, u32 K, double q,
+                                              double u) {
+    double lo = 0.0, hi = 0.0;
 #pragma unroll
     for (u32 k = 0; k < 8; ++k)
         if (K8 || k < K) {
 #pragma unroll
             for (u32 a = 0; a < 3; ++a) {
-                const double f0 = f[(k * 3 + a) * 2 + 0], f1 = f[(k * 3 + a) * 2 + 1];
-#pragma unroll
-                for (u32 e = 0; e < 2; ++e) {
-                    lo[e] = fma(yp[e][k][a], f0, lo[e]);
-                    hi[e] = fma(yp[e][k][a], f1, hi[e]);
-                }
+                lo = fma(yp[k][a], f[(k * 3 + a) * 2 + 0], lo);
+                hi = fma(yp[k][a], f[(k * 3 + a) * 2 + 1], hi);
             }
         }
+    const double tt = hi * 33554432.0;                              // exact: a power of two
+    const double x = fma(-rint(tt * u), q, tt) + lo;                // |.| < 0.75 q, plus low < 2^51
+    return fma(-rint(x * u), q, x);                                 // |v| <= q/2
+}
+
+// the 20-bit pieces of the K special-limb values of one coefficient, as doubles
+__device__ __forceinline__ void mid_pieces(const u64 (&yraw)[8], double (&yp)[8][3]) {
 #pragma unroll
-    for (u32 e = 0; e < 2; ++e) {
-        const double tt = hi[e] * 33554432.0;                       // exact: a power of two
-        double x = fma(-rint(tt * u), q, tt) + lo[e];               // |.| < 0.75 q, plus low < 2^51
-        v[e] = fma(-rint(x * u), q, x);                             // |v| <= q/2
+    for (u32 k = 0; k < 8; ++k) {
+        const u64 v = yraw[k];
+        yp[k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
+        yp[k][1] = __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
+        yp[k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
     }
 }
 
@@ -614,25 +618,13 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
             pass_a16_body<true>(make_field_int(mods, tw_inv, ninv_dn, gl, logN), c0, load, store);
     }
     __syncthreads();
-    // the two coefficients of this thread (rows 2*grp, 2*grp + 1 of this column) leave LDS as they are; their
-    // 20-bit pieces are rebuilt per group of targets, one coefficient at a time (24 doubles live instead of 96)
+    // the two coefficients of this thread (rows 2*grp, 2*grp + 1 of this column) leave LDS as they are
     u64 yraw[2][8];
 #pragma unroll
     for (u32 e = 0; e < 2; ++e)
 #pragma unroll
         for (u32 k = 0; k < 8; ++k) yraw[e][k] = (K8 || k < K) ? ylds[(k * 16 + 2 * grp + e) * MID_COLS + col] : 0;
     __syncthreads();                // every thread has its y: the tile may be overwritten
-    double yp[2][8][3];
-#pragma unroll
-    for (u32 e = 0; e < 2; ++e)
-#pragma unroll
-        for (u32 k = 0; k < 8; ++k) {
-            const u64 v = yraw[e][k];
-            yp[e][k][0] = __longlong_as_double((long long)(0x4330000000000000ull | (v & 0xFFFFFu))) - 4503599627370496.0;
-            yp[e][k][1] =
-                __longlong_as_double((long long)(0x4330000000000000ull | ((v >> 20) & 0xFFFFFu))) - 4503599627370496.0;
-            yp[e][k][2] = __longlong_as_double((long long)(0x4330000000000000ull | (v >> 40))) - 4503599627370496.0;
-        }
     // rescale: the dropped limb first
     double rp[2] = {0.0, 0.0}, hq = 0.0;
     const u32 n_out = RESC ? level - 1 : level;
@@ -644,13 +636,14 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
         fl.u = ml.u;
         fl.n0 = fl.n1 = 0.0;
         fl.tw = nullptr;
-        double wl[2];
-        mid_convert<K8>(yp, dn_matf + (size_t)il * K * 6, K, ml.q, ml.u, wl);
         hq = (double)(mods[il].q >> 1);
 #pragma unroll
         for (u32 e = 0; e < 2; ++e) {
+            double yp[8][3];
+            mid_pieces(yraw[e], yp);
+            const double wl = mid_convert<K8>(yp, dn_matf + (size_t)il * K * 6, K, ml.q, ml.u);
             const double t = fl.in(t_rows[(size_t)pc * N + (2 * grp + e) * 4096 + c0]);
-            double r = t - fl.mul(wl[e], pinvf[il]);
+            double r = t - fl.mul(wl, pinvf[il]);
             fl.norm(r);
             if (r < 0) r += ml.q;                                   // r in [0, q_last)
             r += hq;
@@ -658,29 +651,30 @@ __global__ __launch_bounds__(256) void moddown_mid_kernel(const u64 *__restrict_
         }
     }
     for (u32 i0 = 0; i0 < n_out; i0 += MID_TG) {
-        for (u32 t = 0; t < MID_TG && i0 + t < n_out; ++t) {
-            const u32 i = i0 + t;
-            const double q = modf[i].q, u = modf[i].u;
-            double v[2];
-            mid_convert<K8>(yp, dn_matf + (size_t)i * K * 6, K, q, u, v);
-            if (RESC) {
-                FieldFp fi;
-                fi.q = q;
-                fi.u = u;
-                fi.n0 = fi.n1 = 0.0;
-                fi.tw = nullptr;
-                double hi_ = hq;
-                fi.norm(hi_);                                       // floor(q_last / 2) mod q_i
-                const double pv = pinvf[i];
-#pragma unroll
-                for (u32 e = 0; e < 2; ++e) {
-                    double ri = rp[e];
+        // one coefficient at a time: its 24 pieces are rebuilt per group of targets (24 doubles live instead of 48,
+        // which is what lets four waves share a SIMD)
+#pragma unroll 1
+        for (u32 e = 0; e < 2; ++e) {
+            double yp[8][3];
+            mid_pieces(e ? yraw[1] : yraw[0], yp);
+            const double rpe = e ? rp[1] : rp[0];
+            for (u32 t = 0; t < MID_TG && i0 + t < n_out; ++t) {
+                const u32 i = i0 + t;
+                const double q = modf[i].q, u = modf[i].u;
+                double v = mid_convert<K8>(yp, dn_matf + (size_t)i * K * 6, K, q, u);
+                if (RESC) {
+                    FieldFp fi;
+                    fi.q = q;
+                    fi.u = u;
+                    fi.n0 = fi.n1 = 0.0;
+                    fi.tw = nullptr;
+                    double hi_ = hq, ri = rpe;
+                    fi.norm(hi_);                                   // floor(q_last / 2) mod q_i
                     fi.norm(ri);                                    // r' mod q_i
-                    v[e] = fi.mul(v[e], pv) + (ri - hi_);           // |.| < 2q: the forward round normalises
+                    v = fi.mul(v, pinvf[i]) + (ri - hi_);           // |.| < 2q: the forward round normalises
                 }
+                wlds[(t * 16 + 2 * grp + e) * MID_COLS + col] = (u64)__double_as_longlong(v);
             }
-#pragma unroll
-            for (u32 e = 0; e < 2; ++e) wlds[(t * 16 + 2 * grp + e) * MID_COLS + col] = (u64)__double_as_longlong(v[e]);
         }
         __syncthreads();
         if (i0 + grp < n_out) {
