@@ -895,8 +895,8 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
     const u32 accumulate = it.accumulate;
     auto load = [&](u32 idx) -> u64 { return __builtin_nontemporal_load(wrow + idx); };
     const ModFp mf = modf[i];
-    if (mf.ok)
-        pass_b_fwd_to_lds(make_field_fp(mf, twf_fwd, i, logN), logN, lds, load);
+    if (mf.ok)   // the fp64 epilogue takes the transformed correction as doubles, |x| <= q/2
+        pass_b_fwd_to_lds<true>(make_field_fp(mf, twf_fwd, i, logN), logN, lds, load);
     else
         pass_b_fwd_to_lds(make_field_int(mods, tw_fwd, ninv, i, logN), logN, lds, load);
     // epilogue on pairs of adjacent residues (16-byte accesses to the streamed operands), two pairs at a time so
@@ -947,7 +947,7 @@ __global__ __launch_bounds__(NTT_THREADS) void passb_final_kernel(ItemPack pack,
 #pragma unroll
                     for (u32 j = 0; j < MAX_BETA; ++j)
                         if (j < beta) sum += ff.mul(ff.in(dv[e][z][j]), ff.in(kv[e][j][z]));
-                    const double t = ff.mul(sum, c_sum) - ff.mul(ff.in(lds[lds_pad(loc + z)]), c_w) +
+                    const double t = ff.mul(sum, c_sum) - ff.mul(ff.from_bits(lds[lds_pad(loc + z)]), c_w) +
                                      (ff.in(cv[e][z]) + ff.in(ov[e][z]));
                     out[z] = ff.out(t);
                 } else {

@@ -161,8 +161,10 @@ __device__ __forceinline__ void radix16_inv(const F &f, typename F::T (&v)[16], 
 // between global memory and LDS.  LDS slot of residue e of the tile: lds[lds_pad(e)].
 //
 // forward: load(idx) gives the canonical residue at index idx of the polynomial (round-1 pattern: coalesced); on
-// return the tile's transformed, canonical residues are in LDS and the workgroup is synced.
-template <class F, class Load>
+// return the tile's transformed, canonical residues are in LDS and the workgroup is synced.  RAW: the residues are
+// left in the field's own form instead (f.bits of a value brought back by f.norm: for the fp64 field a double with
+// |x| <= q/2), for a caller that goes on computing in that field and would only convert them back.
+template <bool RAW = false, class F, class Load>
 __device__ __forceinline__ void pass_b_fwd_to_lds(const F &f, u32 logN, u64 *lds, Load load) {
     const u32 tid = threadIdx.x, blk = tid >> 4, c = tid & 15;
     const u32 base = blockIdx.x << 12;
@@ -185,7 +187,14 @@ __device__ __forceinline__ void pass_b_fwd_to_lds(const F &f, u32 logN, u64 *lds
     for (u32 j = 0; j < 16; ++j) v[j] = f.from_bits(lds[lds_pad(contig + j)]);
     radix16_fwd(f, v, logN - 4, run * 16 + c);
 #pragma unroll
-    for (u32 j = 0; j < 16; ++j) lds[lds_pad(contig + j)] = f.out(v[j]);   // a thread's own slots
+    for (u32 j = 0; j < 16; ++j) {                                          // a thread's own slots
+        if (RAW) {
+            f.norm(v[j]);
+            lds[lds_pad(contig + j)] = f.bits(v[j]);
+        } else {
+            lds[lds_pad(contig + j)] = f.out(v[j]);
+        }
+    }
     __syncthreads();
 }
 
