@@ -52,8 +52,9 @@ def test_projection_sweep(seed):
 
 @pytest.mark.parametrize("seed", range(100, 124))
 def test_pair_compression_sweep(seed):
-    """Complexified inputs x^(2u) + i x^(2u+1), weights (W_even - i W_odd)/2, one conjugation per output block; when
-    the number of real input groups is odd the last complexified group is real and may keep half records."""
+    """Complexified inputs x^(2u) + i x^(2u+1), weights (W_even - i W_odd)/2, one conjugation per output block (odd
+    seeds: one per giant-step accumulator, the order Sec. 3.2 displays); when the number of real input groups is odd
+    the last complexified group is real and may keep half records."""
     from paper_2604_09975_amd import binding as B
     c = _draw(seed)
     O = helpers.small_oracle(c["logN"], L=c["L"], K=c["K"], dnum=c["dnum"], qbits=c["qbits"], pbits=c["pbits"])
@@ -79,13 +80,16 @@ def test_pair_compression_sweep(seed):
     w = B.ckks_weights_create(P, level, m, C, U, B_out, N1)
     B.ckks_weights_set_diagonals(w, 0, to_dev(diag.reshape(-1, N)))
     B.ckks_weights_set_bias(w, to_dev(bias_c), int(sc))
+    per_acc = seed % 2 == 1
     y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h, conj_key=conj_h,
-                                    flags=B.MATMUL_MERGED_GIANT if c["merged"] else 0)
+                                    flags=(B.MATMUL_MERGED_GIANT if c["merged"] else 0) |
+                                          (B.MATMUL_CONJ_PER_ACC if per_acc else 0))
     y_res = B.ckks_rescale(P, y_dev, level, B_out)
     torch.cuda.synchronize()
     want = O.ctpt_matmul(level, m, U, B_out, N1, N2, diag, bias_c, int(sc), ct_x, baby_np, giant_np,
-                         merged=c["merged"], conj_key=conj_np)
+                         merged=c["merged"], conj_key=conj_np, conj_per_acc=per_acc)
     assert (to_host(y_dev) == want).all(), c
+    assert cnt.key_switches >= B_out * (N2 if per_acc else 1)
     got = to_host(y_res)
     assert (got == O.rescale(want, level)).all(), c
     slots = np.stack([cl.decrypt_slots(got[b], level - 1, sc * sc / O.q[level - 1], nlimbs=min(level - 1, 2))
