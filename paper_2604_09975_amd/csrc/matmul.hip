@@ -213,13 +213,14 @@ __global__ __launch_bounds__(EW_THREADS) void copy_blocks_kernel(u64 *__restrict
         *reinterpret_cast<const vec_t *>(src + blockIdx.z * src_stride + k);
 }
 
-// y[b][0][i][.] += bias[b][i][.]: blockIdx.y = limb, blockIdx.z = output block, two residues per thread
-__global__ __launch_bounds__(EW_THREADS) void add_bias_kernel(u64 *__restrict__ y, const u64 *__restrict__ bias,
+// c0 of block b (at y + b * y_stride) += bias[b]: blockIdx.y = limb, blockIdx.z = output block, two residues per thread
+__global__ __launch_bounds__(EW_THREADS) void add_bias_kernel(u64 *__restrict__ y, size_t y_stride,
+                                                              const u64 *__restrict__ bias,
                                                               const ModConst *__restrict__ mods, u32 level, u32 N) {
     typedef u64 vec_t __attribute__((ext_vector_type(2)));
     const u32 k = (blockIdx.x * EW_THREADS + threadIdx.x) * 2, i = blockIdx.y, b = blockIdx.z;
     const u64 q = mods[i].q;
-    vec_t *dst = reinterpret_cast<vec_t *>(y + ((size_t)b * 2 * level + i) * N + k);
+    vec_t *dst = reinterpret_cast<vec_t *>(y + (size_t)b * y_stride + (size_t)i * N + k);
     const vec_t s = *reinterpret_cast<const vec_t *>(bias + ((size_t)b * level + i) * N + k);
     vec_t v = *dst;
     v[0] = add_mod(v[0], s[0], q);
@@ -1097,8 +1098,16 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
             CKKS_LAUNCH_CHECK("add_rows_kernel");
         }
     }
-    // 3. giant steps: y_b = acc_{b,0} + sum_p rot(acc_{b,p})
-    for (u32 b0 = 0; b0 < B; b0 += 65535) {
+    // 3. giant steps: y_b = acc_{b,0} + sum_p rot(acc_{b,p}).  Where ModDown and rescale are one pass and at least one
+    //    rotation needs a key, that pass writes the caller's buffer itself and y_b is assembled where acc_{b,0} lies;
+    //    otherwise y_b starts as a copy of acc_{b,0} in the output (or its full-level stand-in).
+    std::vector<u32> ps;                                      // giant rotations that are not a full turn
+    for (u32 p = 1; p < N2; ++p)
+        if (giant_g[p] != 1) ps.push_back(p);
+    const bool in_place = fused_rescale && !ps.empty();
+    u64 *y_base = in_place ? d_acc : d_ct_y;
+    const size_t y_stride = in_place ? (size_t)N2 * ctw : ctw;
+    for (u32 b0 = 0; !in_place && b0 < B; b0 += 65535) {
         hipLaunchKernelGGL(copy_blocks_kernel, dim3((u32)(ctw / (2 * EW_THREADS)), 1, std::min<u32>(B - b0, 65535)),
                            dim3(EW_THREADS), 0, stream, d_ct_y + (size_t)b0 * ctw, d_acc + (size_t)b0 * N2 * ctw, ctw,
                            (size_t)N2 * ctw);
@@ -1107,7 +1116,7 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
     auto add_bias = [&]() -> int {
         for (u32 b0 = 0; w->d_bias && b0 < B; b0 += 65535) {
             hipLaunchKernelGGL(add_bias_kernel, dim3(N / (2 * EW_THREADS), level, std::min<u32>(B - b0, 65535)),
-                               dim3(EW_THREADS), 0, stream, d_ct_y + (size_t)b0 * ctw,
+                               dim3(EW_THREADS), 0, stream, y_base + (size_t)b0 * y_stride, y_stride,
                                w->d_bias + (size_t)b0 * level * N, P->d_mod, level, N);
             CKKS_LAUNCH_CHECK("add_bias_kernel");
         }
@@ -1120,15 +1129,11 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
         // rotations that are a full turn are plain additions; the others are grouped: the accumulators of a
         // group are decomposed, then one pass sums their switched forms over the extended basis; one ModDown
         // per block follows
-        std::vector<u32> ps;
         for (u32 p = 1; p < N2; ++p) {
-            if (giant_g[p] != 1) {
-                ps.push_back(p);
-                continue;
-            }
+            if (giant_g[p] != 1) continue;
             for (u32 b = 0; b < B; ++b) {
                 hipLaunchKernelGGL(add_rows_kernel, dim3(N / EW_THREADS, 2 * level), dim3(EW_THREADS), 0, stream,
-                                   d_ct_y + (size_t)b * ctw, d_acc + ((size_t)b * N2 + p) * ctw, P->d_mod, level, N);
+                                   y_base + (size_t)b * y_stride, d_acc + ((size_t)b * N2 + p) * ctw, P->d_mod, level, N);
                 CKKS_LAUNCH_CHECK("add_rows_kernel");
             }
         }
@@ -1159,11 +1164,12 @@ int ckks_ctpt_matmul(ckks_params_t *P, const ckks_weights_t *w, const uint64_t *
                     rots.c0_off[i] = (size_t)p * ctw;
                 }
                 rc = switch_accumulate_merged(P, level, rots, nb, d_mdig, d_acc + (size_t)b0 * N2 * ctw,
-                                              (size_t)N2 * ctw, d_ct_y + (size_t)b0 * ctw, ctw, u_b, i0 > 0, stream);
+                                              (size_t)N2 * ctw, y_base + (size_t)b0 * y_stride, y_stride, u_b, i0 > 0,
+                                              stream);
                 if (rc) return rc;
             }
             u64 *dsts[ROT_BATCH];
-            for (u32 r = 0; r < nb; ++r) dsts[r] = d_ct_y + (size_t)(b0 + r) * ctw;
+            for (u32 r = 0; r < nb; ++r) dsts[r] = y_base + (size_t)(b0 + r) * y_stride;
             any_giant = true;
             if (fused_rescale) {
                 u64 *outs[ROT_BATCH];
