@@ -124,13 +124,16 @@ def test_full_size_projection_bit_exact(spec, merged, pairs, which):
     assert np.abs(slots.imag).max() <= 1e-3
 
 
-@pytest.mark.parametrize("merged,level", [(False, 9), (True, 24)], ids=["default_level_9", "merged_giant_level_24"])
+@pytest.mark.parametrize("merged,level", [(False, 9), (True, 24), (True, 9)],
+                         ids=["default_level_9", "merged_giant_level_24", "merged_giant_level_9"])
 def test_gpt2_ffn_down_width_one_block_bit_exact(merged, level):
     """Full ring, the input width of the GPT-2 FFN-down layer (d_in = 3072: twelve input ciphertexts, so the
     baby-step batches hold one step of all inputs each; N1 = 8, so the giant step has 31 rotations, four
     groups of the merged form), one output block of 256 columns, every residue of it against the oracle: at
     level 24 with the merged giant step, as the benchmark runs the layer, and at level 9 of 24 (two digits, the
-    second with a single limb: a partial last digit at N = 2^16) with one key switch per giant rotation."""
+    second with a single limb: a partial last digit at N = 2^16) with one key switch per giant rotation and with the
+    merged giant step.  Each case also with the rescale inside the call (at level 9 with the merged giant step: ModDown
+    and rescale in one pass below the full level): the same residues."""
     from paper_2604_09975_amd import binding as B
     t0 = time.time()
     spec = W.GPT2_LAYERS[3]
@@ -154,7 +157,10 @@ def test_gpt2_ffn_down_width_one_block_bit_exact(merged, level):
     y_dev, cnt = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h,
                                     flags=B.MATMUL_MERGED_GIANT if merged else 0)
     y_res = B.ckks_rescale(P, y_dev, level, B_out)
+    y_fused, _ = B.ckks_ctpt_matmul(P, w, to_dev(ct_x), baby_h, giant_h,
+                                    flags=(B.MATMUL_MERGED_GIANT if merged else 0) | B.MATMUL_RESCALE)
     torch.cuda.synchronize()
+    assert torch.equal(y_fused, y_res)
     assert cnt.key_switches == G * (N1 - 1) + B_out * (N2 - 1)
     want = O.ctpt_matmul(level, m, G, B_out, N1, N2, diag, bias_c, int(scale), ct_x, baby_np, giant_np,
                          merged=merged)
