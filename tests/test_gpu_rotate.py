@@ -101,6 +101,15 @@ def test_full_size_hoisted_batch():
         assert np.abs(zz - want).max() < 585 * O.N / 2.0**40
 
 
+@pytest.mark.parametrize("level", [1, 7, 8, 9, 16, 17, 23])
+def test_full_ring_lower_levels(level):
+    """N = 2^16 below the full level: one limb, a partial first digit, exactly one digit, one digit and one limb,
+    two digits, two and one limb, all but the last limb: the kernels that run the base conversions between the
+    column passes see every digit shape."""
+    O, P = make_pair(W.BIG_RING)
+    _run(O, P, level, [1, 300, "conj"], 900 + level, 2.0**40)
+
+
 def test_rotate_errors():
     B = _B()
     O, P = make_pair(W.TOY_RING)
